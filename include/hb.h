@@ -1,0 +1,166 @@
+/*
+ * hb.h -- C ABI of the MI355X (gfx950) Hogbatch GPU-worker mini-batch step.
+ *
+ * The library implements the body of the GPU worker's ExecuteWork handler of the paper
+ * "Heterogeneous CPU+GPU Stochastic Gradient Descent Algorithms" (Ma & Rusu, 2020):
+ * Algorithm 1 / Algorithm 2, worker side -- "Gradient" then "Update model" -- for a
+ * fully-connected network, on a device-resident deep copy of the model (Section 5.1, GPU
+ * workers; Section 6.2), at whatever batch size the coordinator assigns (Algorithm 2
+ * rescales it by a user-set factor on every request, so B is arbitrary and changes from
+ * call to call), plus the replica <-> global-model exchange of Section 6.2.
+ *
+ * Conventions
+ *   layer_dims = [d_0, d_1, ..., d_L], n_dims = L + 1 >= 2.
+ *   W_l is d_l x d_{l-1}, row-major (out x in: the orientation of Section 3, W^l in
+ *   R^{d_{l+1} x d_l}); b_l has d_l entries.
+ *   Flat parameter / gradient layout, fp32, P = sum_l (d_l d_{l-1} + d_l) elements:
+ *       [W_1, b_1, W_2, b_2, ..., W_L, b_L].
+ *   X is B x d_0 row-major (one example per row, Section 3), a DEVICE pointer: fp32 in
+ *   HB_F32 mode, bfloat16 in HB_BF16_F32MASTER mode.
+ *   y is a DEVICE pointer to B int32 labels: class index in [0, d_L) for
+ *   HB_LOSS_SOFTMAX_CE; -1 / +1 for HB_LOSS_LOGISTIC (d_L = 1: loss on the margin
+ *   y * z; d_L = 2: two-way softmax with class (y + 1) / 2).  Labels are not range-checked;
+ *   an out-of-range label cannot cause an out-of-bounds access, only a wrong loss.
+ *   The batch gradient is the MEAN over the batch of the per-example gradients; the
+ *   loss a step returns is the mean batch loss at the weights before the update.
+ *
+ * Ownership: the handle owns every device buffer it uses (replica, gradient partials,
+ * activations sized for max_B).  The caller owns X, y, the CSR arrays, gradient output
+ * buffers and the host model; nothing of the caller's is retained after a call returns,
+ * except that *_async calls read their inputs until the stream reaches that point.
+ *
+ * Threading: one handle is driven by one thread at a time (the GPU worker is the
+ * exclusive interface of its device, Section 5.1).  hb_model_merge reads and writes the
+ * host model without any atomicity with respect to other host threads (Hogbatch updates
+ * the shared model without synchronisation, Section 6.1).
+ *
+ * Errors: int-returning calls give HB_OK or a negative code; float-returning calls give
+ * a quiet NaN on error; hb_mlp_create gives NULL.  hb_last_error() then describes the
+ * failure.  Every argument check happens before any device call.
+ */
+#ifndef HB_H
+#define HB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hb_model hb_model;
+
+enum { HB_ACT_SIGMOID = 0, HB_ACT_RELU = 1 };
+enum { HB_LOSS_SOFTMAX_CE = 0, HB_LOSS_LOGISTIC = 1 };
+enum { HB_F32 = 0, HB_BF16_F32MASTER = 1 };
+enum {
+    HB_OK = 0,
+    HB_ERR_INVALID = -1,     /* bad argument */
+    HB_ERR_ALLOC = -2,       /* host or device allocation failed */
+    HB_ERR_DEVICE = -3,      /* a HIP call failed */
+    HB_ERR_UNSUPPORTED = -4, /* valid request this build does not implement */
+    HB_ERR_STATE = -5        /* call made in the wrong state (e.g. step before configure) */
+};
+
+/*
+ * Describe the network (Section 5.2, initialisation: the model configuration is passed to
+ * the GPU worker).  Host-only: touches no device.  activation applies to the hidden layers
+ * (sigmoid per Section 7.1, or ReLU); loss is softmax cross-entropy (Section 7.1) or
+ * logistic (needs d_L <= 2).  layer_dims is a HOST pointer, copied.  NULL on error.
+ */
+hb_model *hb_mlp_create(const int32_t *layer_dims, int32_t n_dims, int activation, int loss);
+
+/*
+ * Allocate the device replica and the workspace for batches of up to max_B rows (Section
+ * 5.2: "GPU workers ... have to allocate memory on the device").  dtype: HB_F32 or
+ * HB_BF16_F32MASTER (bf16 weights/activations, fp32 master weights and accumulation).
+ * sparse_first_layer != 0 selects CSR input for layer 1 (then only the *_csr step calls
+ * are valid, and only HB_F32).  hip_stream is a hipStream_t (NULL = the default stream)
+ * on which every kernel and copy of this handle is issued; the device current at this
+ * call is the handle's device.  Parameters start as zeros.  May be called once.
+ */
+int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_layer,
+                     void *hip_stream);
+
+/* Free everything the handle owns.  NULL is allowed. */
+void hb_model_destroy(hb_model *m);
+
+/* P, the length of the flat parameter vector.  -1 if m is NULL. */
+int64_t hb_model_num_params(const hb_model *m);
+
+/* Replica <- host_flat (HOST pointer, P floats).  Synchronises the stream. */
+int hb_model_set_params(hb_model *m, const float *host_flat);
+
+/* host_flat <- replica (fp32 master weights).  Synchronises the stream. */
+int hb_model_get_params(hb_model *m, float *host_flat);
+
+/*
+ * One GPU-worker step (Algorithm 1, worker lines "Gradient" and "Update model"; Section 3,
+ * Eq. (1) forward, Eq. (2) backward, Eq. (3) W <- W - lr * g) on the replica, for the
+ * B rows at dX / dy (DEVICE pointers), 1 <= B <= max_B.  Returns the pre-update mean
+ * loss after synchronising the stream; NaN on error.
+ */
+float hb_batch_step(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float lr);
+
+/*
+ * Same step without any host synchronisation: the mean loss is written to *d_loss (DEVICE
+ * pointer, one float, may be NULL) when the stream reaches that point.
+ */
+int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float lr,
+                        float *d_loss);
+
+/*
+ * The step for a CSR batch (sparse first layer; the paper processes its data densely and
+ * names sparse input as future work in Section 8 -- this is the benchmark's
+ * real-sim-shaped configuration).  d_row_ptr: B + 1 int32 starting at 0; d_col_idx /
+ * d_vals: nnz entries, column indices in [0, d_0), any order within a row (DEVICE
+ * pointers).  nnz must equal d_row_ptr[B]; it is passed so that no device read is needed
+ * to size the launch.  Column indices are trusted: an index outside [0, d_0) is an
+ * out-of-bounds access.  Only the weight columns that occur in the batch are touched.
+ */
+float hb_batch_step_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                        const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,
+                        float lr);
+int hb_batch_step_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                            const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,
+                            float lr, float *d_loss);
+
+/*
+ * Gradient only (Section 6.2: the stale-replica alternative computes the gradient on the
+ * replica and lets the caller apply it to the current global model).  The replica is
+ * left untouched; d_grad_flat (DEVICE pointer, P floats, flat layout) receives the mean
+ * gradient.  Returns the mean loss after synchronising; NaN on error.
+ */
+float hb_batch_grad(hb_model *m, const void *dX, const int32_t *dy, int64_t B,
+                    float *d_grad_flat);
+float hb_batch_grad_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                        const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,
+                        float *d_grad_flat);
+
+/*
+ * Forward pass and mean loss only, no gradient, no update (Section 5.2: the loss is
+ * evaluated with a forward pass over batches that fit the worker's memory).
+ */
+float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B);
+
+/*
+ * Replica <-> global model exchange (Section 6.2: the replica is a deep copy of the
+ * global model, pushed back to it after the update; a stale replica's contribution can be
+ * damped).  With H = host_model (HOST pointer, P floats, flat layout; pinned memory makes
+ * the copies asynchronous) and D = the device replica:
+ *     M = (1 - weight) * H + weight * D,   then   H <- M and D <- M.
+ * weight = 0: replica <- global (the deep copy on ExecuteWork); weight = 1: global <-
+ * replica (the push); 0 < weight < 1: damped push.  weight outside [0, 1] or NaN is
+ * HB_ERR_INVALID.  Synchronises the stream before returning.
+ */
+int hb_model_merge(hb_model *device_replica, float *host_model, float weight);
+
+/* Message for the last failing call on this thread ("" if none). */
+const char *hb_last_error(void);
+
+/* Library version string, e.g. for logs. */
+const char *hb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HB_H */

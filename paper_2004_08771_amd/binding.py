@@ -1,0 +1,158 @@
+"""ctypes binding of libhb.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhb.so")
+
+HB_ACT_SIGMOID, HB_ACT_RELU = 0, 1
+HB_LOSS_SOFTMAX_CE, HB_LOSS_LOGISTIC = 0, 1
+HB_F32, HB_BF16_F32MASTER = 0, 1
+HB_OK, HB_ERR_INVALID, HB_ERR_ALLOC, HB_ERR_DEVICE, HB_ERR_UNSUPPORTED, HB_ERR_STATE = 0, -1, -2, -3, -4, -5
+
+# name -> (restype, argtypes); every symbol include/hb.h declares
+_vp, _i32, _i64, _f32, _int = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_int
+_i32p = ctypes.POINTER(ctypes.c_int32)
+SIGNATURES = {
+    "hb_mlp_create": (_vp, [_i32p, _i32, _int, _int]),
+    "hb_mlp_configure": (_int, [_vp, _int, _i64, _int, _vp]),
+    "hb_model_destroy": (None, [_vp]),
+    "hb_model_num_params": (_i64, [_vp]),
+    "hb_model_set_params": (_int, [_vp, _vp]),
+    "hb_model_get_params": (_int, [_vp, _vp]),
+    "hb_batch_step": (_f32, [_vp, _vp, _vp, _i64, _f32]),
+    "hb_batch_step_async": (_int, [_vp, _vp, _vp, _i64, _f32, _vp]),
+    "hb_batch_step_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _f32]),
+    "hb_batch_step_csr_async": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _f32, _vp]),
+    "hb_batch_grad": (_f32, [_vp, _vp, _vp, _i64, _vp]),
+    "hb_batch_grad_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "hb_batch_loss": (_f32, [_vp, _vp, _vp, _i64]),
+    "hb_model_merge": (_int, [_vp, _vp, _f32]),
+    "hb_last_error": (ctypes.c_char_p, []),
+    "hb_version": (ctypes.c_char_p, []),
+}
+
+_lib = None
+
+
+class HbError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"hb error {code}: {message}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; "
+                              "g.build()'` (or paper_2004_08771_amd/build.py) first")
+        l = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def last_error() -> str:
+    return lib().hb_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != HB_OK:
+        raise HbError(rc, last_error())
+
+
+def _ptr(t):
+    """Device/host address of a torch tensor, numpy array, int or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+class Model:
+    """Owner of one hb_model handle.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, layer_dims, activation=HB_ACT_SIGMOID, loss=HB_LOSS_SOFTMAX_CE):
+        dims = (ctypes.c_int32 * len(layer_dims))(*[int(d) for d in layer_dims])
+        self._h = lib().hb_mlp_create(dims, len(layer_dims), int(activation), int(loss))
+        if not self._h:
+            raise HbError(HB_ERR_INVALID, last_error())
+        self.layer_dims = tuple(int(d) for d in layer_dims)
+
+    def configure(self, dtype=HB_F32, max_B=4096, sparse_first_layer=False, stream=None):
+        """stream: a hipStream_t as int (e.g. torch.cuda.current_stream().cuda_stream) or None."""
+        _check(lib().hb_mlp_configure(self._h, int(dtype), int(max_B), int(bool(sparse_first_layer)),
+                                      stream if stream else None))
+        return self
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().hb_model_destroy(self._h)
+            self._h = None
+
+    __del__ = destroy
+
+    @property
+    def num_params(self) -> int:
+        return int(lib().hb_model_num_params(self._h))
+
+    def set_params(self, host_flat):
+        _check(lib().hb_model_set_params(self._h, _ptr(host_flat)))
+
+    def get_params(self, host_flat):
+        _check(lib().hb_model_get_params(self._h, _ptr(host_flat)))
+
+    def batch_step(self, dX, dy, B, lr) -> float:
+        v = lib().hb_batch_step(self._h, _ptr(dX), _ptr(dy), int(B), float(lr))
+        if v != v:
+            raise HbError(HB_ERR_INVALID, last_error())
+        return v
+
+    def batch_step_async(self, dX, dy, B, lr, d_loss=None):
+        _check(lib().hb_batch_step_async(self._h, _ptr(dX), _ptr(dy), int(B), float(lr), _ptr(d_loss)))
+
+    def batch_step_csr(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr) -> float:
+        v = lib().hb_batch_step_csr(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals), int(nnz),
+                                    _ptr(dy), int(B), float(lr))
+        if v != v:
+            raise HbError(HB_ERR_INVALID, last_error())
+        return v
+
+    def batch_step_csr_async(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr, d_loss=None):
+        _check(lib().hb_batch_step_csr_async(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals),
+                                             int(nnz), _ptr(dy), int(B), float(lr), _ptr(d_loss)))
+
+    def batch_grad(self, dX, dy, B, d_grad_flat) -> float:
+        v = lib().hb_batch_grad(self._h, _ptr(dX), _ptr(dy), int(B), _ptr(d_grad_flat))
+        if v != v:
+            raise HbError(HB_ERR_INVALID, last_error())
+        return v
+
+    def batch_grad_csr(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, d_grad_flat) -> float:
+        v = lib().hb_batch_grad_csr(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals), int(nnz),
+                                    _ptr(dy), int(B), _ptr(d_grad_flat))
+        if v != v:
+            raise HbError(HB_ERR_INVALID, last_error())
+        return v
+
+    def batch_loss(self, dX, dy, B) -> float:
+        v = lib().hb_batch_loss(self._h, _ptr(dX), _ptr(dy), int(B))
+        if v != v:
+            raise HbError(HB_ERR_INVALID, last_error())
+        return v
+
+    def model_merge(self, host_model, weight):
+        _check(lib().hb_model_merge(self._h, _ptr(host_model), float(weight)))

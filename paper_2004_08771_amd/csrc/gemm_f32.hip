@@ -1,0 +1,330 @@
+// fp32 MFMA GEMM for the three dense layer products of the mini-batch step
+// (Section 3 of the paper: forward Eq. (1), backward Eq. (2); on a batch the
+// matrix-vector products become matrix-matrix products, the dominant cost).
+//
+// gfx950 design: 256-thread workgroups (4 wavefronts of 64), v_mfma_f32_32x32x2_f32
+// blocks, operands staged global -> registers -> LDS with a double-buffered LDS tile so
+// that the next tile's global loads are in flight while the current one is multiplied.
+// K-major operands are read from LDS as 16-byte vectors along k (the k index is permuted
+// identically for both operands, which leaves the contraction unchanged); M-major
+// operands are read one float per lane with the 32 rows of a block on consecutive
+// addresses.  Epilogues fuse bias + activation (forward), the activation derivative
+// (backward-data) and the bias-gradient column sums (weight gradient).
+#include "hb_internal.h"
+
+#include <stdlib.h>
+
+namespace hb {
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int NT = 256;  // threads per workgroup
+
+template <int ROWS, int BK, bool KMAJ>
+struct Tile {
+    static_assert(ROWS % 32 == 0 && BK % 8 == 0, "tile shape");
+    static constexpr int LD = KMAJ ? (BK + 4) : (ROWS + 8);
+    static constexpr int FLOATS = KMAJ ? ROWS * LD : BK * LD;
+    static constexpr int VECS = ROWS * BK / 4;
+    static constexpr int VPT = (VECS + NT - 1) / NT;
+
+    // global -> registers; everything outside [0,nrows) x [.., kend) reads as zero
+    static __device__ __forceinline__ void load(v4f (&reg)[VPT], const float *__restrict__ P,
+                                                int ld, int row0, int nrows, int k0, int kend,
+                                                bool vec, int tid)
+    {
+#pragma unroll
+        for (int v = 0; v < VPT; ++v) {
+            const int idx = tid + v * NT;
+            v4f x = {0.f, 0.f, 0.f, 0.f};
+            if (VECS % NT == 0 || idx < VECS) {
+                if (KMAJ) {
+                    const int kq = idx % (BK / 4), r = idx / (BK / 4);
+                    const int row = row0 + r, k = k0 + kq * 4;
+                    if (row < nrows && k < kend) {
+                        const float *p = P + (size_t)row * ld + k;
+                        if (vec && k + 4 <= kend) {
+                            x = *reinterpret_cast<const v4f *>(p);
+                        } else {
+                            x.x = p[0];
+                            if (k + 1 < kend) x.y = p[1];
+                            if (k + 2 < kend) x.z = p[2];
+                            if (k + 3 < kend) x.w = p[3];
+                        }
+                    }
+                } else {
+                    const int mq = idx % (ROWS / 4), kk = idx / (ROWS / 4);
+                    const int row = row0 + mq * 4, k = k0 + kk;
+                    if (k < kend && row < nrows) {
+                        const float *p = P + (size_t)k * ld + row;
+                        if (vec && row + 4 <= nrows) {
+                            x = *reinterpret_cast<const v4f *>(p);
+                        } else {
+                            x.x = p[0];
+                            if (row + 1 < nrows) x.y = p[1];
+                            if (row + 2 < nrows) x.z = p[2];
+                            if (row + 3 < nrows) x.w = p[3];
+                        }
+                    }
+                }
+            }
+            reg[v] = x;
+        }
+    }
+
+    // registers -> LDS (same element <-> thread mapping as load)
+    static __device__ __forceinline__ void store(float *S, const v4f (&reg)[VPT], int tid)
+    {
+#pragma unroll
+        for (int v = 0; v < VPT; ++v) {
+            const int idx = tid + v * NT;
+            if (VECS % NT == 0 || idx < VECS) {
+                if (KMAJ) {
+                    const int kq = idx % (BK / 4), r = idx / (BK / 4);
+                    *reinterpret_cast<v4f *>(&S[r * LD + kq * 4]) = reg[v];
+                } else {
+                    const int mq = idx % (ROWS / 4), kk = idx / (ROWS / 4);
+                    *reinterpret_cast<v4f *>(&S[kk * LD + mq * 4]) = reg[v];
+                }
+            }
+        }
+    }
+
+    // The four operand values of tile row `row` for the MFMA steps of k-group g:
+    // f[j] = element(row, k = 8 g + 4 h + j), h = lane / 32.
+    static __device__ __forceinline__ v4f frag(const float *S, int row, int g, int h)
+    {
+        if (KMAJ) {
+            return *reinterpret_cast<const v4f *>(&S[row * LD + g * 8 + h * 4]);
+        } else {
+            const float *p = &S[(g * 8 + h * 4) * LD + row];
+            v4f f;
+            f.x = p[0];
+            f.y = p[LD];
+            f.z = p[2 * LD];
+            f.w = p[3 * LD];
+            return f;
+        }
+    }
+};
+
+__device__ __forceinline__ float sigmoidf_fast(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+template <int BM, int BN, int BK, int WAVES_M, bool A_KMAJ, bool B_KMAJ, int KIND>
+__global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
+{
+    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    static_assert(TM >= 1 && TN >= 1 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    using TA = Tile<BM, BK, A_KMAJ>;
+    using TB = Tile<BN, BK, B_KMAJ>;
+    constexpr int STAGE = TA::FLOATS + TB::FLOATS;
+    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+
+    // XCD-aware tile order: consecutive hardware workgroup ids go round-robin over the 8
+    // XCDs, so give each XCD a contiguous run of tiles (they share an A row panel in L2).
+    int id = blockIdx.x;
+    const int T = gridDim.x;
+    if ((T & 7) == 0) id = (id & 7) * (T >> 3) + (id >> 3);
+    const int tile_m = id / a.tiles_n, tile_n = id - tile_m * a.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int split = blockIdx.y;
+    const int kbeg = split * a.k_chunk;
+    const int kend = min(a.K, kbeg + a.k_chunk);
+    const int nk = (kend - kbeg + BK - 1) / BK;
+
+    const float *__restrict__ A = static_cast<const float *>(a.A);
+    const float *__restrict__ Bm = static_cast<const float *>(a.B);
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    float colsum = 0.f;  // DW only: column sums of the A tile (bias gradient)
+    const bool do_colsum = (KIND == GEMM_DW) && a.colsum != nullptr && tile_n == 0;
+
+    v4f ra[TA::VPT], rb[TB::VPT];
+    if (nk > 0) {
+        TA::load(ra, A, a.lda, m0, a.M, kbeg, kend, a.a_vec != 0, tid);
+        TB::load(rb, Bm, a.ldb, n0, a.N, kbeg, kend, a.b_vec != 0, tid);
+        TA::store(smem, ra, tid);
+        TB::store(smem + TA::FLOATS, rb, tid);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const float *As = smem + (kt & 1) * STAGE;
+        const float *Bs = As + TA::FLOATS;
+        const bool more = (kt + 1 < nk);
+        if (more) {
+            const int k0 = kbeg + (kt + 1) * BK;
+            TA::load(ra, A, a.lda, m0, a.M, k0, kend, a.a_vec != 0, tid);
+            TB::load(rb, Bm, a.ldb, n0, a.N, k0, kend, a.b_vec != 0, tid);
+        }
+#pragma unroll
+        for (int g = 0; g < BK / 8; ++g) {
+            v4f fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = TA::frag(As, wm * WM + i * 32 + r, g, h);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = TB::frag(Bs, wn * WN + j * 32 + r, g, h);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][s], fb[j][s],
+                                                                         acc[i][j], 0, 0, 0);
+        }
+        if (KIND == GEMM_DW && !A_KMAJ) {
+            if (do_colsum && tid < BM) {
+#pragma unroll
+                for (int k = 0; k < BK; ++k) colsum += As[k * TA::LD + tid];
+            }
+        }
+        if (more) {
+            float *An = smem + ((kt + 1) & 1) * STAGE;
+            TA::store(An, ra, tid);
+            TB::store(An + TA::FLOATS, rb, tid);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue.  acc[i][j][v] is C(row, col) with
+    //      row = 8 (v / 4) + 4 h + (v % 4), col = r   inside its 32 x 32 block.
+    float *__restrict__ C = static_cast<float *>(a.C) + (size_t)split * a.c_split_stride;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + r;
+        const bool n_ok = n < a.N;
+        float bias = 0.f;
+        if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (m < a.M && n_ok) {
+                    float x = acc[i][j][v];
+                    if (KIND == GEMM_FWD) {
+                        x += bias;
+                        if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
+                        else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
+                    } else if (KIND == GEMM_DA) {
+                        const float o = static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
+                        if (a.act == ACT_SIGMOID) x *= o * (1.f - o);
+                        else if (a.act == ACT_RELU) x = (o > 0.f) ? x : 0.f;
+                    }
+                    C[(size_t)m * a.ldc + n] = x;
+                }
+            }
+        }
+    }
+    if (KIND == GEMM_DW) {
+        if (do_colsum && tid < BM && m0 + tid < a.M)
+            a.colsum[(size_t)split * a.M + m0 + tid] = colsum;
+    }
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    return (s && *s) ? atoi(s) : dflt;
+}
+
+// Workgroups wanted per launch: two per compute unit on a 256-CU device.
+constexpr int TARGET_WGS = 512;
+
+struct Shape {
+    int bm, bn;
+};
+
+Shape pick_shape(GemmKind kind, int M, int N)
+{
+    static const int forced = env_int("HB_GEMM_TILE", 0);  // 1: 128x64, 2: 64x64 (tuning aid)
+    if (forced == 1) return {128, 64};
+    if (forced == 2) return {64, 64};
+    (void)kind;
+    const long long t128 = (long long)((M + 127) / 128) * ((N + 63) / 64);
+    if (t128 >= 2 * TARGET_WGS) return {128, 64};
+    return {64, 64};
+}
+
+constexpr int BK_F32 = 16;
+
+template <int BM, int BN, int WAVES_M>
+hipError_t launch_shape(GemmKind kind, const GemmArgs &a, dim3 grid, hipStream_t stream)
+{
+    switch (kind) {
+    case GEMM_FWD:
+        gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, true, GEMM_FWD><<<grid, NT, 0, stream>>>(a);
+        break;
+    case GEMM_DA:
+        gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, false, GEMM_DA><<<grid, NT, 0, stream>>>(a);
+        break;
+    case GEMM_DW:
+        gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, false, false, GEMM_DW><<<grid, NT, 0, stream>>>(a);
+        break;
+    }
+    return hipGetLastError();
+}
+
+struct SplitPlan {
+    int splits, chunk;
+};
+
+// Split-K plan for the weight-gradient product (its contraction runs over the batch):
+// enough slices to fill the device, each a multiple of BK long, none empty.
+SplitPlan plan_splits(int tiles, int K, int max_splits)
+{
+    int s = (TARGET_WGS + tiles - 1) / tiles;
+    const int by_k = (K + 4 * BK_F32 - 1) / (4 * BK_F32);  // at least 4 k-tiles per slice
+    if (s > by_k) s = by_k;
+    if (s > max_splits) s = max_splits;
+    if (s < 1) s = 1;
+    const int chunk = ((K + s - 1) / s + BK_F32 - 1) / BK_F32 * BK_F32;
+    return {(K + chunk - 1) / chunk, chunk};
+}
+
+}  // namespace
+
+int gemm_f32_dw_splits(int M, int N, int K, int max_splits)
+{
+    const Shape sh = pick_shape(GEMM_DW, M, N);
+    const int tiles = ((M + sh.bm - 1) / sh.bm) * ((N + sh.bn - 1) / sh.bn);
+    return plan_splits(tiles, K, max_splits).splits;
+}
+
+hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *splits_out,
+                           hipStream_t stream)
+{
+    if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
+    const Shape sh = pick_shape(kind, a.M, a.N);
+    a.tiles_m = (a.M + sh.bm - 1) / sh.bm;
+    a.tiles_n = (a.N + sh.bn - 1) / sh.bn;
+    const long long tiles = (long long)a.tiles_m * a.tiles_n;
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    SplitPlan sp = {1, (a.K + BK_F32 - 1) / BK_F32 * BK_F32};
+    if (kind == GEMM_DW) sp = plan_splits((int)tiles, a.K, max_splits);
+    a.splits = sp.splits;
+    a.k_chunk = sp.chunk;
+    if (splits_out) *splits_out = sp.splits;
+    const dim3 grid((unsigned)tiles, (unsigned)sp.splits, 1);
+    if (sh.bm == 128) return launch_shape<128, 64, 2>(kind, a, grid, stream);
+    return launch_shape<64, 64, 2>(kind, a, grid, stream);
+}
+
+}  // namespace hb

@@ -1,0 +1,491 @@
+// C ABI of libhb (see include/hb.h): handle, argument validation, and the order in which
+// the kernels of one GPU-worker mini-batch step are issued on the handle's stream
+// (Algorithm 1 / Algorithm 2 of the paper, worker side: "Gradient", then "Update model").
+#include "../../include/hb.h"
+#include "hb_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <vector>
+
+using namespace hb;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+float fail_nan(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return std::numeric_limits<float>::quiet_NaN();
+}
+
+#define HB_HIP(call)                                                                        \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(HB_ERR_DEVICE, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), \
+                        __FILE__, __LINE__);                                                \
+    } while (0)
+
+constexpr int MAX_LAYERS = 16;       // weight layers; 2 * MAX_LAYERS <= HB_MAX_SEGS
+constexpr int MAX_SPLITS = 64;
+constexpr int64_t MAX_BATCH = 1 << 22;
+constexpr int64_t MAX_DIM = 1 << 24;
+
+int round_up(int x, int m) { return (x + m - 1) / m * m; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+enum StepMode { MODE_STEP = 0, MODE_GRAD = 1, MODE_LOSS = 2 };
+
+}  // namespace
+
+struct hb_model {
+    std::vector<int> dims;  // d_0 .. d_L
+    int L = 0;
+    int act = 0, loss = 0;
+    int64_t P = 0;
+    std::vector<int64_t> w_off, b_off;  // [1..L] offsets in the flat layout
+
+    bool configured = false;
+    int dtype = HB_F32;
+    int64_t max_B = 0;
+    bool sparse = false;
+    hipStream_t stream = nullptr;
+    int device = -1;
+
+    float *d_params = nullptr;           // flat layout, fp32 (master) weights
+    std::vector<int> ld;                 // leading dimension of the activation of layer l
+    std::vector<float *> acts;           // [1..L]: max_B x ld[l]
+    float *delta[2] = {nullptr, nullptr};
+    std::vector<float *> partial_w, partial_b;  // [1..L] split-K gradient partials
+    std::vector<int> cap_splits;
+    float *d_loss_partials = nullptr;
+    unsigned int *d_counter = nullptr;
+    float *d_loss = nullptr;
+    float *h_loss = nullptr;             // pinned
+    float *d_stage = nullptr;            // P floats: staging copy of the host model
+    std::vector<void *> owned;           // every device allocation, for destroy
+};
+
+namespace {
+
+template <typename T>
+int dev_alloc(hb_model *m, T **out, size_t count)
+{
+    void *p = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(T);
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess)
+        return fail(HB_ERR_ALLOC, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    m->owned.push_back(p);
+    *out = static_cast<T *>(p);
+    return HB_OK;
+}
+
+void release_device(hb_model *m)
+{
+    for (void *p : m->owned) (void)hipFree(p);
+    m->owned.clear();
+    if (m->h_loss) (void)hipHostFree(m->h_loss);
+    m->h_loss = nullptr;
+}
+
+int check_handle(const hb_model *m, bool need_configured)
+{
+    if (!m) return fail(HB_ERR_INVALID, "model handle is NULL");
+    if (need_configured && !m->configured)
+        return fail(HB_ERR_STATE, "hb_mlp_configure has not been called on this model");
+    return HB_OK;
+}
+
+// Issues the kernels of one step.  X is dense B x d_0 fp32.
+int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr, StepMode mode,
+              float *d_grad_flat, float *d_loss_user)
+{
+    const int L = m->L;
+    const int Bi = (int)B;
+    hipStream_t st = m->stream;
+
+    // ---- forward, Eq. (1): A_l = f(A_{l-1} W_l^T + b_l); the last layer keeps raw scores
+    for (int l = 1; l <= L; ++l) {
+        GemmArgs g = {};
+        g.A = (l == 1) ? X : m->acts[l - 1];
+        g.lda = (l == 1) ? m->dims[0] : m->ld[l - 1];
+        g.B = m->d_params + m->w_off[l];
+        g.ldb = m->dims[l - 1];
+        g.C = m->acts[l];
+        g.ldc = m->ld[l];
+        g.M = Bi;
+        g.N = m->dims[l];
+        g.K = m->dims[l - 1];
+        g.a_vec = aligned16(g.A) && (g.lda % 4 == 0);
+        g.b_vec = aligned16(g.B) && (g.ldb % 4 == 0);
+        g.bias = m->d_params + m->b_off[l];
+        g.act = (l < L) ? m->act : ACT_NONE;
+        HB_HIP(launch_gemm_f32(GEMM_FWD, g, 1, nullptr, st));
+    }
+
+    // ---- loss and output delta (Section 7.1)
+    LossArgs la = {};
+    la.Z = m->acts[L];
+    la.ldz = m->ld[L];
+    la.y = y;
+    la.B = B;
+    la.K = m->dims[L];
+    la.loss = m->loss;
+    la.delta = (mode == MODE_LOSS) ? nullptr : m->delta[L & 1];
+    la.ldd = m->ld[L];
+    la.delta_bf16 = 0;
+    la.block_partials = m->d_loss_partials;
+    la.counter = m->d_counter;
+    la.loss_out = m->d_loss;
+    la.loss_out2 = d_loss_user;
+    HB_HIP(launch_loss(la, st));
+    if (mode == MODE_LOSS) return HB_OK;
+
+    // ---- backward, Eq. (2), with the weights the forward pass used
+    UpdateArgs ua = {};
+    ua.lr = lr;
+    ua.write_grad = (mode == MODE_GRAD) ? 1 : 0;
+    for (int l = L; l >= 1; --l) {
+        const float *delta_l = m->delta[l & 1];
+        if (l > 1) {
+            GemmArgs g = {};
+            g.A = delta_l;
+            g.lda = m->ld[l];
+            g.B = m->d_params + m->w_off[l];
+            g.ldb = m->dims[l - 1];
+            g.C = m->delta[(l - 1) & 1];
+            g.ldc = m->ld[l - 1];
+            g.M = Bi;
+            g.N = m->dims[l - 1];
+            g.K = m->dims[l];
+            g.a_vec = aligned16(g.A) && (g.lda % 4 == 0);
+            g.b_vec = aligned16(g.B) && (g.ldb % 4 == 0);
+            g.aux = m->acts[l - 1];
+            g.ldaux = m->ld[l - 1];
+            g.act = m->act;
+            HB_HIP(launch_gemm_f32(GEMM_DA, g, 1, nullptr, st));
+        }
+        GemmArgs g = {};
+        g.A = delta_l;
+        g.lda = m->ld[l];
+        g.B = (l == 1) ? X : m->acts[l - 1];
+        g.ldb = (l == 1) ? m->dims[0] : m->ld[l - 1];
+        g.C = m->partial_w[l];
+        g.ldc = m->dims[l - 1];
+        g.c_split_stride = (long long)m->dims[l] * m->dims[l - 1];
+        g.M = m->dims[l];
+        g.N = m->dims[l - 1];
+        g.K = Bi;
+        g.a_vec = aligned16(g.A) && (g.lda % 4 == 0);
+        g.b_vec = aligned16(g.B) && (g.ldb % 4 == 0);
+        g.colsum = m->partial_b[l];
+        g.act = ACT_NONE;
+        int splits = 1;
+        HB_HIP(launch_gemm_f32(GEMM_DW, g, m->cap_splits[l], &splits, st));
+
+        UpdateSeg &sw = ua.seg[ua.n_seg++];
+        sw.param = m->d_params + m->w_off[l];
+        sw.grad_out = d_grad_flat ? d_grad_flat + m->w_off[l] : nullptr;
+        sw.partial = m->partial_w[l];
+        sw.count = (long long)m->dims[l] * m->dims[l - 1];
+        sw.stride = sw.count;
+        sw.splits = splits;
+        UpdateSeg &sb = ua.seg[ua.n_seg++];
+        sb.param = m->d_params + m->b_off[l];
+        sb.grad_out = d_grad_flat ? d_grad_flat + m->b_off[l] : nullptr;
+        sb.partial = m->partial_b[l];
+        sb.count = m->dims[l];
+        sb.stride = m->dims[l];
+        sb.splits = splits;
+    }
+
+    // ---- Eq. (3): W <- W - lr g for every tensor in one launch (or the gradient itself)
+    HB_HIP(launch_update(ua, st));
+    return HB_OK;
+}
+
+int validate_batch_call(hb_model *m, const void *a, const int32_t *dy, int64_t B, bool want_sparse)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    if (m->sparse != want_sparse)
+        return fail(HB_ERR_INVALID, want_sparse
+                                        ? "CSR call on a model configured for dense input"
+                                        : "dense call on a model configured with sparse_first_layer");
+    if (!a) return fail(HB_ERR_INVALID, "input pointer is NULL");
+    if (!dy) return fail(HB_ERR_INVALID, "label pointer dy is NULL");
+    if (B < 1 || B > m->max_B)
+        return fail(HB_ERR_INVALID, "B = %lld is outside [1, max_B = %lld]", (long long)B,
+                    (long long)m->max_B);
+    return HB_OK;
+}
+
+int fetch_loss(hb_model *m, float *out)
+{
+    HB_HIP(hipMemcpyAsync(m->h_loss, m->d_loss, sizeof(float), hipMemcpyDeviceToHost, m->stream));
+    HB_HIP(hipStreamSynchronize(m->stream));
+    *out = *m->h_loss;
+    return HB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *hb_last_error(void) { return g_err; }
+const char *hb_version(void) { return "hb-mlp 0.1 (gfx950)"; }
+
+hb_model *hb_mlp_create(const int32_t *layer_dims, int32_t n_dims, int activation, int loss)
+{
+    if (!layer_dims) { fail(HB_ERR_INVALID, "layer_dims is NULL"); return nullptr; }
+    if (n_dims < 2 || n_dims > MAX_LAYERS + 1) {
+        fail(HB_ERR_INVALID, "n_dims = %d is outside [2, %d]", n_dims, MAX_LAYERS + 1);
+        return nullptr;
+    }
+    for (int i = 0; i < n_dims; ++i)
+        if (layer_dims[i] < 1 || layer_dims[i] > MAX_DIM) {
+            fail(HB_ERR_INVALID, "layer_dims[%d] = %d is outside [1, %lld]", i, layer_dims[i],
+                 (long long)MAX_DIM);
+            return nullptr;
+        }
+    if (activation != HB_ACT_SIGMOID && activation != HB_ACT_RELU) {
+        fail(HB_ERR_INVALID, "unknown activation %d", activation);
+        return nullptr;
+    }
+    if (loss != HB_LOSS_SOFTMAX_CE && loss != HB_LOSS_LOGISTIC) {
+        fail(HB_ERR_INVALID, "unknown loss %d", loss);
+        return nullptr;
+    }
+    if (loss == HB_LOSS_LOGISTIC && layer_dims[n_dims - 1] > 2) {
+        fail(HB_ERR_INVALID, "logistic loss needs d_L <= 2, got %d", layer_dims[n_dims - 1]);
+        return nullptr;
+    }
+    hb_model *m = new (std::nothrow) hb_model();
+    if (!m) { fail(HB_ERR_ALLOC, "out of host memory"); return nullptr; }
+    m->dims.assign(layer_dims, layer_dims + n_dims);
+    m->L = n_dims - 1;
+    m->act = activation;
+    m->loss = loss;
+    m->w_off.assign(n_dims, 0);
+    m->b_off.assign(n_dims, 0);
+    int64_t off = 0;
+    for (int l = 1; l <= m->L; ++l) {
+        m->w_off[l] = off;
+        off += (int64_t)m->dims[l] * m->dims[l - 1];
+        m->b_off[l] = off;
+        off += m->dims[l];
+    }
+    m->P = off;
+    g_err[0] = 0;
+    return m;
+}
+
+int64_t hb_model_num_params(const hb_model *m) { return m ? m->P : -1; }
+
+int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_layer, void *hip_stream)
+{
+    int rc = check_handle(m, false);
+    if (rc != HB_OK) return rc;
+    if (m->configured) return fail(HB_ERR_STATE, "model is already configured");
+    if (dtype != HB_F32 && dtype != HB_BF16_F32MASTER)
+        return fail(HB_ERR_INVALID, "unknown dtype %d", dtype);
+    if (max_B < 1 || max_B > MAX_BATCH)
+        return fail(HB_ERR_INVALID, "max_B = %lld is outside [1, %lld]", (long long)max_B,
+                    (long long)MAX_BATCH);
+    if (sparse_first_layer && dtype != HB_F32)
+        return fail(HB_ERR_INVALID, "sparse_first_layer needs dtype HB_F32");
+    if (dtype == HB_BF16_F32MASTER)
+        return fail(HB_ERR_UNSUPPORTED, "HB_BF16_F32MASTER is not implemented in this build");
+    if (sparse_first_layer)
+        return fail(HB_ERR_UNSUPPORTED, "sparse_first_layer is not implemented in this build");
+
+    int dev = -1;
+    HB_HIP(hipGetDevice(&dev));
+    m->device = dev;
+    m->dtype = dtype;
+    m->max_B = max_B;
+    m->sparse = sparse_first_layer != 0;
+    m->stream = static_cast<hipStream_t>(hip_stream);
+
+    const int L = m->L;
+    m->ld.assign(L + 1, 0);
+    m->acts.assign(L + 1, nullptr);
+    m->partial_w.assign(L + 1, nullptr);
+    m->partial_b.assign(L + 1, nullptr);
+    m->cap_splits.assign(L + 1, 1);
+    int max_ld = 4;
+    for (int l = 0; l <= L; ++l) {
+        m->ld[l] = round_up(m->dims[l], 4);
+        if (l >= 1 && m->ld[l] > max_ld) max_ld = m->ld[l];
+    }
+    m->ld[0] = m->dims[0];  // X is the caller's, unpadded
+
+    rc = dev_alloc(m, &m->d_params, (size_t)m->P);
+    if (rc == HB_OK) rc = dev_alloc(m, &m->d_stage, (size_t)m->P);
+    for (int l = 1; l <= L && rc == HB_OK; ++l) {
+        rc = dev_alloc(m, &m->acts[l], (size_t)max_B * m->ld[l]);
+        if (rc != HB_OK) break;
+        m->cap_splits[l] = gemm_f32_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, MAX_SPLITS);
+        rc = dev_alloc(m, &m->partial_w[l], (size_t)m->cap_splits[l] * m->dims[l] * m->dims[l - 1]);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
+    }
+    for (int i = 0; i < 2 && rc == HB_OK; ++i) rc = dev_alloc(m, &m->delta[i], (size_t)max_B * max_ld);
+    if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss_partials, (size_t)loss_grid_blocks(max_B, m->dims[L]) + 1);
+    if (rc == HB_OK) rc = dev_alloc(m, &m->d_counter, 4);
+    if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss, 4);
+    if (rc != HB_OK) { release_device(m); return rc; }
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&m->h_loss), 64, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        release_device(m);
+        return fail(HB_ERR_ALLOC, "hipHostMalloc failed: %s", hipGetErrorString(e));
+    }
+    e = hipMemsetAsync(m->d_params, 0, sizeof(float) * (size_t)m->P, m->stream);
+    if (e == hipSuccess) e = launch_fill_u32(m->d_counter, 4, 0u, m->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
+    if (e != hipSuccess) {
+        release_device(m);
+        return fail(HB_ERR_DEVICE, "initialising device buffers failed: %s", hipGetErrorString(e));
+    }
+    m->configured = true;
+    g_err[0] = 0;
+    return HB_OK;
+}
+
+void hb_model_destroy(hb_model *m)
+{
+    if (!m) return;
+    if (m->configured) (void)hipStreamSynchronize(m->stream);
+    release_device(m);
+    delete m;
+}
+
+int hb_model_set_params(hb_model *m, const float *host_flat)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    if (!host_flat) return fail(HB_ERR_INVALID, "host_flat is NULL");
+    HB_HIP(hipMemcpyAsync(m->d_params, host_flat, sizeof(float) * (size_t)m->P, hipMemcpyHostToDevice,
+                          m->stream));
+    HB_HIP(hipStreamSynchronize(m->stream));
+    return HB_OK;
+}
+
+int hb_model_get_params(hb_model *m, float *host_flat)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    if (!host_flat) return fail(HB_ERR_INVALID, "host_flat is NULL");
+    HB_HIP(hipMemcpyAsync(host_flat, m->d_params, sizeof(float) * (size_t)m->P, hipMemcpyDeviceToHost,
+                          m->stream));
+    HB_HIP(hipStreamSynchronize(m->stream));
+    return HB_OK;
+}
+
+int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float lr,
+                        float *d_loss)
+{
+    int rc = validate_batch_call(m, dX, dy, B, false);
+    if (rc != HB_OK) return rc;
+    if (!std::isfinite(lr)) return fail(HB_ERR_INVALID, "lr is not finite");
+    return run_dense(m, static_cast<const float *>(dX), dy, B, lr, MODE_STEP, nullptr, d_loss);
+}
+
+float hb_batch_step(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float lr)
+{
+    if (hb_batch_step_async(m, dX, dy, B, lr, nullptr) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    float out;
+    if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    return out;
+}
+
+float hb_batch_grad(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float *d_grad_flat)
+{
+    if (validate_batch_call(m, dX, dy, B, false) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    if (!d_grad_flat) return fail_nan("d_grad_flat is NULL");
+    if (run_dense(m, static_cast<const float *>(dX), dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    float out;
+    if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    return out;
+}
+
+float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B)
+{
+    if (validate_batch_call(m, dX, dy, B, false) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    if (run_dense(m, static_cast<const float *>(dX), dy, B, 0.f, MODE_LOSS, nullptr, nullptr) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    float out;
+    if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    return out;
+}
+
+int hb_batch_step_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                            const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B, float lr,
+                            float *d_loss)
+{
+    int rc = validate_batch_call(m, d_row_ptr, dy, B, true);
+    if (rc != HB_OK) return rc;
+    (void)d_col_idx; (void)d_vals; (void)nnz; (void)lr; (void)d_loss;
+    return fail(HB_ERR_UNSUPPORTED, "CSR step is not implemented in this build");
+}
+
+float hb_batch_step_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                        const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B, float lr)
+{
+    (void)hb_batch_step_csr_async(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr, nullptr);
+    return std::numeric_limits<float>::quiet_NaN();
+}
+
+float hb_batch_grad_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                        const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,
+                        float *d_grad_flat)
+{
+    (void)d_grad_flat;
+    (void)hb_batch_step_csr_async(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, 0.f, nullptr);
+    return std::numeric_limits<float>::quiet_NaN();
+}
+
+int hb_model_merge(hb_model *m, float *host_model, float weight)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    if (!host_model) return fail(HB_ERR_INVALID, "host_model is NULL");
+    if (!(weight >= 0.f && weight <= 1.f))
+        return fail(HB_ERR_INVALID, "weight = %g is outside [0, 1]", (double)weight);
+    const size_t bytes = sizeof(float) * (size_t)m->P;
+    if (weight == 0.f) {  // replica <- global: the deep copy of the ExecuteWork handler
+        HB_HIP(hipMemcpyAsync(m->d_params, host_model, bytes, hipMemcpyHostToDevice, m->stream));
+    } else if (weight == 1.f) {  // global <- replica: the push after the update
+        HB_HIP(hipMemcpyAsync(host_model, m->d_params, bytes, hipMemcpyDeviceToHost, m->stream));
+    } else {
+        HB_HIP(hipMemcpyAsync(m->d_stage, host_model, bytes, hipMemcpyHostToDevice, m->stream));
+        HB_HIP(launch_merge(m->d_params, m->d_stage, m->P, weight, m->stream));
+        HB_HIP(hipMemcpyAsync(host_model, m->d_stage, bytes, hipMemcpyDeviceToHost, m->stream));
+    }
+    HB_HIP(hipStreamSynchronize(m->stream));
+    return HB_OK;
+}
+
+}  // extern "C"

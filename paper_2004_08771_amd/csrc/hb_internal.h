@@ -1,0 +1,91 @@
+// Internal declarations shared by the HIP translation units of libhb (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hb {
+
+// ---------------------------------------------------------------- fp32 MFMA GEMM
+// C[M x N] (+)= sum_k A(m,k) * B(n,k), fp32 operands, fp32 MFMA accumulation.
+//   A K-major: A(m,k) = A[m*lda + k];  A M-major: A(m,k) = A[k*lda + m]  (same for B).
+// The three layer products of the step map onto it as
+//   forward   Z_l       = A_{l-1} . W_l^T      (A K-major, B K-major, epilogue FWD)
+//   backward  D_{l-1}   = (D_l . W_l) * f'     (A K-major, B M-major, epilogue DA)
+//   gradient  dW_l      = D_l^T . A_{l-1}      (A M-major, B M-major, epilogue DW, split over K = batch)
+enum GemmKind { GEMM_FWD = 0, GEMM_DA = 1, GEMM_DW = 2 };
+enum { ACT_NONE = -1, ACT_SIGMOID = 0, ACT_RELU = 1 };
+
+struct GemmArgs {
+    const void *A;
+    const void *B;
+    void *C;
+    int M, N, K;
+    int lda, ldb, ldc;
+    int a_vec, b_vec;          // 16-byte vector loads are legal for this operand
+    int splits;                // gridDim.y; slice s covers k in [s*k_chunk, min(K,(s+1)*k_chunk))
+    int k_chunk;               // multiple of the kernel's BK
+    long long c_split_stride;  // elements between the C slices of successive splits
+    const float *bias;         // FWD: bias[N] (may be null)
+    const void *aux;           // DA: stored output of the layer whose derivative is applied
+    int ldaux;
+    float *colsum;             // DW: column sums of A (= bias gradient partials) [splits][M], may be null
+    int act;                   // ACT_*
+    int tiles_m, tiles_n;
+};
+
+// Chooses the tile shape for (kind, M, N, K), fills tiles/splits (splits <= max_splits)
+// and launches.  Returns the number of K-splits used through *splits_out.
+hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *splits_out,
+                           hipStream_t stream);
+
+// Number of split-K slices launch_gemm_f32 will use for a DW product of this shape
+// (so that the caller can size the partial buffers).
+int gemm_f32_dw_splits(int M, int N, int K, int max_splits);
+
+// ---------------------------------------------------------------- loss / delta
+struct LossArgs {
+    const float *Z;   // B x ldz logits (fp32)
+    int ldz;
+    const int32_t *y;
+    long long B;
+    int K;            // d_L
+    int loss;         // HB_LOSS_*
+    void *delta;      // B x ldd, receives d(mean loss)/dZ (fp32, or bf16 when delta_bf16); may be null
+    int ldd;
+    int delta_bf16;
+    float *block_partials;   // >= grid blocks
+    unsigned int *counter;   // zero before the first launch; the kernel leaves it zero
+    float *loss_out;         // 1 float: mean loss
+    float *loss_out2;        // optional second destination (caller's d_loss), may be null
+};
+int loss_grid_blocks(long long B, int K);
+hipError_t launch_loss(const LossArgs &a, hipStream_t stream);
+
+// ---------------------------------------------------------------- update
+// One segment = one parameter tensor: value[i] -= lr * sum_s partial[s*stride + i]   (STEP)
+//                                 or  grad[i]  =       sum_s partial[s*stride + i]   (GRAD)
+struct UpdateSeg {
+    float *param;
+    float *grad_out;
+    const float *partial;
+    long long count;
+    long long stride;
+    int splits;
+    int pad;
+    void *shadow;   // bf16 copy of the tensor to refresh after the update (may be null)
+};
+constexpr int HB_MAX_SEGS = 40;
+struct UpdateArgs {
+    UpdateSeg seg[HB_MAX_SEGS];
+    int n_seg;
+    float lr;
+    int write_grad;   // 0: update params; 1: write grad_out
+};
+hipError_t launch_update(const UpdateArgs &a, hipStream_t stream);
+
+// D[i] = H[i] = (1-w) H[i] + w D[i]   (H is a device staging copy of the host model)
+hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t stream);
+hipError_t launch_fill_u32(unsigned int *p, long long n, unsigned int v, hipStream_t stream);
+
+}  // namespace hb
