@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the GPU-worker mini-batch step (forward, backward, SGD update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--batch 4096]
+
+A "step" is one hb_batch_step_async call over one batch of synthetic rows that are already
+resident in HBM; successive steps take successive contiguous row ranges of the dataset
+(the way the coordinator hands out batches, Algorithm 1 / 2 of the paper).  Prints ONE JSON
+line: throughput in training examples/s, the roofline figures of the dominant kernel
+(per-dispatch execution times read from events attached to the kernel launches in a second,
+profiled pass over the same steps), and the fp64 CPU oracle timed on a bounded sample of
+the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=2, help="workload (hb_inputs.CONFIGS index)")
+    ap.add_argument("--batch", type=int, default=4096, help="rows per step (the metric is quoted at 4096)")
+    ap.add_argument("--rows", type=int, default=0, help="dataset rows kept on the device (0: the config's size)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
+    return ap.parse_args()
+
+
+def make_device_dataset(hi, torch, config, rows):
+    """Synthetic dataset of the config's shape on the device: (X, y) or CSR arrays."""
+    cfg = hi.CONFIGS[config]
+    if cfg.sparse:
+        rp, ci, va, y = hi.make_csr_dataset(config, rows)
+        return {"row_ptr": rp, "col_idx": ci, "vals": va, "y": y}
+    X, y = hi.make_dense_dataset(config, rows)
+    return {"X": X, "y": y}
+
+
+def step_flops(dims, B, first_layer_nnz_per_row=None):
+    """Algorithmic flop of one step: forward 2P_w, dW 2P_w, dA 2(P_w - d_1 d_0) per example."""
+    pw = sum(dims[l] * dims[l - 1] for l in range(1, len(dims)))
+    first = dims[1] * dims[0]
+    if first_layer_nnz_per_row is not None:
+        pw_eff = pw - first + dims[1] * first_layer_nnz_per_row
+        return B * (4.0 * pw_eff + 2.0 * (pw - first))
+    return B * (6.0 * pw - 2.0 * first)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (each GPU worker owns one device and its own "
+              f"replica; there are no inter-GPU collectives on this path); --gpus {args.gpus} is not "
+              f"supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import hb_inputs as hi
+    import paper_2004_08771_amd as hb
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    hb.lib()  # fails loudly if the HIP library was not built
+    torch.cuda.set_device(0)
+
+    cfg = hi.CONFIGS[args.config]
+    B = args.batch
+    rows = args.rows or cfg.n_examples
+    rows = max(rows, B)
+    t_gen = time.perf_counter()
+    data = make_device_dataset(hi, torch, args.config, rows)
+    t_gen = time.perf_counter() - t_gen
+    dtype_name = "bf16" if cfg.dtype == hi.DTYPE_BF16_F32MASTER else "f32"
+
+    model = hb.Model(cfg.dims, cfg.activation, cfg.loss)
+    model.configure(hb.HB_BF16_F32MASTER if dtype_name == "bf16" else hb.HB_F32, B, cfg.sparse)
+    model.set_params(hi.make_params(args.config))
+    lr = 0.1 * B / 256 if args.config == 2 else cfg.lr
+
+    n_batches = rows // B
+    if cfg.sparse:
+        rp = data["row_ptr"]
+        d_ci = torch.from_numpy(data["col_idx"]).cuda()
+        d_va = torch.from_numpy(data["vals"]).cuda()
+        d_y = torch.from_numpy(data["y"]).cuda()
+        # per-batch row_ptr rebased to 0 (a batch is a contiguous row range)
+        batch_rp = [torch.from_numpy((rp[i * B:(i + 1) * B + 1] - rp[i * B]).astype(np.int32)).cuda()
+                    for i in range(n_batches)]
+        starts = [int(rp[i * B]) for i in range(n_batches)]
+        nnzs = [int(rp[(i + 1) * B] - rp[i * B]) for i in range(n_batches)]
+        mean_nnz = float(rp[n_batches * B]) / (n_batches * B)
+
+        def one_step(i, d_loss=None):
+            j = i % n_batches
+            model.batch_step_csr_async(batch_rp[j], d_ci[starts[j]:], d_va[starts[j]:], nnzs[j],
+                                       d_y[j * B:], B, lr, d_loss)
+    else:
+        X = data["X"]
+        d_X = torch.from_numpy(X).cuda()
+        if dtype_name == "bf16":
+            d_X = d_X.to(torch.bfloat16)
+        d_y = torch.from_numpy(data["y"]).cuda()
+        mean_nnz = None
+
+        row_bytes = d_X.element_size() * cfg.dims[0]
+        x_ptr = [d_X.data_ptr() + j * B * row_bytes for j in range(n_batches)]
+        y_ptr = [d_y.data_ptr() + j * B * 4 for j in range(n_batches)]
+
+        def one_step(i, d_loss=None):
+            j = i % n_batches
+            model.batch_step_async(x_ptr[j], y_ptr[j], B, lr, d_loss)
+
+    d_loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for i in range(args.warmup):
+        one_step(i, d_loss)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(args.warmup + i, d_loss)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    last_loss = float(d_loss.item())
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = args.steps * B / elapsed
+    flops = step_flops(cfg.dims, B, mean_nnz)
+
+    # ---- second pass over the same steps with per-dispatch events -> per-kernel times
+    roofline, kernels = None, []
+    if not args.no_profile:
+        model.profile_enable(True)
+        for i in range(args.steps):
+            one_step(args.warmup + i, d_loss)
+        stats = model.profile_read(512)
+        model.profile_enable(False)
+        for s in stats:
+            avg_us = 1e3 * s["total_ms"] / max(s["launches"], 1)
+            kernels.append({
+                "kernel": hb.binding.HB_K_NAMES.get(s["kind"], "?"), "layer": s["layer"],
+                "M": s["M"], "N": s["N"], "K": s["K"], "launches": s["launches"],
+                "avg_us": round(avg_us, 3), "share": 0.0,
+                "tflops": round(s["flops_per_launch"] / (avg_us * 1e-6) / 1e12, 3) if avg_us > 0 else None,
+                "gbs": round(s["bytes_per_launch"] / (avg_us * 1e-6) / 1e9, 1) if avg_us > 0 else None,
+                "_total_ms": s["total_ms"], "_flops": s["flops_per_launch"], "_bytes": s["bytes_per_launch"],
+            })
+        total = sum(k["_total_ms"] for k in kernels) or 1.0
+        for k in kernels:
+            k["share"] = round(k["_total_ms"] / total, 4)
+        # dominant kernel: merge entries of equal (kernel, shape) -- the hidden layers run the
+        # same kernel on the same shape -- and take the group with the largest total time
+        groups = {}
+        for k in kernels:
+            g = groups.setdefault((k["kernel"], k["M"], k["N"], k["K"]),
+                                  {"ms": 0.0, "n": 0, "flops": k["_flops"], "bytes": k["_bytes"]})
+            g["ms"] += k["_total_ms"]
+            g["n"] += k["launches"]
+        (name, M, N, K), g = max(groups.items(), key=lambda kv: kv[1]["ms"])
+        avg_s = 1e-3 * g["ms"] / g["n"]
+        mfma_time = g["flops"] / (PEAK_TFLOPS[dtype_name] * 1e12)
+        hbm_time = g["bytes"] / (PEAK_HBM_GBS * 1e9)
+        if mfma_time >= hbm_time and g["flops"] > 0:
+            ach = g["flops"] / avg_s / 1e12
+            roofline = {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_TFLOPS[dtype_name],
+                        "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS[dtype_name], 4)}
+        else:
+            ach = g["bytes"] / avg_s / 1e9
+            roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(ach / PEAK_HBM_GBS, 4)}
+        roofline.update({"traffic": None, "kernel": name, "shape": [M, N, K],
+                         "avg_kernel_us": round(avg_s * 1e6, 3), "launches": g["n"],
+                         "share_of_kernel_time": round(g["ms"] / total, 4),
+                         "sum_kernel_us_per_step": round(1e3 * total / args.steps, 2)})
+        traffic_file = os.path.join(ROOT, "profiles", f"traffic_config{args.config}_B{B}.json")
+        if os.path.exists(traffic_file):
+            with open(traffic_file) as f:
+                roofline["traffic"] = json.load(f).get(name)
+        for k in kernels:
+            for key in ("_total_ms", "_flops", "_bytes"):
+                k.pop(key)
+    model.destroy()
+
+    # ---- the oracle as it stands, on the host cores, on a bounded sample of the same workload
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        params64 = hi.make_params(args.config).astype(np.float64)
+        cores = oracle.max_threads()
+
+        def oracle_step(nrows):
+            t = time.perf_counter()
+            if cfg.sparse:
+                r, c, v = hi.csr_slice(data["row_ptr"], data["col_idx"], data["vals"], 0, nrows)
+                oracle.batch_step_csr(cfg.dims, cfg.activation, cfg.loss, params64, r, c, v,
+                                      data["y"][:nrows], lr)
+            else:
+                Xs = data["X"][:nrows]
+                if dtype_name == "bf16":
+                    Xs = oracle.bf16_round(Xs)
+                oracle.batch_step(cfg.dims, cfg.activation, cfg.loss, params64, Xs, data["y"][:nrows], lr)
+            return time.perf_counter() - t
+
+        probe_rows = min(B, 64)
+        rate = probe_rows / oracle_step(probe_rows)          # examples/s, B-independent
+        sample = int(min(B, max(probe_rows, rate * args.cpu_seconds)))
+        dt = oracle_step(sample)
+        cpu_baseline = {"value": round(sample / dt, 2), "unit": "examples/s", "cores": cores,
+                        "kind": "oracle",
+                        "sample": f"one fp64 oracle step (forward, backward, update) on the first {sample} "
+                                  f"rows of the same batch, {dt:.1f} s"}
+
+    out = {
+        "metric": "training examples/sec per SGD batch step at B=4096; % of MFMA peak",
+        "value": round(value, 1),
+        "unit": "examples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": dtype_name,
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg.name}", "layer_dims": list(cfg.dims),
+                   "batch": B, "dataset_rows": rows, "lr": lr, "sparse_first_layer": cfg.sparse},
+        "step_tflops": round(flops / (elapsed / args.steps) / 1e12, 3),
+        "step_frac_of_mfma_peak": round(flops / (elapsed / args.steps) / 1e12 / PEAK_TFLOPS[dtype_name], 4),
+        "last_loss": last_loss,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

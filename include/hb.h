@@ -154,8 +154,39 @@ float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B);
  */
 int hb_model_merge(hb_model *device_replica, float *host_model, float weight);
 
-/* Message for the last failing call on this thread ("" if none). */
+/* Message and code of the last failing call on this thread ("" / HB_OK if none). */
 const char *hb_last_error(void);
+int hb_last_error_code(void);
+
+/*
+ * Per-kernel timing, for measurement only (the benchmark's roofline figures).  While
+ * enabled, every kernel of a step is launched with a pair of events attached to its own
+ * dispatch, so that the recorded time is the kernel's execution time and nothing else.
+ * hb_profile_read synchronises the stream, adds up what was recorded since the last read
+ * into one entry per (kind, layer), writes at most cap entries to out (HOST pointer),
+ * stores the number of entries in *n_out and clears the record.
+ */
+enum {
+    HB_K_FWD_GEMM = 0,   /* Z_l = A_{l-1} W_l^T + b_l, activation          (Eq. (1)) */
+    HB_K_DA_GEMM = 1,    /* delta_{l-1} = (delta_l W_l) * f'                (Eq. (2)) */
+    HB_K_DW_GEMM = 2,    /* dW_l = delta_l^T A_{l-1}, db_l (split-K partials) (Eq. (2)) */
+    HB_K_LOSS = 3,       /* loss and output delta                           (Section 7.1) */
+    HB_K_UPDATE = 4,     /* W <- W - lr * sum of partials, all tensors      (Eq. (3)) */
+    HB_K_SPMM_FWD = 5,   /* CSR first layer, forward */
+    HB_K_SPARSE_DW = 6,  /* CSR first layer, gradient + update of the touched columns */
+    HB_K_OTHER = 7
+};
+typedef struct hb_kernel_stat {
+    int32_t kind;            /* HB_K_* */
+    int32_t layer;           /* 1..L, or 0 when the kernel is not per layer */
+    int64_t M, N, K;         /* product shape C[M x N] += A[M x K] B[K x N]; 0 if not a product */
+    int64_t launches;
+    double total_ms;         /* sum of the kernel execution times */
+    double flops_per_launch; /* algorithmic: 2 M N K for a product */
+    double bytes_per_launch; /* algorithmic HBM bytes: each operand read once, result written once */
+} hb_kernel_stat;
+int hb_profile_enable(hb_model *m, int on);
+int hb_profile_read(hb_model *m, hb_kernel_stat *out, int32_t cap, int32_t *n_out);
 
 /* Library version string, e.g. for logs. */
 const char *hb_version(void);

@@ -34,6 +34,22 @@ SIGNATURES = {
     "hb_version": (ctypes.c_char_p, []),
 }
 
+HB_K_NAMES = {0: "fwd_gemm", 1: "da_gemm", 2: "dw_gemm", 3: "loss", 4: "update", 5: "spmm_fwd",
+              6: "sparse_dw", 7: "other"}
+
+
+class KernelStat(ctypes.Structure):
+    """Mirror of hb_kernel_stat."""
+    _fields_ = [("kind", ctypes.c_int32), ("layer", ctypes.c_int32), ("M", ctypes.c_int64),
+                ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("launches", ctypes.c_int64),
+                ("total_ms", ctypes.c_double), ("flops_per_launch", ctypes.c_double),
+                ("bytes_per_launch", ctypes.c_double)]
+
+
+SIGNATURES["hb_last_error_code"] = (_int, [])
+SIGNATURES["hb_profile_enable"] = (_int, [_vp, _int])
+SIGNATURES["hb_profile_read"] = (_int, [_vp, ctypes.POINTER(KernelStat), _i32, _i32p])
+
 _lib = None
 
 
@@ -69,6 +85,12 @@ def last_error() -> str:
 def _check(rc: int) -> None:
     if rc != HB_OK:
         raise HbError(rc, last_error())
+
+
+def _check_float(v: float) -> float:
+    if v != v:
+        raise HbError(int(lib().hb_last_error_code()), last_error())
+    return v
 
 
 def _ptr(t):
@@ -117,9 +139,7 @@ class Model:
 
     def batch_step(self, dX, dy, B, lr) -> float:
         v = lib().hb_batch_step(self._h, _ptr(dX), _ptr(dy), int(B), float(lr))
-        if v != v:
-            raise HbError(HB_ERR_INVALID, last_error())
-        return v
+        return _check_float(v)
 
     def batch_step_async(self, dX, dy, B, lr, d_loss=None):
         _check(lib().hb_batch_step_async(self._h, _ptr(dX), _ptr(dy), int(B), float(lr), _ptr(d_loss)))
@@ -127,9 +147,7 @@ class Model:
     def batch_step_csr(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr) -> float:
         v = lib().hb_batch_step_csr(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals), int(nnz),
                                     _ptr(dy), int(B), float(lr))
-        if v != v:
-            raise HbError(HB_ERR_INVALID, last_error())
-        return v
+        return _check_float(v)
 
     def batch_step_csr_async(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr, d_loss=None):
         _check(lib().hb_batch_step_csr_async(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals),
@@ -137,22 +155,26 @@ class Model:
 
     def batch_grad(self, dX, dy, B, d_grad_flat) -> float:
         v = lib().hb_batch_grad(self._h, _ptr(dX), _ptr(dy), int(B), _ptr(d_grad_flat))
-        if v != v:
-            raise HbError(HB_ERR_INVALID, last_error())
-        return v
+        return _check_float(v)
 
     def batch_grad_csr(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, d_grad_flat) -> float:
         v = lib().hb_batch_grad_csr(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals), int(nnz),
                                     _ptr(dy), int(B), _ptr(d_grad_flat))
-        if v != v:
-            raise HbError(HB_ERR_INVALID, last_error())
-        return v
+        return _check_float(v)
 
     def batch_loss(self, dX, dy, B) -> float:
         v = lib().hb_batch_loss(self._h, _ptr(dX), _ptr(dy), int(B))
-        if v != v:
-            raise HbError(HB_ERR_INVALID, last_error())
-        return v
+        return _check_float(v)
 
     def model_merge(self, host_model, weight):
         _check(lib().hb_model_merge(self._h, _ptr(host_model), float(weight)))
+
+    def profile_enable(self, on=True):
+        _check(lib().hb_profile_enable(self._h, int(bool(on))))
+
+    def profile_read(self, cap=256):
+        """List of dicts, one per (kind, layer, shape) launched since the last read."""
+        buf = (KernelStat * cap)()
+        n = ctypes.c_int32(0)
+        _check(lib().hb_profile_read(self._h, buf, cap, ctypes.byref(n)))
+        return [{f: getattr(buf[i], f) for f, _ in KernelStat._fields_} for i in range(n.value)]

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(LOSS_NT) void loss_kernel(LossArgs a)
         __threadfence();
         double s = 0.0;
         for (unsigned int i = tid; i < gridDim.x; i += LOSS_NT)
-            s += (double)__builtin_nontemporal_load(&a.block_partials[i]);
+            s += (double)__hip_atomic_load(&a.block_partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __shared__ double dred[LOSS_NT];
         dred[tid] = s;
         __syncthreads();
@@ -204,22 +204,21 @@ int loss_grid_blocks(long long B, int K)
     return (int)((B + rows_per_block - 1) / rows_per_block);
 }
 
-hipError_t launch_loss(const LossArgs &a, hipStream_t stream)
+hipError_t launch_loss(const LossArgs &a, hipStream_t stream, const LaunchEvents &ev)
 {
-    const int blocks = loss_grid_blocks(a.B, a.K);
+    const dim3 grid((unsigned)loss_grid_blocks(a.B, a.K)), block(LOSS_NT);
     switch (loss_group(a.K)) {
-    case 1: loss_kernel<1><<<blocks, LOSS_NT, 0, stream>>>(a); break;
-    case 2: loss_kernel<2><<<blocks, LOSS_NT, 0, stream>>>(a); break;
-    case 4: loss_kernel<4><<<blocks, LOSS_NT, 0, stream>>>(a); break;
-    case 8: loss_kernel<8><<<blocks, LOSS_NT, 0, stream>>>(a); break;
-    case 16: loss_kernel<16><<<blocks, LOSS_NT, 0, stream>>>(a); break;
-    case 32: loss_kernel<32><<<blocks, LOSS_NT, 0, stream>>>(a); break;
-    default: loss_kernel<64><<<blocks, LOSS_NT, 0, stream>>>(a); break;
+    case 1: return launch_kernel(loss_kernel<1>, grid, block, stream, ev, a);
+    case 2: return launch_kernel(loss_kernel<2>, grid, block, stream, ev, a);
+    case 4: return launch_kernel(loss_kernel<4>, grid, block, stream, ev, a);
+    case 8: return launch_kernel(loss_kernel<8>, grid, block, stream, ev, a);
+    case 16: return launch_kernel(loss_kernel<16>, grid, block, stream, ev, a);
+    case 32: return launch_kernel(loss_kernel<32>, grid, block, stream, ev, a);
+    default: return launch_kernel(loss_kernel<64>, grid, block, stream, ev, a);
     }
-    return hipGetLastError();
 }
 
-hipError_t launch_update(const UpdateArgs &a, hipStream_t stream)
+hipError_t launch_update(const UpdateArgs &a, hipStream_t stream, const LaunchEvents &ev)
 {
     if (a.n_seg <= 0) return hipSuccess;
     long long mx = 0;
@@ -227,8 +226,8 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t stream)
     long long bx = (mx / 4 + UPD_NT - 1) / UPD_NT;
     if (bx < 1) bx = 1;
     if (bx > 2048) bx = 2048;
-    update_kernel<<<dim3((unsigned)bx, (unsigned)a.n_seg, 1), UPD_NT, 0, stream>>>(a);
-    return hipGetLastError();
+    return launch_kernel(update_kernel, dim3((unsigned)bx, (unsigned)a.n_seg, 1), dim3(UPD_NT), stream,
+                         ev, a);
 }
 
 hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t stream)

@@ -266,20 +266,21 @@ Shape pick_shape(GemmKind kind, int M, int N)
 constexpr int BK_F32 = 16;
 
 template <int BM, int BN, int WAVES_M>
-hipError_t launch_shape(GemmKind kind, const GemmArgs &a, dim3 grid, hipStream_t stream)
+hipError_t launch_shape(GemmKind kind, const GemmArgs &a, dim3 grid, hipStream_t stream,
+                        const LaunchEvents &ev)
 {
     switch (kind) {
     case GEMM_FWD:
-        gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, true, GEMM_FWD><<<grid, NT, 0, stream>>>(a);
-        break;
+        return launch_kernel(gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, true, GEMM_FWD>, grid,
+                             dim3(NT), stream, ev, a);
     case GEMM_DA:
-        gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, false, GEMM_DA><<<grid, NT, 0, stream>>>(a);
-        break;
+        return launch_kernel(gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, false, GEMM_DA>, grid,
+                             dim3(NT), stream, ev, a);
     case GEMM_DW:
-        gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, false, false, GEMM_DW><<<grid, NT, 0, stream>>>(a);
-        break;
+        return launch_kernel(gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, false, false, GEMM_DW>, grid,
+                             dim3(NT), stream, ev, a);
     }
-    return hipGetLastError();
+    return hipErrorInvalidValue;
 }
 
 struct SplitPlan {
@@ -309,7 +310,7 @@ int gemm_f32_dw_splits(int M, int N, int K, int max_splits)
 }
 
 hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *splits_out,
-                           hipStream_t stream)
+                           hipStream_t stream, const LaunchEvents &ev)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     const Shape sh = pick_shape(kind, a.M, a.N);
@@ -323,8 +324,8 @@ hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *split
     a.k_chunk = sp.chunk;
     if (splits_out) *splits_out = sp.splits;
     const dim3 grid((unsigned)tiles, (unsigned)sp.splits, 1);
-    if (sh.bm == 128) return launch_shape<128, 64, 2>(kind, a, grid, stream);
-    return launch_shape<64, 64, 2>(kind, a, grid, stream);
+    if (sh.bm == 128) return launch_shape<128, 64, 2>(kind, a, grid, stream, ev);
+    return launch_shape<64, 64, 2>(kind, a, grid, stream, ev);
 }
 
 }  // namespace hb

@@ -17,6 +17,7 @@ using namespace hb;
 namespace {
 
 thread_local char g_err[512] = "";
+thread_local int g_err_code = HB_OK;
 
 int fail(int code, const char *fmt, ...)
 {
@@ -24,6 +25,7 @@ int fail(int code, const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+    g_err_code = code;
     return code;
 }
 
@@ -33,7 +35,14 @@ float fail_nan(const char *fmt, ...)
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+    g_err_code = HB_ERR_INVALID;
     return std::numeric_limits<float>::quiet_NaN();
+}
+
+void clear_error()
+{
+    g_err[0] = 0;
+    g_err_code = HB_OK;
 }
 
 #define HB_HIP(call)                                                                        \
@@ -82,6 +91,15 @@ struct hb_model {
     float *h_loss = nullptr;             // pinned
     float *d_stage = nullptr;            // P floats: staging copy of the host model
     std::vector<void *> owned;           // every device allocation, for destroy
+
+    // per-kernel profile (measurement only)
+    struct ProfRec {
+        hb_kernel_stat info;
+        hipEvent_t start, stop;
+    };
+    bool prof_on = false;
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> free_events;
 };
 
 namespace {
@@ -101,10 +119,48 @@ int dev_alloc(hb_model *m, T **out, size_t count)
 
 void release_device(hb_model *m)
 {
+    for (auto &r : m->prof) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    m->prof.clear();
+    for (hipEvent_t e : m->free_events) (void)hipEventDestroy(e);
+    m->free_events.clear();
     for (void *p : m->owned) (void)hipFree(p);
     m->owned.clear();
     if (m->h_loss) (void)hipHostFree(m->h_loss);
     m->h_loss = nullptr;
+}
+
+// Events for one profiled dispatch (empty when profiling is off or events run out).
+LaunchEvents prof_begin(hb_model *m, int kind, int layer, int64_t M, int64_t N, int64_t K, double flops,
+                        double bytes)
+{
+    LaunchEvents ev;
+    if (!m->prof_on) return ev;
+    hipEvent_t e[2] = {nullptr, nullptr};
+    for (int i = 0; i < 2; ++i) {
+        if (!m->free_events.empty()) {
+            e[i] = m->free_events.back();
+            m->free_events.pop_back();
+        } else if (hipEventCreate(&e[i]) != hipSuccess) {
+            if (i == 1) m->free_events.push_back(e[0]);
+            return ev;
+        }
+    }
+    hb_model::ProfRec r;
+    r.info = hb_kernel_stat{kind, layer, M, N, K, 1, 0.0, flops, bytes};
+    r.start = e[0];
+    r.stop = e[1];
+    m->prof.push_back(r);
+    ev.start = e[0];
+    ev.stop = e[1];
+    return ev;
+}
+
+double gemm_bytes(int64_t M, int64_t N, int64_t K, int64_t extra)
+{
+    return 4.0 * ((double)M * K + (double)N * K + (double)M * N + (double)extra);
 }
 
 int check_handle(const hb_model *m, bool need_configured)
@@ -139,7 +195,9 @@ int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr
         g.b_vec = aligned16(g.B) && (g.ldb % 4 == 0);
         g.bias = m->d_params + m->b_off[l];
         g.act = (l < L) ? m->act : ACT_NONE;
-        HB_HIP(launch_gemm_f32(GEMM_FWD, g, 1, nullptr, st));
+        HB_HIP(launch_gemm_f32(GEMM_FWD, g, 1, nullptr, st,
+                               prof_begin(m, HB_K_FWD_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                          gemm_bytes(g.M, g.N, g.K, g.N))));
     }
 
     // ---- loss and output delta (Section 7.1)
@@ -157,7 +215,8 @@ int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr
     la.counter = m->d_counter;
     la.loss_out = m->d_loss;
     la.loss_out2 = d_loss_user;
-    HB_HIP(launch_loss(la, st));
+    HB_HIP(launch_loss(la, st, prof_begin(m, HB_K_LOSS, 0, 0, 0, 0, 0.0,
+                                          4.0 * B * (la.K * (la.delta ? 2.0 : 1.0) + 1.0))));
     if (mode == MODE_LOSS) return HB_OK;
 
     // ---- backward, Eq. (2), with the weights the forward pass used
@@ -182,7 +241,9 @@ int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr
             g.aux = m->acts[l - 1];
             g.ldaux = m->ld[l - 1];
             g.act = m->act;
-            HB_HIP(launch_gemm_f32(GEMM_DA, g, 1, nullptr, st));
+            HB_HIP(launch_gemm_f32(GEMM_DA, g, 1, nullptr, st,
+                                   prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                              gemm_bytes(g.M, g.N, g.K, (int64_t)g.M * g.N))));
         }
         GemmArgs g = {};
         g.A = delta_l;
@@ -200,7 +261,9 @@ int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr
         g.colsum = m->partial_b[l];
         g.act = ACT_NONE;
         int splits = 1;
-        HB_HIP(launch_gemm_f32(GEMM_DW, g, m->cap_splits[l], &splits, st));
+        HB_HIP(launch_gemm_f32(GEMM_DW, g, m->cap_splits[l], &splits, st,
+                               prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                          gemm_bytes(g.M, g.N, g.K, g.M))));
 
         UpdateSeg &sw = ua.seg[ua.n_seg++];
         sw.param = m->d_params + m->w_off[l];
@@ -219,7 +282,9 @@ int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr
     }
 
     // ---- Eq. (3): W <- W - lr g for every tensor in one launch (or the gradient itself)
-    HB_HIP(launch_update(ua, st));
+    double upd_bytes = 0.0;  // read W, read one gradient, write W
+    for (int i = 0; i < ua.n_seg; ++i) upd_bytes += 12.0 * (double)ua.seg[i].count;
+    HB_HIP(launch_update(ua, st, prof_begin(m, HB_K_UPDATE, 0, 0, 0, 0, 2.0 * (double)m->P, upd_bytes)));
     return HB_OK;
 }
 
@@ -252,6 +317,49 @@ int fetch_loss(hb_model *m, float *out)
 extern "C" {
 
 const char *hb_last_error(void) { return g_err; }
+int hb_last_error_code(void) { return g_err_code; }
+
+int hb_profile_enable(hb_model *m, int on)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    m->prof_on = on != 0;
+    return HB_OK;
+}
+
+int hb_profile_read(hb_model *m, hb_kernel_stat *out, int32_t cap, int32_t *n_out)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    if (!out || !n_out || cap < 1) return fail(HB_ERR_INVALID, "out / n_out is NULL or cap < 1");
+    HB_HIP(hipStreamSynchronize(m->stream));
+    std::vector<hb_kernel_stat> acc;
+    for (auto &r : m->prof) {
+        float ms = 0.f;
+        HB_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+        m->free_events.push_back(r.start);
+        m->free_events.push_back(r.stop);
+        bool found = false;
+        for (auto &a : acc)
+            if (a.kind == r.info.kind && a.layer == r.info.layer && a.M == r.info.M && a.N == r.info.N &&
+                a.K == r.info.K) {
+                a.launches += 1;
+                a.total_ms += ms;
+                found = true;
+                break;
+            }
+        if (!found) {
+            hb_kernel_stat s = r.info;
+            s.total_ms = ms;
+            acc.push_back(s);
+        }
+    }
+    m->prof.clear();
+    const int32_t n = (int32_t)acc.size() < cap ? (int32_t)acc.size() : cap;
+    for (int32_t i = 0; i < n; ++i) out[i] = acc[i];
+    *n_out = n;
+    return HB_OK;
+}
 const char *hb_version(void) { return "hb-mlp 0.1 (gfx950)"; }
 
 hb_model *hb_mlp_create(const int32_t *layer_dims, int32_t n_dims, int activation, int loss)
@@ -295,7 +403,7 @@ hb_model *hb_mlp_create(const int32_t *layer_dims, int32_t n_dims, int activatio
         off += m->dims[l];
     }
     m->P = off;
-    g_err[0] = 0;
+    clear_error();
     return m;
 }
 
@@ -366,7 +474,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         return fail(HB_ERR_DEVICE, "initialising device buffers failed: %s", hipGetErrorString(e));
     }
     m->configured = true;
-    g_err[0] = 0;
+    clear_error();
     return HB_OK;
 }
 

@@ -2,9 +2,28 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace hb {
+
+// Optional pair of events attached to one kernel dispatch: their elapsed time is that
+// kernel's own execution time (used by the per-kernel profile the benchmark reads).
+struct LaunchEvents {
+    hipEvent_t start = nullptr;
+    hipEvent_t stop = nullptr;
+};
+
+template <typename F, typename... Args>
+inline hipError_t launch_kernel(F kernel, dim3 grid, dim3 block, hipStream_t stream,
+                                const LaunchEvents &ev, Args... args)
+{
+    if (ev.start != nullptr)
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev.start, ev.stop, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+    return hipGetLastError();
+}
 
 // ---------------------------------------------------------------- fp32 MFMA GEMM
 // C[M x N] (+)= sum_k A(m,k) * B(n,k), fp32 operands, fp32 MFMA accumulation.
@@ -37,7 +56,7 @@ struct GemmArgs {
 // Chooses the tile shape for (kind, M, N, K), fills tiles/splits (splits <= max_splits)
 // and launches.  Returns the number of K-splits used through *splits_out.
 hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *splits_out,
-                           hipStream_t stream);
+                           hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
 // Number of split-K slices launch_gemm_f32 will use for a DW product of this shape
 // (so that the caller can size the partial buffers).
@@ -60,7 +79,7 @@ struct LossArgs {
     float *loss_out2;        // optional second destination (caller's d_loss), may be null
 };
 int loss_grid_blocks(long long B, int K);
-hipError_t launch_loss(const LossArgs &a, hipStream_t stream);
+hipError_t launch_loss(const LossArgs &a, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
 // ---------------------------------------------------------------- update
 // One segment = one parameter tensor: value[i] -= lr * sum_s partial[s*stride + i]   (STEP)
@@ -82,7 +101,7 @@ struct UpdateArgs {
     float lr;
     int write_grad;   // 0: update params; 1: write grad_out
 };
-hipError_t launch_update(const UpdateArgs &a, hipStream_t stream);
+hipError_t launch_update(const UpdateArgs &a, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
 // D[i] = H[i] = (1-w) H[i] + w D[i]   (H is a device staging copy of the host model)
 hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t stream);

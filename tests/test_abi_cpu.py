@@ -1,0 +1,69 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching a device."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2004_08771_amd as hb
+from paper_2004_08771_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert "hb_mlp_create" in names and "hb_batch_step" in names and "hb_model_merge" in names
+    assert "hb_batch_grad" in names and len(names) >= 18
+    l = hb.lib()
+    for n in names:
+        assert hasattr(l, n), f"{n} is declared in include/hb.h but not exported"
+    # and the binding marshals every one of them
+    assert sorted(binding.SIGNATURES) == names
+
+
+def test_create_validates_on_the_host():
+    for dims, act, loss in [((54,), 0, 0), ((), 0, 0), ((54, 0, 7), 0, 0), ((54, -3, 7), 0, 0),
+                            ((54, 32, 7), 2, 0), ((54, 32, 7), 0, 5), ((54, 32, 3), 0, 1),
+                            (tuple([8] * 40), 0, 0)]:
+        with pytest.raises(hb.HbError):
+            hb.Model(dims, act, loss)
+    m = hb.Model((54, 32, 7))
+    assert m.num_params == 54 * 32 + 32 + 32 * 7 + 7
+    m.destroy()
+    assert hb.lib().hb_model_num_params(None) == -1
+    hb.lib().hb_model_destroy(None)  # allowed
+
+
+def test_calls_before_configure_fail_with_state_error():
+    m = hb.Model((8, 4, 2), hb.HB_ACT_RELU, hb.HB_LOSS_LOGISTIC)
+    buf = np.zeros(m.num_params, np.float32)
+    for call in (lambda: m.set_params(buf), lambda: m.get_params(buf), lambda: m.model_merge(buf, 0.5),
+                 lambda: m.batch_step(1, 1, 4, 0.1), lambda: m.batch_grad(1, 1, 4, 1),
+                 lambda: m.batch_loss(1, 1, 4), lambda: m.batch_step_async(1, 1, 4, 0.1),
+                 lambda: m.batch_step_csr(1, 1, 1, 4, 1, 4, 0.1), lambda: m.profile_enable(True)):
+        with pytest.raises(hb.HbError) as e:
+            call()
+        assert e.value.code == hb.HB_ERR_STATE
+    m.destroy()
+
+
+def test_configure_validates_before_any_device_call():
+    m = hb.Model((8, 4, 2))
+    for dtype, max_B, sparse in [(7, 16, 0), (hb.HB_F32, 0, 0), (hb.HB_F32, -5, 0),
+                                 (hb.HB_F32, 1 << 40, 0), (hb.HB_BF16_F32MASTER, 16, 1)]:
+        with pytest.raises(hb.HbError) as e:
+            m.configure(dtype, max_B, sparse)
+        assert e.value.code == hb.HB_ERR_INVALID
+    m.destroy()
+    with pytest.raises(hb.HbError) as e:
+        hb.lib().hb_mlp_configure.restype  # keep the symbol referenced
+        binding._check(hb.lib().hb_mlp_configure(None, 0, 16, 0, None))
+    assert e.value.code == hb.HB_ERR_INVALID

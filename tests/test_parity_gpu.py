@@ -7,6 +7,7 @@ import pytest
 
 import hb_inputs as hi
 import oracle
+from relu_margin import keep_relu_units_off_the_kink
 
 pytestmark = pytest.mark.gpu
 
@@ -67,6 +68,9 @@ def gpu_grad_and_step(dims, act, loss, params, X, y, lr, max_B=None):
 
 
 def check_case(dims, act, loss, params, X, y, lr, max_B=None, tol=TOL_F32):
+    if act == hi.ACT_RELU:
+        # the ReLU mask is a discrete decision: keep it identical in fp32 and fp64
+        params = keep_relu_units_off_the_kink(dims, params, X)
     l_ref, g_ref = oracle.batch_grad(dims, act, loss, params, X, y)
     l_ref2, p_ref = oracle.batch_step(dims, act, loss, params, X, y, lr)
     lg, g, lf, ls, after = gpu_grad_and_step(dims, act, loss, params, X, y, lr, max_B)
