@@ -90,6 +90,15 @@ struct hb_model {
     float *d_loss = nullptr;
     float *h_loss = nullptr;             // pinned
     float *d_stage = nullptr;            // P floats: staging copy of the host model
+
+    // sparse first layer: W_1 lives transposed (d_0 x d_1); the W_1 region of d_params is
+    // only a staging area for set/get/merge
+    float *d_w1t = nullptr;
+    int32_t *d_col_cnt = nullptr, *d_col_start = nullptr, *d_chunk_start = nullptr, *d_cursor = nullptr;
+    int32_t *d_csc_row = nullptr;
+    float *d_csc_val = nullptr;
+    int64_t csc_cap = 0;
+    int b1_splits = 1;
     std::vector<void *> owned;           // every device allocation, for destroy
 
     // per-kernel profile (measurement only)
@@ -126,6 +135,11 @@ void release_device(hb_model *m)
     m->prof.clear();
     for (hipEvent_t e : m->free_events) (void)hipEventDestroy(e);
     m->free_events.clear();
+    if (m->d_csc_row) (void)hipFree(m->d_csc_row);
+    if (m->d_csc_val) (void)hipFree(m->d_csc_val);
+    m->d_csc_row = nullptr;
+    m->d_csc_val = nullptr;
+    m->csc_cap = 0;
     for (void *p : m->owned) (void)hipFree(p);
     m->owned.clear();
     if (m->h_loss) (void)hipHostFree(m->h_loss);
@@ -171,16 +185,79 @@ int check_handle(const hb_model *m, bool need_configured)
     return HB_OK;
 }
 
-// Issues the kernels of one step.  X is dense B x d_0 fp32.
-int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr, StepMode mode,
-              float *d_grad_flat, float *d_loss_user)
+struct Input {
+    const float *X = nullptr;  // dense B x d_0, or
+    const int32_t *row_ptr = nullptr, *col_idx = nullptr;
+    const float *vals = nullptr;
+    int64_t nnz = 0;
+};
+
+// W1t <-> the W_1 region of the flat buffer (sparse mode only)
+int sync_w1t_from_flat(hb_model *m)
+{
+    if (!m->sparse) return HB_OK;
+    HB_HIP(launch_transpose(m->d_params + m->w_off[1], m->d_w1t, m->dims[1], m->dims[0], m->stream));
+    return HB_OK;
+}
+
+int sync_flat_from_w1t(hb_model *m)
+{
+    if (!m->sparse) return HB_OK;
+    HB_HIP(launch_transpose(m->d_w1t, m->d_params + m->w_off[1], m->dims[0], m->dims[1], m->stream));
+    return HB_OK;
+}
+
+// The per-batch CSC arrays grow on demand (nnz is only known per call).
+int ensure_csc_capacity(hb_model *m, int64_t nnz)
+{
+    if (nnz <= m->csc_cap) return HB_OK;
+    HB_HIP(hipStreamSynchronize(m->stream));
+    int64_t cap = m->csc_cap > 0 ? m->csc_cap : 1024;
+    while (cap < nnz) cap *= 2;
+    if (m->d_csc_row) (void)hipFree(m->d_csc_row);
+    if (m->d_csc_val) (void)hipFree(m->d_csc_val);
+    m->d_csc_row = nullptr;
+    m->d_csc_val = nullptr;
+    m->csc_cap = 0;
+    if (hipMalloc(reinterpret_cast<void **>(&m->d_csc_row), sizeof(int32_t) * (size_t)cap) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&m->d_csc_val), sizeof(float) * (size_t)cap) != hipSuccess)
+        return fail(HB_ERR_ALLOC, "could not allocate the per-batch CSC workspace for %lld non-zeros",
+                    (long long)nnz);
+    m->csc_cap = cap;
+    return HB_OK;
+}
+
+// Issues the kernels of one step.
+int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr, StepMode mode,
+             float *d_grad_flat, float *d_loss_user)
 {
     const int L = m->L;
     const int Bi = (int)B;
     hipStream_t st = m->stream;
+    const float *X = in.X;
 
     // ---- forward, Eq. (1): A_l = f(A_{l-1} W_l^T + b_l); the last layer keeps raw scores
     for (int l = 1; l <= L; ++l) {
+        if (l == 1 && m->sparse) {
+            SpmmArgs sp = {};
+            sp.row_ptr = in.row_ptr;
+            sp.col_idx = in.col_idx;
+            sp.vals = in.vals;
+            sp.W1t = m->d_w1t;
+            sp.ldw = m->dims[1];
+            sp.bias = m->d_params + m->b_off[1];
+            sp.out = m->acts[1];
+            sp.ldo = m->ld[1];
+            sp.d1 = m->dims[1];
+            sp.act = (L > 1) ? m->act : ACT_NONE;
+            sp.vec = (m->dims[1] % 4 == 0) && aligned16(sp.bias);
+            const double gather = (double)in.nnz * (8.0 + 4.0 * m->dims[1]);
+            HB_HIP(launch_spmm_fwd(sp, B, st,
+                                   prof_begin(m, HB_K_SPMM_FWD, 1, B, m->dims[1], in.nnz,
+                                              2.0 * in.nnz * m->dims[1],
+                                              gather + 4.0 * B * (m->dims[1] + 1.0))));
+            continue;
+        }
         GemmArgs g = {};
         g.A = (l == 1) ? X : m->acts[l - 1];
         g.lda = (l == 1) ? m->dims[0] : m->ld[l - 1];
@@ -245,6 +322,55 @@ int run_dense(hb_model *m, const float *X, const int32_t *y, int64_t B, float lr
                                    prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
                                               gemm_bytes(g.M, g.N, g.K, (int64_t)g.M * g.N))));
         }
+        if (l == 1 && m->sparse) {
+            // db_1: column sums of delta_1; dW_1: column-segmented sums over the non-zeros,
+            // applied to W1t directly (only columns that occur in the batch are touched)
+            HB_HIP(launch_colsum(delta_l, m->ld[1], B, m->dims[1], m->b1_splits, m->partial_b[1], st,
+                                 prof_begin(m, HB_K_OTHER, 1, 0, 0, 0, (double)B * m->dims[1],
+                                            4.0 * B * m->dims[1])));
+            UpdateSeg &sb = ua.seg[ua.n_seg++];
+            sb.param = m->d_params + m->b_off[1];
+            sb.grad_out = d_grad_flat ? d_grad_flat + m->b_off[1] : nullptr;
+            sb.partial = m->partial_b[1];
+            sb.count = m->dims[1];
+            sb.stride = m->dims[1];
+            sb.splits = m->b1_splits;
+            HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_col_cnt,
+                                    m->d_col_start, m->d_chunk_start, m->d_cursor, m->d_csc_row,
+                                    m->d_csc_val, st,
+                                    prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
+                                    prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
+                                    prof_begin(m, HB_K_OTHER, 4, 0, 0, 0, 0.0, 16.0 * in.nnz)));
+            SparseDwArgs sd = {};
+            sd.col_start = m->d_col_start;
+            sd.chunk_start = m->d_chunk_start;
+            sd.csc_row = m->d_csc_row;
+            sd.csc_val = m->d_csc_val;
+            sd.delta = delta_l;
+            sd.ldd = m->ld[1];
+            sd.W1t = m->d_w1t;
+            sd.ldw = m->dims[1];
+            sd.d0 = m->dims[0];
+            sd.d1 = m->dims[1];
+            sd.lr = lr;
+            sd.vec = (m->dims[1] % 4 == 0);
+            if (mode == MODE_GRAD) {
+                sd.grad_out = d_grad_flat + m->w_off[1];
+                HB_HIP(hipMemsetAsync(sd.grad_out, 0, sizeof(float) * (size_t)m->dims[1] * m->dims[0], st));
+            }
+            // chunks <= nnz / CHUNK + (number of distinct columns) <= nnz / CHUNK + min(d_0, nnz)
+            const long long max_chunks = in.nnz / sparse_chunk() + (in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
+            // algorithmic bytes: delta_1 rows gathered once per non-zero is cache traffic; HBM sees
+            // delta_1 once, the CSC arrays, and a read + write of each touched weight row (bounded
+            // by min(nnz, d_0) rows)
+            const double touched = (double)(in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
+            HB_HIP(launch_sparse_dw(sd, max_chunks, st,
+                                    prof_begin(m, HB_K_SPARSE_DW, 1, m->dims[1], m->dims[0], in.nnz,
+                                               2.0 * in.nnz * m->dims[1],
+                                               4.0 * B * m->dims[1] + 8.0 * in.nnz +
+                                                   8.0 * touched * m->dims[1])));
+            continue;
+        }
         GemmArgs g = {};
         g.A = delta_l;
         g.lda = m->ld[l];
@@ -301,6 +427,21 @@ int validate_batch_call(hb_model *m, const void *a, const int32_t *dy, int64_t B
     if (B < 1 || B > m->max_B)
         return fail(HB_ERR_INVALID, "B = %lld is outside [1, max_B = %lld]", (long long)B,
                     (long long)m->max_B);
+    return HB_OK;
+}
+
+int validate_csr_call(hb_model *m, const int32_t *rp, const int32_t *ci, const float *va, int64_t nnz,
+                      const int32_t *dy, int64_t B, Input *in)
+{
+    int rc = validate_batch_call(m, rp, dy, B, true);
+    if (rc != HB_OK) return rc;
+    if (nnz < 0 || nnz > 0x7fffffffLL || nnz > B * (int64_t)m->dims[0])
+        return fail(HB_ERR_INVALID, "nnz = %lld is outside [0, min(2^31 - 1, B * d_0)]", (long long)nnz);
+    if (nnz > 0 && (!ci || !va)) return fail(HB_ERR_INVALID, "d_col_idx / d_vals is NULL");
+    in->row_ptr = rp;
+    in->col_idx = ci;
+    in->vals = va;
+    in->nnz = nnz;
     return HB_OK;
 }
 
@@ -423,8 +564,6 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         return fail(HB_ERR_INVALID, "sparse_first_layer needs dtype HB_F32");
     if (dtype == HB_BF16_F32MASTER)
         return fail(HB_ERR_UNSUPPORTED, "HB_BF16_F32MASTER is not implemented in this build");
-    if (sparse_first_layer)
-        return fail(HB_ERR_UNSUPPORTED, "sparse_first_layer is not implemented in this build");
 
     int dev = -1;
     HB_HIP(hipGetDevice(&dev));
@@ -452,11 +591,25 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
     for (int l = 1; l <= L && rc == HB_OK; ++l) {
         rc = dev_alloc(m, &m->acts[l], (size_t)max_B * m->ld[l]);
         if (rc != HB_OK) break;
+        if (l == 1 && m->sparse) {
+            m->b1_splits = (int)((max_B + 127) / 128 < MAX_SPLITS ? (max_B + 127) / 128 : MAX_SPLITS);
+            m->cap_splits[l] = m->b1_splits;
+            rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
+            continue;
+        }
         m->cap_splits[l] = gemm_f32_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, MAX_SPLITS);
         rc = dev_alloc(m, &m->partial_w[l], (size_t)m->cap_splits[l] * m->dims[l] * m->dims[l - 1]);
         if (rc == HB_OK) rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
     }
     for (int i = 0; i < 2 && rc == HB_OK; ++i) rc = dev_alloc(m, &m->delta[i], (size_t)max_B * max_ld);
+    if (m->sparse && rc == HB_OK) {
+        const size_t d0 = (size_t)m->dims[0];
+        rc = dev_alloc(m, &m->d_w1t, d0 * m->dims[1]);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_cnt, d0 + 1);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_start, d0 + 1);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 1);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, d0 + 1);
+    }
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss_partials, (size_t)loss_grid_blocks(max_B, m->dims[L]) + 1);
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_counter, 4);
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss, 4);
@@ -467,6 +620,8 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         return fail(HB_ERR_ALLOC, "hipHostMalloc failed: %s", hipGetErrorString(e));
     }
     e = hipMemsetAsync(m->d_params, 0, sizeof(float) * (size_t)m->P, m->stream);
+    if (e == hipSuccess && m->sparse)
+        e = hipMemsetAsync(m->d_w1t, 0, sizeof(float) * (size_t)m->dims[0] * m->dims[1], m->stream);
     if (e == hipSuccess) e = launch_fill_u32(m->d_counter, 4, 0u, m->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
     if (e != hipSuccess) {
@@ -493,6 +648,8 @@ int hb_model_set_params(hb_model *m, const float *host_flat)
     if (!host_flat) return fail(HB_ERR_INVALID, "host_flat is NULL");
     HB_HIP(hipMemcpyAsync(m->d_params, host_flat, sizeof(float) * (size_t)m->P, hipMemcpyHostToDevice,
                           m->stream));
+    rc = sync_w1t_from_flat(m);
+    if (rc != HB_OK) return rc;
     HB_HIP(hipStreamSynchronize(m->stream));
     return HB_OK;
 }
@@ -502,6 +659,8 @@ int hb_model_get_params(hb_model *m, float *host_flat)
     int rc = check_handle(m, true);
     if (rc != HB_OK) return rc;
     if (!host_flat) return fail(HB_ERR_INVALID, "host_flat is NULL");
+    rc = sync_flat_from_w1t(m);
+    if (rc != HB_OK) return rc;
     HB_HIP(hipMemcpyAsync(host_flat, m->d_params, sizeof(float) * (size_t)m->P, hipMemcpyDeviceToHost,
                           m->stream));
     HB_HIP(hipStreamSynchronize(m->stream));
@@ -514,7 +673,9 @@ int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t 
     int rc = validate_batch_call(m, dX, dy, B, false);
     if (rc != HB_OK) return rc;
     if (!std::isfinite(lr)) return fail(HB_ERR_INVALID, "lr is not finite");
-    return run_dense(m, static_cast<const float *>(dX), dy, B, lr, MODE_STEP, nullptr, d_loss);
+    Input in;
+    in.X = static_cast<const float *>(dX);
+    return run_step(m, in, dy, B, lr, MODE_STEP, nullptr, d_loss);
 }
 
 float hb_batch_step(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float lr)
@@ -531,7 +692,9 @@ float hb_batch_grad(hb_model *m, const void *dX, const int32_t *dy, int64_t B, f
     if (validate_batch_call(m, dX, dy, B, false) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
     if (!d_grad_flat) return fail_nan("d_grad_flat is NULL");
-    if (run_dense(m, static_cast<const float *>(dX), dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr) != HB_OK)
+    Input in;
+    in.X = static_cast<const float *>(dX);
+    if (run_step(m, in, dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
     float out;
     if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
@@ -542,7 +705,9 @@ float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B)
 {
     if (validate_batch_call(m, dX, dy, B, false) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
-    if (run_dense(m, static_cast<const float *>(dX), dy, B, 0.f, MODE_LOSS, nullptr, nullptr) != HB_OK)
+    Input in;
+    in.X = static_cast<const float *>(dX);
+    if (run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, nullptr) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
     float out;
     if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
@@ -553,26 +718,39 @@ int hb_batch_step_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t
                             const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B, float lr,
                             float *d_loss)
 {
-    int rc = validate_batch_call(m, d_row_ptr, dy, B, true);
+    Input in;
+    int rc = validate_csr_call(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, &in);
     if (rc != HB_OK) return rc;
-    (void)d_col_idx; (void)d_vals; (void)nnz; (void)lr; (void)d_loss;
-    return fail(HB_ERR_UNSUPPORTED, "CSR step is not implemented in this build");
+    if (!std::isfinite(lr)) return fail(HB_ERR_INVALID, "lr is not finite");
+    rc = ensure_csc_capacity(m, nnz);
+    if (rc != HB_OK) return rc;
+    return run_step(m, in, dy, B, lr, MODE_STEP, nullptr, d_loss);
 }
 
 float hb_batch_step_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
                         const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B, float lr)
 {
-    (void)hb_batch_step_csr_async(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr, nullptr);
-    return std::numeric_limits<float>::quiet_NaN();
+    if (hb_batch_step_csr_async(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, lr, nullptr) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    float out;
+    if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    return out;
 }
 
 float hb_batch_grad_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
                         const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,
                         float *d_grad_flat)
 {
-    (void)d_grad_flat;
-    (void)hb_batch_step_csr_async(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, 0.f, nullptr);
-    return std::numeric_limits<float>::quiet_NaN();
+    Input in;
+    if (validate_csr_call(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, &in) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    if (!d_grad_flat) return fail_nan("d_grad_flat is NULL");
+    if (ensure_csc_capacity(m, nnz) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    if (run_step(m, in, dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    float out;
+    if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    return out;
 }
 
 int hb_model_merge(hb_model *m, float *host_model, float weight)
@@ -585,12 +763,20 @@ int hb_model_merge(hb_model *m, float *host_model, float weight)
     const size_t bytes = sizeof(float) * (size_t)m->P;
     if (weight == 0.f) {  // replica <- global: the deep copy of the ExecuteWork handler
         HB_HIP(hipMemcpyAsync(m->d_params, host_model, bytes, hipMemcpyHostToDevice, m->stream));
+        rc = sync_w1t_from_flat(m);
+        if (rc != HB_OK) return rc;
     } else if (weight == 1.f) {  // global <- replica: the push after the update
+        rc = sync_flat_from_w1t(m);
+        if (rc != HB_OK) return rc;
         HB_HIP(hipMemcpyAsync(host_model, m->d_params, bytes, hipMemcpyDeviceToHost, m->stream));
     } else {
+        rc = sync_flat_from_w1t(m);
+        if (rc != HB_OK) return rc;
         HB_HIP(hipMemcpyAsync(m->d_stage, host_model, bytes, hipMemcpyHostToDevice, m->stream));
         HB_HIP(launch_merge(m->d_params, m->d_stage, m->P, weight, m->stream));
         HB_HIP(hipMemcpyAsync(host_model, m->d_stage, bytes, hipMemcpyDeviceToHost, m->stream));
+        rc = sync_w1t_from_flat(m);
+        if (rc != HB_OK) return rc;
     }
     HB_HIP(hipStreamSynchronize(m->stream));
     return HB_OK;

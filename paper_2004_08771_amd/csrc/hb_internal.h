@@ -107,4 +107,49 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t stream, const LaunchEv
 hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t stream);
 hipError_t launch_fill_u32(unsigned int *p, long long n, unsigned int v, hipStream_t stream);
 
+
+// ---------------------------------------------------------------- CSR first layer
+struct SpmmArgs {
+    const int32_t *row_ptr;
+    const int32_t *col_idx;
+    const float *vals;
+    const float *W1t;   // d_0 x ldw: row c holds the d_1 weights of input column c
+    int ldw;
+    const float *bias;  // d_1
+    float *out;         // B x ldo
+    int ldo;
+    int d1;
+    int act;
+    int vec;            // d_1 % 4 == 0 and all rows 16-byte aligned
+};
+hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream,
+                           const LaunchEvents &ev = LaunchEvents());
+
+struct SparseDwArgs {
+    const int32_t *col_start;    // d_0 + 1: segment of each column in csc_row / csc_val
+    const int32_t *chunk_start;  // d_0 + 1: first chunk of each column; [d_0] = number of chunks
+    const int32_t *csc_row;
+    const float *csc_val;
+    const float *delta;          // B x ldd
+    int ldd;
+    float *W1t;
+    int ldw;
+    float *grad_out;             // null: update W1t; else dW_1 in the flat d_1 x d_0 layout (pre-zeroed)
+    int d0, d1;
+    float lr;
+    int vec;
+};
+int sparse_chunk();
+hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
+                            long long nnz, long long B, int d0, int32_t *cnt, int32_t *col_start,
+                            int32_t *chunk_start, int32_t *cursor, int32_t *csc_row, float *csc_val,
+                            hipStream_t stream, const LaunchEvents &ev_count = LaunchEvents(),
+                            const LaunchEvents &ev_scan = LaunchEvents(),
+                            const LaunchEvents &ev_fill = LaunchEvents());
+hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStream_t stream,
+                            const LaunchEvents &ev = LaunchEvents());
+hipError_t launch_colsum(const float *delta, int ldd, long long B, int d, int splits, float *partial,
+                         hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
+hipError_t launch_transpose(const float *in, float *out, int R, int C, hipStream_t stream);
+
 }  // namespace hb

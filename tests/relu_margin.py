@@ -15,11 +15,10 @@ import hb_inputs as hi
 def _first_layer(X, W, csr):
     if csr is None:
         return X.astype(np.float64) @ W.T
+    import scipy.sparse as sp
     row_ptr, col_idx, vals = csr
-    out = np.zeros((row_ptr.size - 1, W.shape[0]))
-    rows = np.repeat(np.arange(row_ptr.size - 1), np.diff(row_ptr))
-    np.add.at(out, rows, vals.astype(np.float64)[:, None] * W.T[col_idx])
-    return out
+    Xs = sp.csr_matrix((vals.astype(np.float64), col_idx, row_ptr), shape=(row_ptr.size - 1, W.shape[1]))
+    return np.asarray(Xs @ W.T)
 
 
 def keep_relu_units_off_the_kink(dims, params, X=None, csr=None, tau=2e-6, seed=0):
