@@ -94,7 +94,8 @@ struct hb_model {
     // sparse first layer: W_1 lives transposed (d_0 x d_1); the W_1 region of d_params is
     // only a staging area for set/get/merge
     float *d_w1t = nullptr;
-    int32_t *d_col_cnt = nullptr, *d_col_start = nullptr, *d_chunk_start = nullptr, *d_cursor = nullptr;
+    int32_t *d_col_cnt = nullptr, *d_col_start = nullptr, *d_chunk_start = nullptr;
+    int32_t *d_cursor = nullptr;  // per-block column histograms / cursors of the CSC build
     int32_t *d_csc_row = nullptr;
     float *d_csc_val = nullptr;
     int64_t csc_cap = 0;
@@ -335,8 +336,8 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sb.count = m->dims[1];
             sb.stride = m->dims[1];
             sb.splits = m->b1_splits;
-            HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_col_cnt,
-                                    m->d_col_start, m->d_chunk_start, m->d_cursor, m->d_csc_row,
+            HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_cursor,
+                                    m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_csc_row,
                                     m->d_csc_val, st,
                                     prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
                                     prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
@@ -562,6 +563,8 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
                     (long long)MAX_BATCH);
     if (sparse_first_layer && dtype != HB_F32)
         return fail(HB_ERR_INVALID, "sparse_first_layer needs dtype HB_F32");
+    if (sparse_first_layer && !csc_supported(m->dims[0]))
+        return fail(HB_ERR_UNSUPPORTED, "sparse_first_layer supports d_0 <= %d columns", 150 * 1024 / 4);
     if (dtype == HB_BF16_F32MASTER)
         return fail(HB_ERR_UNSUPPORTED, "HB_BF16_F32MASTER is not implemented in this build");
 
@@ -608,7 +611,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_cnt, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_start, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 1);
-        if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, d0 + 1);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, csc_hist_elems(max_B, m->dims[0]));
     }
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss_partials, (size_t)loss_grid_blocks(max_B, m->dims[L]) + 1);
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_counter, 4);

@@ -140,12 +140,17 @@ struct SparseDwArgs {
     int vec;
 };
 int sparse_chunk();
+// Per-batch CSC (column-segmented copy of the batch's non-zeros) by a multi-block counting
+// sort; hist is scratch of csc_hist_elems(max_B, d0) int32.  Needs csc_supported(d0): the
+// column histogram of one block lives in LDS.
+bool csc_supported(int d0);
+size_t csc_hist_elems(long long max_B, int d0);
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
-                            long long nnz, long long B, int d0, int32_t *cnt, int32_t *col_start,
-                            int32_t *chunk_start, int32_t *cursor, int32_t *csc_row, float *csc_val,
-                            hipStream_t stream, const LaunchEvents &ev_count = LaunchEvents(),
+                            long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
+                            int32_t *col_start, int32_t *chunk_start, int32_t *csc_row, float *csc_val,
+                            hipStream_t stream, const LaunchEvents &ev_hist = LaunchEvents(),
                             const LaunchEvents &ev_scan = LaunchEvents(),
-                            const LaunchEvents &ev_fill = LaunchEvents());
+                            const LaunchEvents &ev_place = LaunchEvents());
 hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStream_t stream,
                             const LaunchEvents &ev = LaunchEvents());
 hipError_t launch_colsum(const float *delta, int ldd, long long B, int d, int splits, float *partial,

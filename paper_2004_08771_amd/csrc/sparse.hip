@@ -56,31 +56,66 @@ __global__ __launch_bounds__(SP_NT) void spmm_fwd_kernel(SpmmArgs a)
     }
 }
 
-// ---- per-batch CSC: count, scan, fill
-__global__ __launch_bounds__(256) void col_count_kernel(const int32_t *__restrict__ col_idx,
-                                                        long long nnz, int32_t *__restrict__ cnt)
+// ---- per-batch CSC by a multi-block counting sort (no global atomics: under a Zipf column
+// distribution thousands of non-zeros share the hottest columns, and atomics on one address
+// serialise).  Block b owns a contiguous range of rows:
+//   1. csc_hist_kernel   block-local column histogram in LDS -> hist[b][c]
+//   2. csc_colsum_kernel per column: exclusive prefix over blocks (in place) and total cnt[c]
+//   3. col_scan_kernel   exclusive scan of cnt over columns -> col_start, chunk_start
+//   4. csc_place_kernel  block b re-reads its rows; its LDS cursor of column c starts at
+//                        col_start[c] + hist[b][c]; LDS atomics hand out the positions.
+constexpr int CSC_NT = 1024;
+
+__global__ __launch_bounds__(CSC_NT) void csc_hist_kernel(const int32_t *__restrict__ row_ptr,
+                                                          const int32_t *__restrict__ col_idx,
+                                                          long long B, int rows_per_block, int d0,
+                                                          int32_t *__restrict__ hist)
 {
-    const long long step = (long long)gridDim.x * 256;
-    for (long long p = (long long)blockIdx.x * 256 + threadIdx.x; p < nnz; p += step)
-        atomicAdd(&cnt[col_idx[p]], 1);
+    extern __shared__ int32_t s_hist[];
+    for (int c = threadIdx.x; c < d0; c += CSC_NT) s_hist[c] = 0;
+    __syncthreads();
+    const long long r0 = (long long)blockIdx.x * rows_per_block;
+    const long long r1 = min(B, r0 + rows_per_block);
+    if (r0 < r1) {
+        const int beg = row_ptr[r0], end = row_ptr[r1];
+        for (int p = beg + threadIdx.x; p < end; p += CSC_NT) atomicAdd(&s_hist[col_idx[p]], 1);
+    }
+    __syncthreads();
+    int32_t *out = hist + (size_t)blockIdx.x * d0;
+    for (int c = threadIdx.x; c < d0; c += CSC_NT) out[c] = s_hist[c];
+}
+
+__global__ __launch_bounds__(256) void csc_colsum_kernel(int32_t *__restrict__ hist, int n_blocks, int d0,
+                                                         int32_t *__restrict__ cnt)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= d0) return;
+    int run = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+        const int h = hist[(size_t)b * d0 + c];
+        hist[(size_t)b * d0 + c] = run;
+        run += h;
+    }
+    cnt[c] = run;
 }
 
 // One workgroup: exclusive scans of cnt[0..n) (-> col_start) and of the chunk counts
-// ceil(cnt / CHUNK) (-> chunk_start); both get their totals at index n.  Also clears
-// cursor[] for the fill pass.
+// ceil(cnt / CHUNK) (-> chunk_start); both get their totals at index n.
 __global__ __launch_bounds__(1024) void col_scan_kernel(const int32_t *__restrict__ cnt, int n,
                                                         int32_t *__restrict__ col_start,
-                                                        int32_t *__restrict__ chunk_start,
-                                                        int32_t *__restrict__ cursor)
+                                                        int32_t *__restrict__ chunk_start)
 {
+    extern __shared__ int32_t s_cnt[];  // n entries
     __shared__ int s_a[1024], s_b[1024];
     const int tid = threadIdx.x;
+    for (int c = tid; c < n; c += 1024) s_cnt[c] = cnt[c];
+    __syncthreads();
     const int per = (n + 1023) / 1024;
     const int lo = min(n, tid * per), hi = min(n, lo + per);
     int sa = 0, sb = 0;
     for (int c = lo; c < hi; ++c) {
-        sa += cnt[c];
-        sb += (cnt[c] + CHUNK - 1) / CHUNK;
+        sa += s_cnt[c];
+        sb += (s_cnt[c] + CHUNK - 1) / CHUNK;
     }
     s_a[tid] = sa;
     s_b[tid] = sb;
@@ -95,11 +130,11 @@ __global__ __launch_bounds__(1024) void col_scan_kernel(const int32_t *__restric
     }
     int ra = s_a[tid] - sa, rb = s_b[tid] - sb;  // exclusive prefix of this thread's range
     for (int c = lo; c < hi; ++c) {
+        const int v = s_cnt[c];
         col_start[c] = ra;
         chunk_start[c] = rb;
-        cursor[c] = 0;
-        ra += cnt[c];
-        rb += (cnt[c] + CHUNK - 1) / CHUNK;
+        ra += v;
+        rb += (v + CHUNK - 1) / CHUNK;
     }
     if (tid == 1023) {
         col_start[n] = s_a[1023];
@@ -107,24 +142,30 @@ __global__ __launch_bounds__(1024) void col_scan_kernel(const int32_t *__restric
     }
 }
 
-__global__ __launch_bounds__(256) void csc_fill_kernel(const int32_t *__restrict__ row_ptr,
-                                                       const int32_t *__restrict__ col_idx,
-                                                       const float *__restrict__ vals, long long B,
-                                                       const int32_t *__restrict__ col_start,
-                                                       int32_t *__restrict__ cursor,
-                                                       int32_t *__restrict__ csc_row,
-                                                       float *__restrict__ csc_val)
+__global__ __launch_bounds__(CSC_NT) void csc_place_kernel(const int32_t *__restrict__ row_ptr,
+                                                           const int32_t *__restrict__ col_idx,
+                                                           const float *__restrict__ vals, long long B,
+                                                           int rows_per_block, int d0,
+                                                           const int32_t *__restrict__ hist,
+                                                           const int32_t *__restrict__ col_start,
+                                                           int32_t *__restrict__ csc_row,
+                                                           float *__restrict__ csc_val)
 {
+    extern __shared__ int32_t s_cur[];
+    const int32_t *mine = hist + (size_t)blockIdx.x * d0;
+    for (int c = threadIdx.x; c < d0; c += CSC_NT) s_cur[c] = col_start[c] + mine[c];
+    __syncthreads();
+    const long long r0 = (long long)blockIdx.x * rows_per_block;
+    const long long r1 = min(B, r0 + rows_per_block);
     // one wavefront per row, lanes over the row's non-zeros
-    const long long row = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
-    if (row >= B) return;
-    const int beg = row_ptr[row], end = row_ptr[row + 1];
-    for (int p = beg + lane; p < end; p += 64) {
-        const int c = col_idx[p];
-        const int pos = col_start[c] + atomicAdd(&cursor[c], 1);
-        csc_row[pos] = (int32_t)row;
-        csc_val[pos] = vals[p];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (long long row = r0 + wave; row < r1; row += CSC_NT / 64) {
+        const int beg = row_ptr[row], end = row_ptr[row + 1];
+        for (int p = beg + lane; p < end; p += 64) {
+            const int pos = atomicAdd(&s_cur[col_idx[p]], 1);
+            csc_row[pos] = (int32_t)row;
+            csc_val[pos] = vals[p];
+        }
     }
 }
 
@@ -237,29 +278,71 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream, c
 
 int sparse_chunk() { return CHUNK; }
 
-hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
-                            long long nnz, long long B, int d0, int32_t *cnt, int32_t *col_start,
-                            int32_t *chunk_start, int32_t *cursor, int32_t *csc_row, float *csc_val,
-                            hipStream_t stream, const LaunchEvents &ev_count,
-                            const LaunchEvents &ev_scan, const LaunchEvents &ev_fill)
+int csc_blocks(long long B)
 {
-    hipError_t e = launch_fill_u32(reinterpret_cast<unsigned int *>(cnt), d0 + 1, 0u, stream);
-    if (e != hipSuccess) return e;
-    if (nnz > 0) {
-        long long b = (nnz + 255) / 256;
-        if (b > 2048) b = 2048;
-        e = launch_kernel(col_count_kernel, dim3((unsigned)b), dim3(256), stream, ev_count, col_idx, nnz, cnt);
-        if (e != hipSuccess) return e;
+    long long nb = (B + 127) / 128;  // at least 128 rows per block
+    if (nb > 64) nb = 64;
+    if (nb < 1) nb = 1;
+    return (int)nb;
+}
+
+size_t csc_hist_elems(long long max_B, int d0) { return (size_t)csc_blocks(max_B) * (size_t)d0; }
+
+bool csc_supported(int d0) { return (size_t)d0 * sizeof(int32_t) <= 150 * 1024; }
+
+hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
+                            long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
+                            int32_t *col_start, int32_t *chunk_start, int32_t *csc_row, float *csc_val,
+                            hipStream_t stream, const LaunchEvents &ev_hist,
+                            const LaunchEvents &ev_scan, const LaunchEvents &ev_place)
+{
+    (void)nnz;
+    const int nb = csc_blocks(B);
+    const int rows_per_block = (int)((B + nb - 1) / nb);
+    const size_t lds = (size_t)d0 * sizeof(int32_t);
+    // more than 64 KB of dynamic LDS has to be requested per kernel
+    static size_t lds_granted = 0;
+    if (lds > 32 * 1024 && lds > lds_granted) {
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_hist_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute(reinterpret_cast<const void *>(col_scan_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (ea == hipSuccess)
+            ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_place_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (ea != hipSuccess) return ea;
+        lds_granted = lds;
     }
-    e = launch_kernel(col_scan_kernel, dim3(1), dim3(1024), stream, ev_scan,
-                      static_cast<const int32_t *>(cnt), d0, col_start, chunk_start, cursor);
+    if (ev_hist.start)
+        hipExtLaunchKernelGGL(csc_hist_kernel, dim3(nb), dim3(CSC_NT), (unsigned)lds, stream, ev_hist.start,
+                              ev_hist.stop, 0, row_ptr, col_idx, B, rows_per_block, d0, hist);
+    else
+        hipLaunchKernelGGL(csc_hist_kernel, dim3(nb), dim3(CSC_NT), lds, stream, row_ptr, col_idx, B,
+                           rows_per_block, d0, hist);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (nnz > 0) {
-        const long long blocks = (B * 64 + 255) / 256;
-        e = launch_kernel(csc_fill_kernel, dim3((unsigned)blocks), dim3(256), stream, ev_fill, row_ptr,
-                          col_idx, vals, B, static_cast<const int32_t *>(col_start), cursor, csc_row, csc_val);
-    }
-    return e;
+    e = launch_kernel(csc_colsum_kernel, dim3((unsigned)((d0 + 255) / 256)), dim3(256), stream, LaunchEvents(),
+                      hist, nb, d0, cnt);
+    if (e != hipSuccess) return e;
+    if (ev_scan.start)
+        hipExtLaunchKernelGGL(col_scan_kernel, dim3(1), dim3(1024), (unsigned)lds, stream, ev_scan.start,
+                              ev_scan.stop, 0, static_cast<const int32_t *>(cnt), d0, col_start, chunk_start);
+    else
+        hipLaunchKernelGGL(col_scan_kernel, dim3(1), dim3(1024), lds, stream,
+                           static_cast<const int32_t *>(cnt), d0, col_start, chunk_start);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (ev_place.start)
+        hipExtLaunchKernelGGL(csc_place_kernel, dim3(nb), dim3(CSC_NT), (unsigned)lds, stream, ev_place.start,
+                              ev_place.stop, 0, row_ptr, col_idx, vals, B, rows_per_block, d0,
+                              static_cast<const int32_t *>(hist), static_cast<const int32_t *>(col_start),
+                              csc_row, csc_val);
+    else
+        hipLaunchKernelGGL(csc_place_kernel, dim3(nb), dim3(CSC_NT), lds, stream, row_ptr, col_idx, vals, B,
+                           rows_per_block, d0, static_cast<const int32_t *>(hist),
+                           static_cast<const int32_t *>(col_start), csc_row, csc_val);
+    return hipGetLastError();
 }
 
 hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStream_t stream,
