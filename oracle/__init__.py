@@ -54,6 +54,8 @@ def _load():
     lib.hbo_batch_loss.argtypes = [i32p, i32, ctypes.c_int, ctypes.c_int, f64p, f64p, i32p, i64]
     lib.hbo_batch_grad.restype = f64
     lib.hbo_batch_grad.argtypes = [i32p, i32, ctypes.c_int, ctypes.c_int, f64p, f64p, i32p, i64, f64p]
+    lib.hbo_batch_grad_bf16_storage.restype = f64
+    lib.hbo_batch_grad_bf16_storage.argtypes = [i32p, i32, ctypes.c_int, ctypes.c_int, f64p, f64p, i32p, i64, f64p]
     lib.hbo_batch_grad_csr.restype = f64
     lib.hbo_batch_grad_csr.argtypes = [i32p, i32, ctypes.c_int, ctypes.c_int, f64p, i32p, i32p,
                                        f64p, i32p, i64, f64p]
@@ -120,6 +122,32 @@ def batch_grad(dims, act, loss, params, X, y):
     l = _load().hbo_batch_grad(dp, n, act, loss, _p(params, ctypes.c_double),
                                _p(X, ctypes.c_double), _p(y, ctypes.c_int32), y.size,
                                _p(g, ctypes.c_double))
+    return float(l), g
+
+
+def round_weights_bf16(dims, params):
+    """Copy of the flat parameters with every weight matrix rounded to bf16 (biases kept)."""
+    out = np.array(params, dtype=np.float64, copy=True)
+    off = 0
+    for l in range(1, len(dims)):
+        n = dims[l] * dims[l - 1]
+        out[off:off + n] = bf16_round(np.asarray(params[off:off + n], dtype=np.float32))
+        off += n + dims[l]
+    return out
+
+
+def batch_grad_bf16_storage(dims, act, loss, params, X, y):
+    """(mean loss, gradient) under the bf16-storage policy: weights and X are rounded to bf16
+    here, hidden activations and deltas inside the oracle; sums stay fp64."""
+    d, dp, n = _dims(dims)
+    pr = round_weights_bf16(dims, params)
+    Xr = _f64(bf16_round(np.asarray(X, dtype=np.float32)))
+    y = _i32(y)
+    assert pr.size == num_params(dims) and Xr.shape == (y.size, dims[0])
+    g = np.empty_like(pr)
+    l = _load().hbo_batch_grad_bf16_storage(dp, n, act, loss, _p(pr, ctypes.c_double),
+                                            _p(Xr, ctypes.c_double), _p(y, ctypes.c_int32), y.size,
+                                            _p(g, ctypes.c_double))
     return float(l), g
 
 

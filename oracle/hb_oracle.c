@@ -85,6 +85,33 @@ static int check_args(const int32_t *dims, int32_t n_dims, int act, int loss, in
     return 0;
 }
 
+/* nearest bfloat16 (ties to even) of a finite fp32 value */
+static float bf16_rne_f32(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) != 0x7f800000u) {
+        const uint32_t lower = u & 0xffffu;
+        u &= 0xffff0000u;
+        if (lower > 0x8000u || (lower == 0x8000u && (u & 0x10000u))) u += 0x10000u;
+    } else {
+        u &= 0xffff0000u; /* inf/nan: keep the top half */
+    }
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/*
+ * Storage rounding of the mixed-precision policy "bf16 activations and weights, fp32
+ * master weights and accumulation": a value that the policy keeps in bf16 between two
+ * products (a hidden activation, a delta) is the fp32 result rounded to bf16.  With
+ * store_bf16 == 0 nothing is rounded.
+ */
+static double stored(double v, int store_bf16)
+{
+    return store_bf16 ? (double)bf16_rne_f32((float)v) : v;
+}
+
 /* Section 7.1: sigmoid hidden activation; ReLU is the additional choice. */
 static double act_fn(int act, double z)
 {
@@ -105,7 +132,7 @@ static double act_deriv_from_output(int act, double a)
  * part of the loss below).
  */
 static void forward_from(const int32_t *dims, int L, int act, const double *params,
-                         double **acts, int64_t B, int first)
+                         double **acts, int64_t B, int first, int store_bf16)
 {
     for (int l = first; l <= L; ++l) {
         const int din = dims[l - 1], dout = dims[l];
@@ -118,7 +145,7 @@ static void forward_from(const int32_t *dims, int L, int act, const double *para
             for (int j = 0; j < dout; ++j) {
                 double z = b[j];
                 for (int k = 0; k < din; ++k) z += Ain[i * din + k] * W[(int64_t)j * din + k];
-                Aout[i * dout + j] = (l < L) ? act_fn(act, z) : z;
+                Aout[i * dout + j] = (l < L) ? stored(act_fn(act, z), store_bf16) : z;
             }
         }
     }
@@ -148,7 +175,7 @@ static void forward_first_csr(const int32_t *dims, int L, int act, const double 
  * batch).  Z is B x K; delta (B x K) receives d(mean loss)/dZ.  Returns the mean loss.
  */
 static double loss_and_delta(int loss, int K, const double *Z, const int32_t *y, int64_t B,
-                             double *delta)
+                             double *delta, int store_bf16)
 {
     double total = 0.0;
     for (int64_t i = 0; i < B; ++i) {
@@ -160,7 +187,7 @@ static double loss_and_delta(int loss, int K, const double *Z, const int32_t *y,
             /* dl/dz = -y * sigma(-m) */
             const double s = (m >= 0.0) ? exp(-m) / (1.0 + exp(-m)) : 1.0 / (1.0 + exp(m));
             total += li;
-            if (delta) delta[i] = -(double)y[i] * s / (double)B;
+            if (delta) delta[i] = stored(-(double)y[i] * s / (double)B, store_bf16);
         } else {
             const int c = (loss == HBO_LOSS_LOGISTIC) ? (y[i] + 1) / 2 : y[i];
             double mx = z[0];
@@ -171,7 +198,8 @@ static double loss_and_delta(int loss, int K, const double *Z, const int32_t *y,
             total += lse - z[c];
             if (delta)
                 for (int k = 0; k < K; ++k)
-                    delta[i * K + k] = (exp(z[k] - lse) - (k == c ? 1.0 : 0.0)) / (double)B;
+                    delta[i * K + k] =
+                        stored((exp(z[k] - lse) - (k == c ? 1.0 : 0.0)) / (double)B, store_bf16);
         }
     }
     return total / (double)B;
@@ -204,7 +232,7 @@ static void free_acts(double **a, int L, int from)
  */
 static void backward(const int32_t *dims, int L, int act, const double *params, double **acts,
                      double *delta_L, int64_t B, const double *X, const int32_t *row_ptr,
-                     const int32_t *col_idx, const double *vals, double *grad)
+                     const int32_t *col_idx, const double *vals, double *grad, int store_bf16)
 {
     double *delta = delta_L;
     for (int l = L; l >= 1; --l) {
@@ -245,7 +273,8 @@ static void backward(const int32_t *dims, int L, int act, const double *params, 
                 for (int k = 0; k < din; ++k) {
                     double s = 0.0;
                     for (int j = 0; j < dout; ++j) s += delta[i * dout + j] * W[(int64_t)j * din + k];
-                    prev[i * din + k] = s * act_deriv_from_output(act, Aprev[i * din + k]);
+                    prev[i * din + k] =
+                        stored(s * act_deriv_from_output(act, Aprev[i * din + k]), store_bf16);
                 }
             }
             if (delta != delta_L) free(delta);
@@ -262,7 +291,7 @@ static void backward(const int32_t *dims, int L, int act, const double *params, 
 static double loss_grad(const int32_t *dims, int32_t n_dims, int act, int loss,
                         const double *params, const double *X, const int32_t *row_ptr,
                         const int32_t *col_idx, const double *vals, const int32_t *y,
-                        int64_t B, double *grad)
+                        int64_t B, double *grad, int store_bf16)
 {
     if (check_args(dims, n_dims, act, loss, B) != 0 || !params || !y) return NAN;
     const int L = n_dims - 1;
@@ -270,16 +299,16 @@ static double loss_grad(const int32_t *dims, int32_t n_dims, int act, int loss,
     if (!acts) return NAN;
     if (X) {
         acts[0] = (double *)X;
-        forward_from(dims, L, act, params, acts, B, 1);
+        forward_from(dims, L, act, params, acts, B, 1, store_bf16);
     } else {
         forward_first_csr(dims, L, act, params, row_ptr, col_idx, vals, acts[1], B);
-        forward_from(dims, L, act, params, acts, B, 2);
+        forward_from(dims, L, act, params, acts, B, 2, store_bf16);
     }
     const int K = dims[L];
     double *delta = grad ? (double *)malloc(sizeof(double) * (size_t)B * K) : NULL;
-    const double mean_loss = loss_and_delta(loss, K, acts[L], y, B, delta);
+    const double mean_loss = loss_and_delta(loss, K, acts[L], y, B, delta, store_bf16);
     if (grad) {
-        backward(dims, L, act, params, acts, delta, B, X, row_ptr, col_idx, vals, grad);
+        backward(dims, L, act, params, acts, delta, B, X, row_ptr, col_idx, vals, grad, store_bf16);
         free(delta);
     }
     acts[0] = NULL;
@@ -293,7 +322,7 @@ double hbo_batch_loss(const int32_t *dims, int32_t n_dims, int act, int loss,
                       const double *params, const double *X, const int32_t *y, int64_t B)
 {
     if (!X) return NAN;
-    return loss_grad(dims, n_dims, act, loss, params, X, NULL, NULL, NULL, y, B, NULL);
+    return loss_grad(dims, n_dims, act, loss, params, X, NULL, NULL, NULL, y, B, NULL, 0);
 }
 
 double hbo_batch_grad(const int32_t *dims, int32_t n_dims, int act, int loss,
@@ -301,7 +330,7 @@ double hbo_batch_grad(const int32_t *dims, int32_t n_dims, int act, int loss,
                       double *grad)
 {
     if (!X || !grad) return NAN;
-    return loss_grad(dims, n_dims, act, loss, params, X, NULL, NULL, NULL, y, B, grad);
+    return loss_grad(dims, n_dims, act, loss, params, X, NULL, NULL, NULL, y, B, grad, 0);
 }
 
 double hbo_batch_grad_csr(const int32_t *dims, int32_t n_dims, int act, int loss,
@@ -309,7 +338,22 @@ double hbo_batch_grad_csr(const int32_t *dims, int32_t n_dims, int act, int loss
                           const double *vals, const int32_t *y, int64_t B, double *grad)
 {
     if (!row_ptr || !col_idx || !vals || !grad) return NAN;
-    return loss_grad(dims, n_dims, act, loss, params, NULL, row_ptr, col_idx, vals, y, B, grad);
+    return loss_grad(dims, n_dims, act, loss, params, NULL, row_ptr, col_idx, vals, y, B, grad, 0);
+}
+
+/*
+ * The same gradient under the mixed-precision storage policy (bf16 activations / deltas,
+ * fp32 accumulation): the caller passes X and the weight matrices already rounded to bf16
+ * (biases and all sums stay unrounded); hidden activations and deltas are rounded to bf16
+ * where the policy stores them.  The update itself is applied by the caller to the fp32
+ * master weights with hbo_sgd_update.
+ */
+double hbo_batch_grad_bf16_storage(const int32_t *dims, int32_t n_dims, int act, int loss,
+                                   const double *params, const double *X, const int32_t *y,
+                                   int64_t B, double *grad)
+{
+    if (!X || !grad) return NAN;
+    return loss_grad(dims, n_dims, act, loss, params, X, NULL, NULL, NULL, y, B, grad, 1);
 }
 
 /* Eq. (3): W <- W - eta * g, over the flat vector */

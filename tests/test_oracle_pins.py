@@ -445,3 +445,28 @@ def test_invalid_arguments_return_nan():
     assert math.isnan(oracle.batch_loss((4, 3), SIG, 9, params, X, y))
     p3, X3, y3 = _rand_problem((4, 3), LOGI, 2, seed=0)
     assert math.isnan(oracle.batch_loss((4, 3), SIG, LOGI, p3, X3, y3))  # logistic needs d_L <= 2
+
+
+def test_bf16_storage_gradient_is_the_plain_gradient_up_to_storage_rounding():
+    """The mixed-precision variant differs from the plain oracle only by bf16 storage
+    rounding of hidden activations and deltas: the two agree to about 2^-8 on a smooth
+    (sigmoid) net but are not identical."""
+    dims = (32, 24, 24, 6)
+    params, X, y = _rand_problem(dims, CE, 40, seed=31, bias_scale=0.2)
+    pr = oracle.round_weights_bf16(dims, params.astype(np.float32))
+    Xr = oracle.bf16_round(X.astype(np.float32)).astype(np.float64)
+    l0, g0 = oracle.batch_grad(dims, SIG, CE, pr, Xr, y)
+    l1, g1 = oracle.batch_grad_bf16_storage(dims, SIG, CE, params.astype(np.float32), X, y)
+    assert abs(l1 - l0) / l0 < 1e-2
+    assert np.linalg.norm(g1 - g0) / np.linalg.norm(g0) < 1e-2
+    assert not np.array_equal(g1, g0)
+    # no hidden layer: the only stored value is delta_L, so dW = delta_L^T X and
+    # db = delta_L^T 1 move by at most the bf16 rounding of delta_L
+    dims0 = (16, 4)
+    p0, X0, y0 = _rand_problem(dims0, CE, 8, seed=32)
+    l_a, ga = oracle.batch_grad_bf16_storage(dims0, SIG, CE, p0.astype(np.float32), X0, y0)
+    pr0 = oracle.round_weights_bf16(dims0, p0.astype(np.float32))
+    Xr0 = oracle.bf16_round(X0.astype(np.float32)).astype(np.float64)
+    l_b, gb = oracle.batch_grad(dims0, SIG, CE, pr0, Xr0, y0)
+    assert l_a == l_b                       # the loss sees no stored value
+    assert np.linalg.norm(ga - gb) / np.linalg.norm(gb) < 2.0 ** -8
