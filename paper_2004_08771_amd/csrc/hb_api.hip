@@ -91,6 +91,14 @@ struct hb_model {
     float *h_loss = nullptr;             // pinned
     float *d_stage = nullptr;            // P floats: staging copy of the host model
 
+    // bf16 mode: bf16 copies of every weight matrix (row-major and transposed), bf16
+    // activations / deltas in both layouts; acts[L] holds the fp32 logits
+    std::vector<int> ld8;                       // d_l rounded up to 8
+    std::vector<void *> shadow, shadow_t;       // [1..L]
+    std::vector<void *> act_bf, act_t;          // [1..L-1] / [0..L-1]
+    void *delta_bf[2] = {nullptr, nullptr};
+    void *delta_t[2] = {nullptr, nullptr};
+
     // sparse first layer: W_1 lives transposed (d_0 x d_1); the W_1 region of d_params is
     // only a staging area for set/get/merge
     float *d_w1t = nullptr;
@@ -415,6 +423,136 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
     return HB_OK;
 }
 
+int refresh_shadows(hb_model *m)
+{
+    if (m->dtype != HB_BF16_F32MASTER) return HB_OK;
+    for (int l = 1; l <= m->L; ++l)
+        HB_HIP(launch_shadow(m->d_params + m->w_off[l], m->dims[l], m->dims[l - 1], m->shadow[l],
+                             m->ld8[l - 1], m->shadow_t[l], m->ld8[l], m->stream));
+    return HB_OK;
+}
+
+// The step in bf16 mode.  X is dense B x d_0 bf16.
+int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float lr, StepMode mode,
+                  float *d_grad_flat, float *d_loss_user)
+{
+    const int L = m->L;
+    const int Bi = (int)B;
+    const long long ldB = round_up(Bi, 8);
+    hipStream_t st = m->stream;
+    const bool back = (mode != MODE_LOSS);
+
+    if (back)  // X^T for dW_1 = D_1^T X
+        HB_HIP(launch_transpose_bf16(X, m->dims[0], m->act_t[0], ldB, Bi, m->dims[0], st,
+                                     prof_begin(m, HB_K_OTHER, 1, 0, 0, 0, 0.0, 4.0 * B * m->dims[0])));
+    for (int l = 1; l <= L; ++l) {
+        GemmBf16Args g = {};
+        g.A = (l == 1) ? X : m->act_bf[l - 1];
+        g.lda = (l == 1) ? m->dims[0] : m->ld8[l - 1];
+        g.B = m->shadow[l];
+        g.ldb = m->ld8[l - 1];
+        g.M = Bi;
+        g.N = m->dims[l];
+        g.K = m->dims[l - 1];
+        g.a_vec = aligned16(g.A) && (g.lda % 8 == 0);
+        g.b_vec = 1;
+        g.bias = m->d_params + m->b_off[l];
+        if (l < L) {
+            g.act = m->act;
+            g.C_bf16 = m->act_bf[l];
+            g.ldcb = m->ld8[l];
+            if (back) {
+                g.Ct_bf16 = m->act_t[l];
+                g.ldct = ldB;
+            }
+        } else {
+            g.act = ACT_NONE;
+            g.C_f32 = m->acts[L];
+            g.ldc = m->ld[L];
+        }
+        HB_HIP(launch_gemm_bf16(GEMM_FWD, g, st,
+                                prof_begin(m, HB_K_FWD_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                           2.0 * ((double)g.M * g.K + (double)g.N * g.K + 2.0 * g.M * g.N))));
+    }
+
+    LossArgs la = {};
+    la.Z = m->acts[L];
+    la.ldz = m->ld[L];
+    la.y = y;
+    la.B = B;
+    la.K = m->dims[L];
+    la.loss = m->loss;
+    la.delta = back ? m->delta_bf[L & 1] : nullptr;
+    la.ldd = m->ld8[L];
+    la.delta_bf16 = 1;
+    la.block_partials = m->d_loss_partials;
+    la.counter = m->d_counter;
+    la.loss_out = m->d_loss;
+    la.loss_out2 = d_loss_user;
+    HB_HIP(launch_loss(la, st, prof_begin(m, HB_K_LOSS, 0, 0, 0, 0, 0.0, B * (4.0 * la.K + 2.0 * la.K + 4.0))));
+    if (!back) return HB_OK;
+    HB_HIP(launch_transpose_bf16(m->delta_bf[L & 1], m->ld8[L], m->delta_t[L & 1], ldB, Bi, m->dims[L], st,
+                                 prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * B * m->dims[L])));
+
+    const bool grad_mode = (mode == MODE_GRAD);
+    for (int l = L; l >= 1; --l) {
+        if (l > 1) {
+            GemmBf16Args g = {};
+            g.A = m->delta_bf[l & 1];
+            g.lda = m->ld8[l];
+            g.B = m->shadow_t[l];
+            g.ldb = m->ld8[l];
+            g.M = Bi;
+            g.N = m->dims[l - 1];
+            g.K = m->dims[l];
+            g.a_vec = 1;
+            g.b_vec = 1;
+            g.aux = m->act_bf[l - 1];
+            g.ldaux = m->ld8[l - 1];
+            g.act = m->act;
+            g.C_bf16 = m->delta_bf[(l - 1) & 1];
+            g.ldcb = m->ld8[l - 1];
+            g.Ct_bf16 = m->delta_t[(l - 1) & 1];
+            g.ldct = ldB;
+            HB_HIP(launch_gemm_bf16(GEMM_DA, g, st,
+                                    prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                               2.0 * ((double)g.M * g.K + (double)g.N * g.K + 3.0 * g.M * g.N))));
+        }
+        GemmBf16Args g = {};
+        g.A = m->delta_t[l & 1];
+        g.lda = ldB;
+        g.B = m->act_t[l - 1];
+        g.ldb = ldB;
+        g.M = m->dims[l];
+        g.N = m->dims[l - 1];
+        g.K = Bi;
+        g.a_vec = 1;
+        g.b_vec = 1;
+        g.act = ACT_NONE;
+        g.lr = lr;
+        g.ldc = m->dims[l - 1];
+        if (grad_mode) {
+            g.write_grad = 1;
+            g.C_f32 = d_grad_flat + m->w_off[l];
+        } else {
+            g.C_f32 = m->d_params + m->w_off[l];
+            g.C_bf16 = m->shadow[l];
+            g.ldcb = m->ld8[l - 1];
+            g.Ct_bf16 = m->shadow_t[l];
+            g.ldct = m->ld8[l];
+        }
+        HB_HIP(launch_gemm_bf16(GEMM_DW, g, st,
+                                prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                           2.0 * ((double)g.M * g.K + (double)g.N * g.K) +
+                                               (grad_mode ? 4.0 : 12.0) * g.M * g.N)));
+        HB_HIP(launch_rowsum_bias(m->delta_t[l & 1], ldB, m->dims[l], B, m->d_params + m->b_off[l],
+                                  grad_mode ? d_grad_flat + m->b_off[l] : nullptr, lr, st,
+                                  prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)B * m->dims[l],
+                                             2.0 * B * m->dims[l])));
+    }
+    return HB_OK;
+}
+
 int validate_batch_call(hb_model *m, const void *a, const int32_t *dy, int64_t B, bool want_sparse)
 {
     int rc = check_handle(m, true);
@@ -565,8 +703,6 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         return fail(HB_ERR_INVALID, "sparse_first_layer needs dtype HB_F32");
     if (sparse_first_layer && !csc_supported(m->dims[0]))
         return fail(HB_ERR_UNSUPPORTED, "sparse_first_layer supports d_0 <= %d columns", 150 * 1024 / 4);
-    if (dtype == HB_BF16_F32MASTER)
-        return fail(HB_ERR_UNSUPPORTED, "HB_BF16_F32MASTER is not implemented in this build");
 
     int dev = -1;
     HB_HIP(hipGetDevice(&dev));
@@ -591,20 +727,60 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
 
     rc = dev_alloc(m, &m->d_params, (size_t)m->P);
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_stage, (size_t)m->P);
-    for (int l = 1; l <= L && rc == HB_OK; ++l) {
-        rc = dev_alloc(m, &m->acts[l], (size_t)max_B * m->ld[l]);
-        if (rc != HB_OK) break;
-        if (l == 1 && m->sparse) {
-            m->b1_splits = (int)((max_B + 127) / 128 < MAX_SPLITS ? (max_B + 127) / 128 : MAX_SPLITS);
-            m->cap_splits[l] = m->b1_splits;
-            rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
-            continue;
+    if (dtype == HB_F32) {
+        for (int l = 1; l <= L && rc == HB_OK; ++l) {
+            rc = dev_alloc(m, &m->acts[l], (size_t)max_B * m->ld[l]);
+            if (rc != HB_OK) break;
+            if (l == 1 && m->sparse) {
+                m->b1_splits = (int)((max_B + 127) / 128 < MAX_SPLITS ? (max_B + 127) / 128 : MAX_SPLITS);
+                m->cap_splits[l] = m->b1_splits;
+                rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
+                continue;
+            }
+            m->cap_splits[l] = gemm_f32_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, MAX_SPLITS);
+            rc = dev_alloc(m, &m->partial_w[l], (size_t)m->cap_splits[l] * m->dims[l] * m->dims[l - 1]);
+            if (rc == HB_OK) rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
         }
-        m->cap_splits[l] = gemm_f32_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, MAX_SPLITS);
-        rc = dev_alloc(m, &m->partial_w[l], (size_t)m->cap_splits[l] * m->dims[l] * m->dims[l - 1]);
-        if (rc == HB_OK) rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
+        for (int i = 0; i < 2 && rc == HB_OK; ++i) rc = dev_alloc(m, &m->delta[i], (size_t)max_B * max_ld);
+    } else {
+        // bf16 mode: 2-byte buffers in both layouts; only the logits stay fp32
+        const size_t ldB = (size_t)round_up((int)max_B, 8);
+        m->ld8.assign(L + 1, 0);
+        m->shadow.assign(L + 1, nullptr);
+        m->shadow_t.assign(L + 1, nullptr);
+        m->act_bf.assign(L + 1, nullptr);
+        m->act_t.assign(L + 1, nullptr);
+        int max_ld8 = 8, max_d = 1;
+        for (int l = 0; l <= L; ++l) {
+            m->ld8[l] = round_up(m->dims[l], 8);
+            if (l >= 1 && m->ld8[l] > max_ld8) max_ld8 = m->ld8[l];
+            if (l >= 1 && m->dims[l] > max_d) max_d = m->dims[l];
+        }
+        rc = dev_alloc(m, &m->acts[L], (size_t)max_B * m->ld[L]);
+        for (int l = 1; l <= L && rc == HB_OK; ++l) {
+            unsigned short *p = nullptr;
+            rc = dev_alloc(m, &p, (size_t)m->dims[l] * m->ld8[l - 1]);
+            m->shadow[l] = p;
+            if (rc == HB_OK) rc = dev_alloc(m, &p, (size_t)m->dims[l - 1] * m->ld8[l]);
+            m->shadow_t[l] = p;
+        }
+        for (int l = 0; l < L && rc == HB_OK; ++l) {
+            unsigned short *p = nullptr;
+            if (l >= 1) {
+                rc = dev_alloc(m, &p, (size_t)max_B * m->ld8[l]);
+                m->act_bf[l] = p;
+            }
+            if (rc == HB_OK) rc = dev_alloc(m, &p, (size_t)m->dims[l] * ldB);
+            m->act_t[l] = p;
+        }
+        for (int i = 0; i < 2 && rc == HB_OK; ++i) {
+            unsigned short *p = nullptr;
+            rc = dev_alloc(m, &p, (size_t)max_B * max_ld8);
+            m->delta_bf[i] = p;
+            if (rc == HB_OK) rc = dev_alloc(m, &p, (size_t)max_d * ldB);
+            m->delta_t[i] = p;
+        }
     }
-    for (int i = 0; i < 2 && rc == HB_OK; ++i) rc = dev_alloc(m, &m->delta[i], (size_t)max_B * max_ld);
     if (m->sparse && rc == HB_OK) {
         const size_t d0 = (size_t)m->dims[0];
         rc = dev_alloc(m, &m->d_w1t, d0 * m->dims[1]);
@@ -626,6 +802,14 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
     if (e == hipSuccess && m->sparse)
         e = hipMemsetAsync(m->d_w1t, 0, sizeof(float) * (size_t)m->dims[0] * m->dims[1], m->stream);
     if (e == hipSuccess) e = launch_fill_u32(m->d_counter, 4, 0u, m->stream);
+    if (e == hipSuccess && dtype == HB_BF16_F32MASTER) {
+        // zero weights -> zero bf16 copies (padding columns included)
+        for (int l = 1; l <= L && e == hipSuccess; ++l) {
+            e = hipMemsetAsync(m->shadow[l], 0, 2 * (size_t)m->dims[l] * m->ld8[l - 1], m->stream);
+            if (e == hipSuccess)
+                e = hipMemsetAsync(m->shadow_t[l], 0, 2 * (size_t)m->dims[l - 1] * m->ld8[l], m->stream);
+        }
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(m->stream);
     if (e != hipSuccess) {
         release_device(m);
@@ -652,6 +836,7 @@ int hb_model_set_params(hb_model *m, const float *host_flat)
     HB_HIP(hipMemcpyAsync(m->d_params, host_flat, sizeof(float) * (size_t)m->P, hipMemcpyHostToDevice,
                           m->stream));
     rc = sync_w1t_from_flat(m);
+    if (rc == HB_OK) rc = refresh_shadows(m);
     if (rc != HB_OK) return rc;
     HB_HIP(hipStreamSynchronize(m->stream));
     return HB_OK;
@@ -676,6 +861,7 @@ int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t 
     int rc = validate_batch_call(m, dX, dy, B, false);
     if (rc != HB_OK) return rc;
     if (!std::isfinite(lr)) return fail(HB_ERR_INVALID, "lr is not finite");
+    if (m->dtype == HB_BF16_F32MASTER) return run_step_bf16(m, dX, dy, B, lr, MODE_STEP, nullptr, d_loss);
     Input in;
     in.X = static_cast<const float *>(dX);
     return run_step(m, in, dy, B, lr, MODE_STEP, nullptr, d_loss);
@@ -697,7 +883,8 @@ float hb_batch_grad(hb_model *m, const void *dX, const int32_t *dy, int64_t B, f
     if (!d_grad_flat) return fail_nan("d_grad_flat is NULL");
     Input in;
     in.X = static_cast<const float *>(dX);
-    if (run_step(m, in, dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr) != HB_OK)
+    if ((m->dtype == HB_BF16_F32MASTER ? run_step_bf16(m, dX, dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr)
+                                       : run_step(m, in, dy, B, 0.f, MODE_GRAD, d_grad_flat, nullptr)) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
     float out;
     if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
@@ -710,7 +897,8 @@ float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B)
         return std::numeric_limits<float>::quiet_NaN();
     Input in;
     in.X = static_cast<const float *>(dX);
-    if (run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, nullptr) != HB_OK)
+    if ((m->dtype == HB_BF16_F32MASTER ? run_step_bf16(m, dX, dy, B, 0.f, MODE_LOSS, nullptr, nullptr)
+                                       : run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, nullptr)) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
     float out;
     if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
@@ -767,6 +955,7 @@ int hb_model_merge(hb_model *m, float *host_model, float weight)
     if (weight == 0.f) {  // replica <- global: the deep copy of the ExecuteWork handler
         HB_HIP(hipMemcpyAsync(m->d_params, host_model, bytes, hipMemcpyHostToDevice, m->stream));
         rc = sync_w1t_from_flat(m);
+        if (rc == HB_OK) rc = refresh_shadows(m);
         if (rc != HB_OK) return rc;
     } else if (weight == 1.f) {  // global <- replica: the push after the update
         rc = sync_flat_from_w1t(m);
@@ -779,6 +968,7 @@ int hb_model_merge(hb_model *m, float *host_model, float weight)
         HB_HIP(launch_merge(m->d_params, m->d_stage, m->P, weight, m->stream));
         HB_HIP(hipMemcpyAsync(host_model, m->d_stage, bytes, hipMemcpyDeviceToHost, m->stream));
         rc = sync_w1t_from_flat(m);
+        if (rc == HB_OK) rc = refresh_shadows(m);
         if (rc != HB_OK) return rc;
     }
     HB_HIP(hipStreamSynchronize(m->stream));

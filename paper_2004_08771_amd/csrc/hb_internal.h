@@ -62,6 +62,43 @@ hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *split
 // (so that the caller can size the partial buffers).
 int gemm_f32_dw_splits(int M, int N, int K, int max_splits);
 
+// ---------------------------------------------------------------- bf16 MFMA GEMM (NT only)
+// C[M x N] = sum_k A[m*lda + k] * B[n*ldb + k], bf16 operands, fp32 accumulation.  Outputs
+// (each optional): fp32 C, bf16 C, and a transposed bf16 copy Ct[n*ldct + m].
+//   FWD: C = act(acc + bias)                    DA: C = acc * f'(aux)
+//   DW : C_f32 is the fp32 master weight: C_f32 -= lr * acc, and C / Ct are its bf16 copies
+//        (write_grad: C_f32 = acc, nothing else is written)
+struct GemmBf16Args {
+    const void *A;
+    const void *B;
+    int M, N, K;
+    long long lda, ldb;
+    int a_vec, b_vec;      // 16-byte vector loads are legal (ld % 8 == 0, base 16-byte aligned)
+    void *C_f32;
+    long long ldc;
+    void *C_bf16;
+    long long ldcb;
+    void *Ct_bf16;
+    long long ldct;
+    const float *bias;
+    const void *aux;
+    long long ldaux;
+    int act;
+    int write_grad;
+    float lr;
+    int tiles_m, tiles_n;
+};
+hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream,
+                            const LaunchEvents &ev = LaunchEvents());
+hipError_t launch_transpose_bf16(const void *in, long long ldi, void *out, long long ldo, int R, int C,
+                                 hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
+// bf16 copies (row-major and transposed) of an fp32 matrix W [R x C]
+hipError_t launch_shadow(const float *W, int R, int C, void *shadow, long long lds_, void *shadow_t,
+                         long long ldt, hipStream_t stream);
+// g[j] = sum_b Dt[j*ld + b];  bias[j] -= lr g[j]  (grad == null)  or  grad[j] = g[j]
+hipError_t launch_rowsum_bias(const void *Dt, long long ld, int d, long long B, float *bias, float *grad,
+                              float lr, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
+
 // ---------------------------------------------------------------- loss / delta
 struct LossArgs {
     const float *Z;   // B x ldz logits (fp32)

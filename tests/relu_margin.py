@@ -21,17 +21,24 @@ def _first_layer(X, W, csr):
     return np.asarray(Xs @ W.T)
 
 
-def keep_relu_units_off_the_kink(dims, params, X=None, csr=None, tau=2e-6, seed=0):
+def keep_relu_units_off_the_kink(dims, params, X=None, csr=None, tau=2e-6, seed=0, bf16_storage=False):
     """Returns a copy of the flat fp32 `params` whose hidden pre-activations on this batch
-    all satisfy |z| >= tau.  X is the dense batch, or csr = (row_ptr, col_idx, vals)."""
+    all satisfy |z| >= tau.  X is the dense batch, or csr = (row_ptr, col_idx, vals).
+    With bf16_storage the pre-activations are those of the mixed-precision policy (weights,
+    X and hidden activations rounded to bf16), the ones the bf16 kernels decide on."""
+    import oracle
+    rnd = (lambda a: oracle.bf16_round(np.asarray(a, dtype=np.float32)).astype(np.float64)) \
+        if bf16_storage else (lambda a: np.asarray(a, dtype=np.float64))
     rng = np.random.default_rng(seed)
     params = np.array(params, dtype=np.float32, copy=True)
+    if X is not None:
+        X = rnd(X)
     offs = hi.param_offsets(dims)
     L = len(dims) - 1
     a = None
     for l in range(1, L):
         wo, bo = offs[l - 1]
-        W = params[wo:wo + dims[l] * dims[l - 1]].reshape(dims[l], dims[l - 1]).astype(np.float64)
+        W = rnd(params[wo:wo + dims[l] * dims[l - 1]].reshape(dims[l], dims[l - 1]))
         lin = _first_layer(X, W, csr) if l == 1 else a @ W.T
         for _ in range(100):
             z = lin + params[bo:bo + dims[l]].astype(np.float64)
@@ -42,5 +49,5 @@ def keep_relu_units_off_the_kink(dims, params, X=None, csr=None, tau=2e-6, seed=
             params[bo + cols] = (params[bo + cols] + shift).astype(np.float32)
         else:
             raise RuntimeError("could not move every ReLU unit off the kink")
-        a = np.maximum(z, 0.0)
+        a = rnd(np.maximum(z, 0.0))
     return params

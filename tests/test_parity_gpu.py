@@ -414,3 +414,104 @@ def test_dense_and_csr_calls_are_not_interchangeable():
         sparse.batch_step_csr(rp, rp, x, 4 * 8 + 1, y, 4, 0.1)  # nnz > B * d_0
     dense.destroy()
     sparse.destroy()
+
+
+# ---------------------------------------------------------------- bf16 mode
+TOL_BF16 = 2e-2        # the task's bound: loss and parameters after one step
+TOL_BF16_GRAD = 5e-3   # gradient against the oracle that rounds what the policy stores in bf16
+
+
+def check_bf16_case(dims, act, loss, params, X, y, lr):
+    """Contract: loss and parameters after one step within 2e-2 of the fp64 oracle run on the
+    bf16-rounded inputs (no intermediate rounding).  Diagnostic: the gradient against the
+    oracle's bf16-storage variant (same rounding points as the kernels), much tighter."""
+    import paper_2004_08771_amd as hb
+    torch = _torch()
+    B = X.shape[0]
+    if act == hi.ACT_RELU:
+        params = keep_relu_units_off_the_kink(dims, params, X, bf16_storage=True)
+    Wr = oracle.round_weights_bf16(dims, params)
+    Xr = oracle.bf16_round(X)
+    l_ref, g_plain = oracle.batch_grad(dims, act, loss, Wr, Xr, y)
+    p_ref = oracle.sgd_update(params, g_plain, lr)          # update applies to the fp32 master
+    l_st, g_st = oracle.batch_grad_bf16_storage(dims, act, loss, params, X, y)
+
+    m = hb.Model(dims, act, loss).configure(hb.HB_BF16_F32MASTER, B)
+    m.set_params(params)
+    dX = torch.from_numpy(X).cuda().to(torch.bfloat16)
+    assert np.array_equal(dX.float().cpu().numpy(), Xr)      # torch's RNE == the oracle's
+    dy = torch.from_numpy(y).cuda()
+    dg = torch.full((params.size,), float("nan"), dtype=torch.float32, device="cuda")
+    lg = m.batch_grad(dX, dy, B, dg)
+    before = np.empty_like(params)
+    m.get_params(before)
+    np.testing.assert_array_equal(before, params)
+    lf = m.batch_loss(dX, dy, B)
+    ls = m.batch_step(dX, dy, B, lr)
+    after = np.empty_like(params)
+    m.get_params(after)
+    # the bf16 weight copies were refreshed by the step: a second loss uses the new weights
+    l_after = m.batch_loss(dX, dy, B)
+    m.destroy()
+    g = dg.cpu().numpy()
+
+    for name, v in (("batch_grad", lg), ("batch_loss", lf), ("batch_step", ls)):
+        assert abs(v - l_ref) <= TOL_BF16 * abs(l_ref), f"{name} loss {v} vs {l_ref}"
+        assert abs(v - l_st) <= 1e-3 * abs(l_st), f"{name} loss {v} vs bf16-storage oracle {l_st}"
+    assert_close_per_tensor(dims, after, p_ref, TOL_BF16, "parameters after one step")
+    assert_close_per_tensor(dims, g, g_st, TOL_BF16_GRAD, "gradient (bf16-storage oracle)", abs_floor=1e-7)
+    l_after_ref = oracle.batch_loss(dims, act, loss, oracle.round_weights_bf16(dims, p_ref.astype(np.float32)),
+                                    Xr, y)
+    assert abs(l_after - l_after_ref) <= TOL_BF16 * abs(l_after_ref)
+    assert l_after != ls
+
+
+@pytest.mark.parametrize("dims,act,loss,B", [
+    ((64, 128, 128, 10), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 300),
+    ((64, 128, 128, 10), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 129),
+    ((40, 72, 1000), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 50),       # widths not multiples of 8
+    ((33, 17, 5, 2), hi.ACT_RELU, hi.LOSS_LOGISTIC, 77),
+    ((48, 1), hi.ACT_SIGMOID, hi.LOSS_LOGISTIC, 200),
+    ((200, 264, 136, 7), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 1),
+])
+def test_bf16_small_shapes_match_oracle(dims, act, loss, B):
+    params, X, y = _problem(dims, loss, B, seed=500 + B + len(dims), bias_scale=0.2)
+    check_bf16_case(dims, act, loss, params, X, y, lr=0.1)
+
+
+def test_config5_bf16_reduced_batch():
+    cfg = hi.CONFIGS[5]
+    B = 160                                   # one full 128-row tile and a ragged tail
+    X, y = hi.make_dense_dataset(5, B)
+    params = hi.make_params(5, bias_scale=0.02)
+    check_bf16_case(cfg.dims, cfg.activation, cfg.loss, params, X, y, lr=cfg.lr)
+
+
+def test_config5_bf16_full_batch_equals_mean_of_sub_batches():
+    """At the full size (B = 16384) the oracle is out of reach; the mean over the batch is
+    linear, and 1/B scaling by a power of two commutes with bf16 rounding, so the gradient of
+    the whole batch must equal the mean of the gradients of its four quarters (each a shape
+    already checked against the oracle) up to fp32 summation order."""
+    import paper_2004_08771_amd as hb
+    torch = _torch()
+    cfg = hi.CONFIGS[5]
+    B, parts = cfg.batch, 4
+    X, y = hi.make_dense_dataset(5, B)
+    params = hi.make_params(5, bias_scale=0.02)
+    m = hb.Model(cfg.dims, cfg.activation, cfg.loss).configure(hb.HB_BF16_F32MASTER, B)
+    m.set_params(params)
+    dX = torch.from_numpy(X).cuda().to(torch.bfloat16)
+    dy = torch.from_numpy(y).cuda()
+    g_full = torch.empty(params.size, dtype=torch.float32, device="cuda")
+    l_full = m.batch_grad(dX, dy, B, g_full)
+    g_sum = torch.zeros_like(g_full)
+    g_part = torch.empty_like(g_full)
+    l_sum, q = 0.0, B // parts
+    for i in range(parts):
+        l_sum += m.batch_grad(dX[i * q:(i + 1) * q], dy[i * q:(i + 1) * q], q, g_part)
+        g_sum += g_part
+    m.destroy()
+    assert abs(l_full - l_sum / parts) <= 1e-5 * abs(l_full)
+    assert abs(l_full - np.log(1000.0)) < 0.5          # random labels, small weights
+    assert_close_per_tensor(cfg.dims, g_full.cpu().numpy(), (g_sum / parts).cpu().numpy(), 2e-3,
+                            "full-batch gradient vs mean of quarter-batch gradients", abs_floor=1e-9)
