@@ -29,14 +29,17 @@ def _tensors(dims, flat):
 
 
 def assert_close_per_tensor(dims, got, ref, tol, what, abs_floor=0.0):
+    errs = {}
     for name, sl in _tensors(dims, ref):
         r, g = ref[sl].astype(np.float64), got[sl].astype(np.float64)
         denom = max(np.linalg.norm(r), abs_floor)
         if denom == 0.0:
             assert np.linalg.norm(g) == 0.0, f"{what} {name}: reference is zero, got {np.linalg.norm(g)}"
             continue
-        err = np.linalg.norm(g - r) / denom
-        assert err <= tol, f"{what} {name}: relative L2 error {err:.3e} > {tol}"
+        errs[name] = np.linalg.norm(g - r) / denom
+    bad = {k: f"{v:.3e}" for k, v in errs.items() if not v <= tol}
+    assert not bad, f"{what}: relative L2 error above {tol} for {bad}; all: " + \
+        ", ".join(f"{k}={v:.2e}" for k, v in errs.items())
 
 
 def make_model(dims, act, loss, max_B, params):
@@ -429,7 +432,9 @@ def check_bf16_case(dims, act, loss, params, X, y, lr):
     torch = _torch()
     B = X.shape[0]
     if act == hi.ACT_RELU:
-        params = keep_relu_units_off_the_kink(dims, params, X, bf16_storage=True)
+        # a stored activation that lands on the other side of a bf16 rounding boundary (fp32 vs
+        # fp64 sums) moves the next layer's z by ~1e-4 of its scale: keep the kink further away
+        params = keep_relu_units_off_the_kink(dims, params, X, tau=1e-3, bf16_storage=True)
     Wr = oracle.round_weights_bf16(dims, params)
     Xr = oracle.bf16_round(X)
     l_ref, g_plain = oracle.batch_grad(dims, act, loss, Wr, Xr, y)
