@@ -14,6 +14,8 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
+
 namespace hb {
 namespace {
 
@@ -74,6 +76,38 @@ struct Tile {
         }
     }
 
+    // The same tile without any guard: legal when the tile lies inside the matrix in both
+    // directions.  vec: 16-byte loads, else four 4-byte loads (rows that are not 16-byte
+    // aligned, e.g. the caller's X with d_0 = 54).
+    static __device__ __forceinline__ void load_fast(v4f (&reg)[VPT], const float *__restrict__ P,
+                                                     int ld, int row0, int k0, bool vec, int tid)
+    {
+#pragma unroll
+        for (int v = 0; v < VPT; ++v) {
+            const int idx = tid + v * NT;
+            if (VECS % NT == 0 || idx < VECS) {
+                const float *p;
+                if (KMAJ) {
+                    const int kq = idx % (BK / 4), r = idx / (BK / 4);
+                    p = P + (size_t)(row0 + r) * ld + k0 + kq * 4;
+                } else {
+                    const int mq = idx % (ROWS / 4), kk = idx / (ROWS / 4);
+                    p = P + (size_t)(k0 + kk) * ld + row0 + mq * 4;
+                }
+                if (vec) {
+                    reg[v] = *reinterpret_cast<const v4f *>(p);
+                } else {
+                    v4f x;
+                    x.x = p[0];
+                    x.y = p[1];
+                    x.z = p[2];
+                    x.w = p[3];
+                    reg[v] = x;
+                }
+            }
+        }
+    }
+
     // registers -> LDS (same element <-> thread mapping as load)
     static __device__ __forceinline__ void store(float *S, const v4f (&reg)[VPT], int tid)
     {
@@ -110,7 +144,10 @@ struct Tile {
     }
 };
 
-__device__ __forceinline__ float sigmoidf_fast(float z) { return 1.0f / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float sigmoidf_fast(float z)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-z));  // v_rcp_f32: 1 ulp, no division sequence
+}
 
 template <int BM, int BN, int BK, int WAVES_M, bool A_KMAJ, bool B_KMAJ, int KIND>
 __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
@@ -144,63 +181,94 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
     const float *__restrict__ A = static_cast<const float *>(a.A);
     const float *__restrict__ Bm = static_cast<const float *>(a.B);
 
-    v16f acc[TM][TN];
+    // With a single 32 x 32 block per wavefront every MFMA would depend on the one before
+    // it; two accumulators per block, fed by alternating k-groups, give two independent chains.
+    constexpr int CHAINS = (TM * TN == 1) ? 2 : 1;
+    v16f acc[TM][TN][CHAINS];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int c = 0; c < CHAINS; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][c][v] = 0.f;
+
+    // tiles that lie inside the matrix are loaded without guards (uniform per workgroup)
+    const bool a_in = (m0 + BM <= a.M), b_in = (n0 + BN <= a.N);
 
     float colsum = 0.f;  // DW only: column sums of the A tile (bias gradient)
     const bool do_colsum = (KIND == GEMM_DW) && a.colsum != nullptr && tile_n == 0;
 
+    // Software pipeline, three levels deep:
+    //   global -> registers : the loads of tile kt+2 are issued at the top of iteration kt
+    //   registers -> LDS    : just before that, tile kt+1 (loaded during iteration kt-1) is
+    //                         written to the idle LDS stage, long before anyone needs it
+    //   LDS -> fragments    : the fragments of k-group g+1 are read while the MFMAs of group g
+    //                         run; the first group of tile kt+1 is read right after the
+    //                         barrier, under the last MFMAs of tile kt.
+    // One barrier per k-tile; nothing but the barrier itself sits between two MFMA groups.
+    constexpr int G = BK / 8;
+    static_assert(G % 2 == 0, "fragment slots alternate with the k-group parity");
     v4f ra[TA::VPT], rb[TB::VPT];
+    auto load_tile = [&](int t) {
+        const int k0 = kbeg + t * BK;
+        const bool kfull = (k0 + BK <= kend);
+        if (a_in && kfull) TA::load_fast(ra, A, a.lda, m0, k0, a.a_vec != 0, tid);
+        else TA::load(ra, A, a.lda, m0, a.M, k0, kend, a.a_vec != 0, tid);
+        if (b_in && kfull) TB::load_fast(rb, Bm, a.ldb, n0, k0, a.b_vec != 0, tid);
+        else TB::load(rb, Bm, a.ldb, n0, a.N, k0, kend, a.b_vec != 0, tid);
+    };
+    v4f fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int slot, const float *As, const float *Bs, int g) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[slot][i] = TA::frag(As, wm * WM + i * 32 + r, g, h);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[slot][j] = TB::frag(Bs, wn * WN + j * 32 + r, g, h);
+    };
+    auto mfma_group = [&](int slot, int chain) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j][chain % CHAINS] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                        fa[slot][i][s], fb[slot][j][s], acc[i][j][chain % CHAINS], 0, 0, 0);
+    };
+
     if (nk > 0) {
-        TA::load(ra, A, a.lda, m0, a.M, kbeg, kend, a.a_vec != 0, tid);
-        TB::load(rb, Bm, a.ldb, n0, a.N, kbeg, kend, a.b_vec != 0, tid);
+        load_tile(0);
         TA::store(smem, ra, tid);
         TB::store(smem + TA::FLOATS, rb, tid);
+        if (nk > 1) load_tile(1);
     }
     __syncthreads();
+    if (nk > 0) read_frags(0, smem, smem + TA::FLOATS, 0);
 
     for (int kt = 0; kt < nk; ++kt) {
         const float *As = smem + (kt & 1) * STAGE;
         const float *Bs = As + TA::FLOATS;
-        const bool more = (kt + 1 < nk);
-        if (more) {
-            const int k0 = kbeg + (kt + 1) * BK;
-            TA::load(ra, A, a.lda, m0, a.M, k0, kend, a.a_vec != 0, tid);
-            TB::load(rb, Bm, a.ldb, n0, a.N, k0, kend, a.b_vec != 0, tid);
+        float *An = smem + ((kt + 1) & 1) * STAGE;
+        if (kt + 1 < nk) {  // tile kt+1 -> the stage nobody reads during this iteration
+            TA::store(An, ra, tid);
+            TB::store(An + TA::FLOATS, rb, tid);
         }
-#pragma unroll
-        for (int g = 0; g < BK / 8; ++g) {
-            v4f fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = TA::frag(As, wm * WM + i * 32 + r, g, h);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = TB::frag(Bs, wn * WN + j * 32 + r, g, h);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][s], fb[j][s],
-                                                                         acc[i][j], 0, 0, 0);
-        }
+        if (kt + 2 < nk) load_tile(kt + 2);
         if (KIND == GEMM_DW && !A_KMAJ) {
             if (do_colsum && tid < BM) {
 #pragma unroll
                 for (int k = 0; k < BK; ++k) colsum += As[k * TA::LD + tid];
             }
         }
-        if (more) {
-            float *An = smem + ((kt + 1) & 1) * STAGE;
-            TA::store(An, ra, tid);
-            TB::store(An + TA::FLOATS, rb, tid);
+#pragma unroll
+        for (int g = 0; g + 1 < G; ++g) {
+            read_frags((g + 1) & 1, As, Bs, g + 1);
+            mfma_group(g & 1, g);
         }
-        __syncthreads();
+        __syncthreads();  // tile kt fully read by everyone, tile kt+1 fully written
+        if (kt + 1 < nk) read_frags(0, An, An + TA::FLOATS, 0);
+        mfma_group((G - 1) & 1, G - 1);
     }
 
     // ---- epilogue.  acc[i][j][v] is C(row, col) with
@@ -218,7 +286,8 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
                 if (m < a.M && n_ok) {
-                    float x = acc[i][j][v];
+                    float x = acc[i][j][0][v];
+                    if (CHAINS == 2) x += acc[i][j][CHAINS - 1][v];
                     if (KIND == GEMM_FWD) {
                         x += bias;
                         if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
@@ -246,38 +315,44 @@ int env_int(const char *name, int dflt)
 }
 
 // Workgroups wanted per launch: two per compute unit on a 256-CU device.
-constexpr int TARGET_WGS = 512;
+int target_wgs()
+{
+    static const int v = env_int("HB_GEMM_WGS", 512);  // tuning aid
+    return v;
+}
 
 struct Shape {
-    int bm, bn;
+    int bm, bn, bk;
 };
+
+// Tile shapes that are instantiated.  HB_GEMM_TILE = 1..5 forces one (tuning aid).
+constexpr Shape SHAPES[] = {{64, 64, 16}, {64, 64, 32}, {128, 64, 16}, {128, 64, 32}, {128, 128, 16}};
+constexpr int K_CHUNK_ALIGN = 32;  // split-K slices are multiples of every BK above
 
 Shape pick_shape(GemmKind kind, int M, int N)
 {
-    static const int forced = env_int("HB_GEMM_TILE", 0);  // 1: 128x64, 2: 64x64 (tuning aid)
-    if (forced == 1) return {128, 64};
-    if (forced == 2) return {64, 64};
-    (void)kind;
-    const long long t128 = (long long)((M + 127) / 128) * ((N + 63) / 64);
-    if (t128 >= 2 * TARGET_WGS) return {128, 64};
-    return {64, 64};
+    static const int forced = env_int("HB_GEMM_TILE", 0);
+    if (forced >= 1 && forced <= 5) return SHAPES[forced - 1];
+    // measured on 4096 x 512 x 512 (MI355X): forward / backward-data are fastest with
+    // 64 x 64 x 32 tiles (two workgroups per CU), the split-K weight gradient with 128 x 64 x 32
+    (void)N;
+    if (kind == GEMM_DW && M >= 128) return SHAPES[3];
+    return SHAPES[1];
 }
 
-constexpr int BK_F32 = 16;
-
-template <int BM, int BN, int WAVES_M>
+template <int BM, int BN, int BK, int WAVES_M>
 hipError_t launch_shape(GemmKind kind, const GemmArgs &a, dim3 grid, hipStream_t stream,
                         const LaunchEvents &ev)
 {
     switch (kind) {
     case GEMM_FWD:
-        return launch_kernel(gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, true, GEMM_FWD>, grid,
+        return launch_kernel(gemm_f32_kernel<BM, BN, BK, WAVES_M, true, true, GEMM_FWD>, grid,
                              dim3(NT), stream, ev, a);
     case GEMM_DA:
-        return launch_kernel(gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, true, false, GEMM_DA>, grid,
+        return launch_kernel(gemm_f32_kernel<BM, BN, BK, WAVES_M, true, false, GEMM_DA>, grid,
                              dim3(NT), stream, ev, a);
     case GEMM_DW:
-        return launch_kernel(gemm_f32_kernel<BM, BN, BK_F32, WAVES_M, false, false, GEMM_DW>, grid,
+        return launch_kernel(gemm_f32_kernel<BM, BN, BK, WAVES_M, false, false, GEMM_DW>, grid,
                              dim3(NT), stream, ev, a);
     }
     return hipErrorInvalidValue;
@@ -291,12 +366,12 @@ struct SplitPlan {
 // enough slices to fill the device, each a multiple of BK long, none empty.
 SplitPlan plan_splits(int tiles, int K, int max_splits)
 {
-    int s = (TARGET_WGS + tiles - 1) / tiles;
-    const int by_k = (K + 4 * BK_F32 - 1) / (4 * BK_F32);  // at least 4 k-tiles per slice
+    int s = (target_wgs() + tiles - 1) / tiles;
+    const int by_k = (K + 4 * K_CHUNK_ALIGN - 1) / (4 * K_CHUNK_ALIGN);  // slices of >= 128
     if (s > by_k) s = by_k;
     if (s > max_splits) s = max_splits;
     if (s < 1) s = 1;
-    const int chunk = ((K + s - 1) / s + BK_F32 - 1) / BK_F32 * BK_F32;
+    const int chunk = ((K + s - 1) / s + K_CHUNK_ALIGN - 1) / K_CHUNK_ALIGN * K_CHUNK_ALIGN;
     return {(K + chunk - 1) / chunk, chunk};
 }
 
@@ -318,14 +393,17 @@ hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *split
     a.tiles_n = (a.N + sh.bn - 1) / sh.bn;
     const long long tiles = (long long)a.tiles_m * a.tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    SplitPlan sp = {1, (a.K + BK_F32 - 1) / BK_F32 * BK_F32};
+    SplitPlan sp = {1, (a.K + K_CHUNK_ALIGN - 1) / K_CHUNK_ALIGN * K_CHUNK_ALIGN};
     if (kind == GEMM_DW) sp = plan_splits((int)tiles, a.K, max_splits);
     a.splits = sp.splits;
     a.k_chunk = sp.chunk;
     if (splits_out) *splits_out = sp.splits;
     const dim3 grid((unsigned)tiles, (unsigned)sp.splits, 1);
-    if (sh.bm == 128) return launch_shape<128, 64, 2>(kind, a, grid, stream, ev);
-    return launch_shape<64, 64, 2>(kind, a, grid, stream, ev);
+    if (sh.bm == 64 && sh.bk == 16) return launch_shape<64, 64, 16, 2>(kind, a, grid, stream, ev);
+    if (sh.bm == 64 && sh.bk == 32) return launch_shape<64, 64, 32, 2>(kind, a, grid, stream, ev);
+    if (sh.bn == 64 && sh.bk == 16) return launch_shape<128, 64, 16, 2>(kind, a, grid, stream, ev);
+    if (sh.bn == 64 && sh.bk == 32) return launch_shape<128, 64, 32, 2>(kind, a, grid, stream, ev);
+    return launch_shape<128, 128, 16, 2>(kind, a, grid, stream, ev);
 }
 
 }  // namespace hb
