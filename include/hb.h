@@ -174,7 +174,8 @@ enum {
     HB_K_UPDATE = 4,     /* W <- W - lr * sum of partials, all tensors      (Eq. (3)) */
     HB_K_SPMM_FWD = 5,   /* CSR first layer, forward */
     HB_K_SPARSE_DW = 6,  /* CSR first layer, gradient + update of the touched columns */
-    HB_K_OTHER = 7
+    HB_K_OTHER = 7,
+    HB_K_OUT_LAYER = 8   /* narrow output layer: forward + loss + delta + its gradients, fused */
 };
 typedef struct hb_kernel_stat {
     int32_t kind;            /* HB_K_* */

@@ -81,9 +81,10 @@ __global__ __launch_bounds__(LOSS_NT) void loss_kernel(LossArgs a)
         }
     }
 
-    // block sum of row_loss (fixed order)
+    // block sum of row_loss in a fixed order; the block partials are added up by whoever
+    // consumes the loss next on the stream (the update kernel or loss_finalize_kernel), so no
+    // fence, ticket or atomic is needed here
     __shared__ float red[LOSS_NT];
-    __shared__ bool is_last;
     red[tid] = row_loss;
     __syncthreads();
 #pragma unroll
@@ -91,33 +92,33 @@ __global__ __launch_bounds__(LOSS_NT) void loss_kernel(LossArgs a)
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) {
-        a.block_partials[blockIdx.x] = red[0];
-        __threadfence();
-        const unsigned int ticket = atomicAdd(a.counter, 1u);
-        is_last = (ticket == gridDim.x - 1);
-    }
+    if (tid == 0) a.block_partials[blockIdx.x] = red[0];
+}
+
+// mean loss = (sum of the block partials, in index order per thread then a fixed tree) / B
+__device__ __forceinline__ void loss_finalize(const LossFinalize &f, double *dred /* 256 */)
+{
+    const int tid = threadIdx.x;
+    double s = 0.0;
+    for (int i = tid; i < f.n; i += 256) s += (double)f.partials[i];
+    dred[tid] = s;
     __syncthreads();
-    if (is_last) {
-        __threadfence();
-        double s = 0.0;
-        for (unsigned int i = tid; i < gridDim.x; i += LOSS_NT)
-            s += (double)__hip_atomic_load(&a.block_partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __shared__ double dred[LOSS_NT];
-        dred[tid] = s;
-        __syncthreads();
 #pragma unroll
-        for (int st = LOSS_NT / 2; st > 0; st >>= 1) {
-            if (tid < st) dred[tid] += dred[tid + st];
-            __syncthreads();
-        }
-        if (tid == 0) {
-            const float mean = (float)(dred[0] / (double)a.B);
-            a.loss_out[0] = mean;
-            if (a.loss_out2) a.loss_out2[0] = mean;
-            *a.counter = 0u;  // ready for the next launch on this stream
-        }
+    for (int st = 128; st > 0; st >>= 1) {
+        if (tid < st) dred[tid] += dred[tid + st];
+        __syncthreads();
     }
+    if (tid == 0) {
+        const float mean = (float)(dred[0] / (double)f.B);
+        f.out[0] = mean;
+        if (f.out2) f.out2[0] = mean;
+    }
+}
+
+__global__ __launch_bounds__(256) void loss_finalize_kernel(LossFinalize f)
+{
+    __shared__ double dred[256];
+    loss_finalize(f, dred);
 }
 
 int loss_group(int K)
@@ -130,51 +131,84 @@ int loss_group(int K)
 // ---------------------------------------------------------------- update
 constexpr int UPD_NT = 256;
 
-__global__ __launch_bounds__(UPD_NT) void update_kernel(UpdateArgs a)
+// Lanes per element that share the sum over the splits: enough that no lane adds more
+// than 8 partials (a long serial chain of dependent-latency loads is what made this kernel
+// slow), at most 64.
+__host__ __device__ inline int split_lanes(int splits)
 {
-    const UpdateSeg &sg = a.seg[blockIdx.y];
-    const long long n = sg.count;
-    const long long stride = sg.stride;
-    const float *__restrict__ part = sg.partial;
-    const bool vec_ok = ((n & 3) == 0) && ((stride & 3) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(part) & 15) == 0) &&
-                        ((reinterpret_cast<uintptr_t>(a.write_grad ? sg.grad_out : sg.param) & 15) == 0);
-    const long long step = (long long)gridDim.x * UPD_NT;
-    if (vec_ok) {
-        const long long n4 = n >> 2;
-        for (long long i = (long long)blockIdx.x * UPD_NT + threadIdx.x; i < n4; i += step) {
-            float4 g = reinterpret_cast<const float4 *>(part)[i];
-            for (int s = 1; s < sg.splits; ++s) {
-                const float4 t = reinterpret_cast<const float4 *>(part + s * stride)[i];
-                g.x += t.x; g.y += t.y; g.z += t.z; g.w += t.w;
+    int t = 1;
+    while (t < 64 && t * 8 < splits) t <<= 1;
+    return t;
+}
+
+__device__ __forceinline__ void vadd(float4 &g, const float4 &w) { g.x += w.x; g.y += w.y; g.z += w.z; g.w += w.w; }
+__device__ __forceinline__ void vadd(float &g, const float &w) { g += w; }
+__device__ __forceinline__ void vaxpy(float4 &p, float lr, const float4 &g)
+{
+    p.x -= lr * g.x; p.y -= lr * g.y; p.z -= lr * g.z; p.w -= lr * g.w;
+}
+__device__ __forceinline__ void vaxpy(float &p, float lr, const float &g) { p -= lr * g; }
+
+// One segment, elements of type V (float4 when everything is 16-byte aligned, else float).
+// T lanes per element: lane t adds splits t, t+T, ... (in that order), the T sums meet in
+// LDS and are added in lane order.  Adjacent lanes hold adjacent elements of the same split.
+template <typename V>
+__device__ __forceinline__ void update_segment(const UpdateSeg &sg, long long nv, long long stride_v, float lr,
+                                               int write_grad, V *sred)
+{
+    const V *__restrict__ part = reinterpret_cast<const V *>(sg.partial);
+    const int T = split_lanes(sg.splits);
+    const int EPB = UPD_NT / T;  // elements per block
+    const int e_local = threadIdx.x % EPB, t = threadIdx.x / EPB;
+    for (long long e0 = (long long)blockIdx.x * EPB; e0 < nv; e0 += (long long)gridDim.x * EPB) {
+        const long long i = e0 + e_local;
+        V g = V();
+        if (i < nv) {
+            V v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int s = t + u * T;
+                v[u] = V();
+                if (s < sg.splits) v[u] = part[s * stride_v + i];
             }
-            if (a.write_grad) {
-                reinterpret_cast<float4 *>(sg.grad_out)[i] = g;
-            } else {
-                float4 w = reinterpret_cast<float4 *>(sg.param)[i];
-                w.x -= a.lr * g.x; w.y -= a.lr * g.y; w.z -= a.lr * g.z; w.w -= a.lr * g.w;
-                reinterpret_cast<float4 *>(sg.param)[i] = w;
-                if (sg.shadow) {
-                    ushort4 b;
-                    b.x = f32_to_bf16_rne(w.x); b.y = f32_to_bf16_rne(w.y);
-                    b.z = f32_to_bf16_rne(w.z); b.w = f32_to_bf16_rne(w.w);
-                    reinterpret_cast<ushort4 *>(sg.shadow)[i] = b;
-                }
-            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) vadd(g, v[u]);
+            for (int s = t + 8 * T; s < sg.splits; s += T) vadd(g, part[s * stride_v + i]);  // splits > 512
         }
-    } else {
-        for (long long i = (long long)blockIdx.x * UPD_NT + threadIdx.x; i < n; i += step) {
-            float g = part[i];
-            for (int s = 1; s < sg.splits; ++s) g += part[s * stride + i];
-            if (a.write_grad) {
-                sg.grad_out[i] = g;
+        if (T > 1) {
+            sred[threadIdx.x] = g;
+            __syncthreads();
+            if (t == 0)
+                for (int q = 1; q < T; ++q) vadd(g, sred[q * EPB + e_local]);
+            __syncthreads();
+        }
+        if (t == 0 && i < nv) {
+            if (write_grad) {
+                reinterpret_cast<V *>(sg.grad_out)[i] = g;
             } else {
-                const float w = sg.param[i] - a.lr * g;
-                sg.param[i] = w;
-                if (sg.shadow) static_cast<unsigned short *>(sg.shadow)[i] = f32_to_bf16_rne(w);
+                V w = reinterpret_cast<V *>(sg.param)[i];
+                vaxpy(w, lr, g);
+                reinterpret_cast<V *>(sg.param)[i] = w;
             }
         }
     }
+}
+
+__global__ __launch_bounds__(UPD_NT) void update_kernel(UpdateArgs a)
+{
+    __shared__ double dred[256];
+    __shared__ float4 sred[UPD_NT];
+    if ((int)blockIdx.y == a.n_seg) {  // the extra row of the grid finishes the loss
+        if (blockIdx.x == 0) loss_finalize(a.fin, dred);
+        return;
+    }
+    const UpdateSeg &sg = a.seg[blockIdx.y];
+    const long long n = sg.count;
+    const bool vec_ok = ((n & 3) == 0) && ((sg.stride & 3) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(sg.partial) & 15) == 0) &&
+                        ((reinterpret_cast<uintptr_t>(a.write_grad ? sg.grad_out : sg.param) & 15) == 0);
+    if (vec_ok) update_segment<float4>(sg, n >> 2, sg.stride >> 2, a.lr, a.write_grad, sred);
+    else update_segment<float>(sg, n, sg.stride, a.lr, a.write_grad, reinterpret_cast<float *>(sred));
 }
 
 __global__ __launch_bounds__(256) void merge_kernel(float *__restrict__ D, float *__restrict__ H,
@@ -220,14 +254,22 @@ hipError_t launch_loss(const LossArgs &a, hipStream_t stream, const LaunchEvents
 
 hipError_t launch_update(const UpdateArgs &a, hipStream_t stream, const LaunchEvents &ev)
 {
-    if (a.n_seg <= 0) return hipSuccess;
-    long long mx = 0;
-    for (int i = 0; i < a.n_seg; ++i) mx = a.seg[i].count > mx ? a.seg[i].count : mx;
-    long long bx = (mx / 4 + UPD_NT - 1) / UPD_NT;
-    if (bx < 1) bx = 1;
-    if (bx > 2048) bx = 2048;
-    return launch_kernel(update_kernel, dim3((unsigned)bx, (unsigned)a.n_seg, 1), dim3(UPD_NT), stream,
-                         ev, a);
+    const int extra = a.fin.n > 0 ? 1 : 0;
+    if (a.n_seg <= 0 && !extra) return hipSuccess;
+    long long bx = 1;
+    for (int i = 0; i < a.n_seg; ++i) {  // blocks the largest segment wants (float4 elements)
+        const int epb = UPD_NT / split_lanes(a.seg[i].splits);
+        const long long b = ((a.seg[i].count + 3) / 4 + epb - 1) / epb;
+        if (b > bx) bx = b;
+    }
+    if (bx > 1024) bx = 1024;
+    return launch_kernel(update_kernel, dim3((unsigned)bx, (unsigned)(a.n_seg + extra), 1), dim3(UPD_NT),
+                         stream, ev, a);
+}
+
+hipError_t launch_loss_finalize(const LossFinalize &f, hipStream_t stream, const LaunchEvents &ev)
+{
+    return launch_kernel(loss_finalize_kernel, dim3(1), dim3(256), stream, ev, f);
 }
 
 hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t stream)

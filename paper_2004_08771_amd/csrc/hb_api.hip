@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <new>
@@ -82,11 +83,11 @@ struct hb_model {
     float *d_params = nullptr;           // flat layout, fp32 (master) weights
     std::vector<int> ld;                 // leading dimension of the activation of layer l
     std::vector<float *> acts;           // [1..L]: max_B x ld[l]
-    float *delta[2] = {nullptr, nullptr};
+    std::vector<float *> delta;          // [1..L]: d(loss)/dZ_l, max_B x ld[l] (one buffer per layer)
     std::vector<float *> partial_w, partial_b;  // [1..L] split-K gradient partials
     std::vector<int> cap_splits;
+    int out_rows = 0;                    // rows per block of the fused output-layer kernel (0: not used)
     float *d_loss_partials = nullptr;
-    unsigned int *d_counter = nullptr;
     float *d_loss = nullptr;
     float *h_loss = nullptr;             // pinned
     float *d_stage = nullptr;            // P floats: staging copy of the host model
@@ -137,6 +138,7 @@ int dev_alloc(hb_model *m, T **out, size_t count)
 
 void release_device(hb_model *m)
 {
+
     for (auto &r : m->prof) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -245,8 +247,13 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
     hipStream_t st = m->stream;
     const float *X = in.X;
 
+    // narrow output layers (d_L <= 16) are handled by one fused kernel: forward, loss, D_L,
+    // D_{L-1} and the dW_L / db_L partials from a single read of A_{L-1}
+    const bool fused_out = m->out_rows > 0 && aligned16(m->d_params + m->w_off[L]);
+    const int L_gemm = fused_out ? L - 1 : L;
+
     // ---- forward, Eq. (1): A_l = f(A_{l-1} W_l^T + b_l); the last layer keeps raw scores
-    for (int l = 1; l <= L; ++l) {
+    for (int l = 1; l <= L_gemm; ++l) {
         if (l == 1 && m->sparse) {
             SpmmArgs sp = {};
             sp.row_ptr = in.row_ptr;
@@ -286,6 +293,44 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
                                           gemm_bytes(g.M, g.N, g.K, g.N))));
     }
 
+    // the kernel that computes the loss leaves one partial sum per block; the update kernel
+    // (or, when there is none, a one-block kernel) turns them into the mean
+    LossFinalize fin = {};
+    fin.partials = m->d_loss_partials;
+    fin.B = B;
+    fin.out = m->d_loss;
+    fin.out2 = d_loss_user;
+    int out_blocks = 0;
+    if (fused_out) {
+        OutLayerArgs o = {};
+        o.A = m->acts[L - 1];
+        o.lda = m->ld[L - 1];
+        o.W = m->d_params + m->w_off[L];
+        o.bias = m->d_params + m->b_off[L];
+        o.y = y;
+        o.B = B;
+        o.d = m->dims[L - 1];
+        o.K = m->dims[L];
+        o.loss = m->loss;
+        o.act = m->act;
+        o.backward = (mode != MODE_LOSS) ? 1 : 0;
+        o.Dprev = m->delta[L - 1];
+        o.ldp = m->ld[L - 1];
+        o.dW_partial = m->partial_w[L];
+        o.db_partial = m->partial_b[L];
+        o.block_partials = m->d_loss_partials;
+        const int rows = out_layer_rows_for_batch(o.d, o.K, B);
+        out_blocks = (int)((B + rows - 1) / rows);
+        const double flops = (o.backward ? 6.0 : 2.0) * B * o.d * o.K;
+        const double bytes = 4.0 * B * o.d * (o.backward ? 2.0 : 1.0) + 4.0 * B;
+        HB_HIP(launch_out_layer(o, st, prof_begin(m, HB_K_OUT_LAYER, L, B, o.K, o.d, flops, bytes)));
+        fin.n = out_blocks;
+        if (mode == MODE_LOSS) {
+            HB_HIP(launch_loss_finalize(fin, st));
+            return HB_OK;
+        }
+    }
+
     // ---- loss and output delta (Section 7.1)
     LossArgs la = {};
     la.Z = m->acts[L];
@@ -294,30 +339,53 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
     la.B = B;
     la.K = m->dims[L];
     la.loss = m->loss;
-    la.delta = (mode == MODE_LOSS) ? nullptr : m->delta[L & 1];
+    la.delta = (mode == MODE_LOSS) ? nullptr : m->delta[L];
     la.ldd = m->ld[L];
     la.delta_bf16 = 0;
     la.block_partials = m->d_loss_partials;
-    la.counter = m->d_counter;
-    la.loss_out = m->d_loss;
-    la.loss_out2 = d_loss_user;
-    HB_HIP(launch_loss(la, st, prof_begin(m, HB_K_LOSS, 0, 0, 0, 0, 0.0,
-                                          4.0 * B * (la.K * (la.delta ? 2.0 : 1.0) + 1.0))));
-    if (mode == MODE_LOSS) return HB_OK;
+    if (!fused_out) {
+        HB_HIP(launch_loss(la, st, prof_begin(m, HB_K_LOSS, 0, 0, 0, 0, 0.0,
+                                              4.0 * B * (la.K * (la.delta ? 2.0 : 1.0) + 1.0))));
+        fin.n = loss_grid_blocks(B, la.K);
+        if (mode == MODE_LOSS) {
+            HB_HIP(launch_loss_finalize(fin, st));
+            return HB_OK;
+        }
+    }
 
-    // ---- backward, Eq. (2), with the weights the forward pass used
+    // ---- backward, Eq. (2), with the weights the forward pass used.  (Running the
+    // weight-gradient products on a second stream next to the backward-data chain was
+    // measured and dropped: the two kernels slow each other down by as much as they overlap.)
     UpdateArgs ua = {};
     ua.lr = lr;
     ua.write_grad = (mode == MODE_GRAD) ? 1 : 0;
-    for (int l = L; l >= 1; --l) {
-        const float *delta_l = m->delta[l & 1];
+    ua.fin = fin;
+    hipStream_t sw_stream = st;
+    if (fused_out) {  // layer L's gradient partials came out of the fused kernel, one per row block
+        UpdateSeg &sw = ua.seg[ua.n_seg++];
+        sw.param = m->d_params + m->w_off[L];
+        sw.grad_out = d_grad_flat ? d_grad_flat + m->w_off[L] : nullptr;
+        sw.partial = m->partial_w[L];
+        sw.count = (long long)m->dims[L] * m->dims[L - 1];
+        sw.stride = sw.count;
+        sw.splits = out_blocks;
+        UpdateSeg &sb = ua.seg[ua.n_seg++];
+        sb.param = m->d_params + m->b_off[L];
+        sb.grad_out = d_grad_flat ? d_grad_flat + m->b_off[L] : nullptr;
+        sb.partial = m->partial_b[L];
+        sb.count = m->dims[L];
+        sb.stride = m->dims[L];
+        sb.splits = out_blocks;
+    }
+    for (int l = L_gemm; l >= 1; --l) {
+        const float *delta_l = m->delta[l];
         if (l > 1) {
             GemmArgs g = {};
             g.A = delta_l;
             g.lda = m->ld[l];
             g.B = m->d_params + m->w_off[l];
             g.ldb = m->dims[l - 1];
-            g.C = m->delta[(l - 1) & 1];
+            g.C = m->delta[l - 1];
             g.ldc = m->ld[l - 1];
             g.M = Bi;
             g.N = m->dims[l - 1];
@@ -334,7 +402,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
         if (l == 1 && m->sparse) {
             // db_1: column sums of delta_1; dW_1: column-segmented sums over the non-zeros,
             // applied to W1t directly (only columns that occur in the batch are touched)
-            HB_HIP(launch_colsum(delta_l, m->ld[1], B, m->dims[1], m->b1_splits, m->partial_b[1], st,
+            HB_HIP(launch_colsum(delta_l, m->ld[1], B, m->dims[1], m->b1_splits, m->partial_b[1], sw_stream,
                                  prof_begin(m, HB_K_OTHER, 1, 0, 0, 0, (double)B * m->dims[1],
                                             4.0 * B * m->dims[1])));
             UpdateSeg &sb = ua.seg[ua.n_seg++];
@@ -346,7 +414,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sb.splits = m->b1_splits;
             HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_cursor,
                                     m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_csc_row,
-                                    m->d_csc_val, st,
+                                    m->d_csc_val, sw_stream,
                                     prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
                                     prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
                                     prof_begin(m, HB_K_OTHER, 4, 0, 0, 0, 0.0, 16.0 * in.nnz)));
@@ -365,7 +433,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sd.vec = (m->dims[1] % 4 == 0);
             if (mode == MODE_GRAD) {
                 sd.grad_out = d_grad_flat + m->w_off[1];
-                HB_HIP(hipMemsetAsync(sd.grad_out, 0, sizeof(float) * (size_t)m->dims[1] * m->dims[0], st));
+                HB_HIP(hipMemsetAsync(sd.grad_out, 0, sizeof(float) * (size_t)m->dims[1] * m->dims[0], sw_stream));
             }
             // chunks <= nnz / CHUNK + (number of distinct columns) <= nnz / CHUNK + min(d_0, nnz)
             const long long max_chunks = in.nnz / sparse_chunk() + (in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
@@ -373,7 +441,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             // delta_1 once, the CSC arrays, and a read + write of each touched weight row (bounded
             // by min(nnz, d_0) rows)
             const double touched = (double)(in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
-            HB_HIP(launch_sparse_dw(sd, max_chunks, st,
+            HB_HIP(launch_sparse_dw(sd, max_chunks, sw_stream,
                                     prof_begin(m, HB_K_SPARSE_DW, 1, m->dims[1], m->dims[0], in.nnz,
                                                2.0 * in.nnz * m->dims[1],
                                                4.0 * B * m->dims[1] + 8.0 * in.nnz +
@@ -396,7 +464,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
         g.colsum = m->partial_b[l];
         g.act = ACT_NONE;
         int splits = 1;
-        HB_HIP(launch_gemm_f32(GEMM_DW, g, m->cap_splits[l], &splits, st,
+        HB_HIP(launch_gemm_f32(GEMM_DW, g, m->cap_splits[l], &splits, sw_stream,
                                prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
                                           gemm_bytes(g.M, g.N, g.K, g.M))));
 
@@ -486,10 +554,9 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
     la.ldd = m->ld8[L];
     la.delta_bf16 = 1;
     la.block_partials = m->d_loss_partials;
-    la.counter = m->d_counter;
-    la.loss_out = m->d_loss;
-    la.loss_out2 = d_loss_user;
     HB_HIP(launch_loss(la, st, prof_begin(m, HB_K_LOSS, 0, 0, 0, 0, 0.0, B * (4.0 * la.K + 2.0 * la.K + 4.0))));
+    LossFinalize fin = {m->d_loss_partials, loss_grid_blocks(B, la.K), B, m->d_loss, d_loss_user};
+    HB_HIP(launch_loss_finalize(fin, st));
     if (!back) return HB_OK;
     HB_HIP(launch_transpose_bf16(m->delta_bf[L & 1], m->ld8[L], m->delta_t[L & 1], ldB, Bi, m->dims[L], st,
                                  prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * B * m->dims[L])));
@@ -718,10 +785,8 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
     m->partial_w.assign(L + 1, nullptr);
     m->partial_b.assign(L + 1, nullptr);
     m->cap_splits.assign(L + 1, 1);
-    int max_ld = 4;
     for (int l = 0; l <= L; ++l) {
         m->ld[l] = round_up(m->dims[l], 4);
-        if (l >= 1 && m->ld[l] > max_ld) max_ld = m->ld[l];
     }
     m->ld[0] = m->dims[0];  // X is the caller's, unpadded
 
@@ -738,10 +803,19 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
                 continue;
             }
             m->cap_splits[l] = gemm_f32_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, MAX_SPLITS);
+            if (l == L && L >= 2) {
+                m->out_rows = out_layer_rows(m->dims[L - 1], m->dims[L]);
+                if (m->out_rows > 0) {  // one partial per row block of the fused kernel
+                    const int rmin = out_layer_min_rows();
+                    const int blocks = (int)((max_B + rmin - 1) / rmin);
+                    if (blocks > m->cap_splits[l]) m->cap_splits[l] = blocks;
+                }
+            }
             rc = dev_alloc(m, &m->partial_w[l], (size_t)m->cap_splits[l] * m->dims[l] * m->dims[l - 1]);
             if (rc == HB_OK) rc = dev_alloc(m, &m->partial_b[l], (size_t)m->cap_splits[l] * m->dims[l]);
         }
-        for (int i = 0; i < 2 && rc == HB_OK; ++i) rc = dev_alloc(m, &m->delta[i], (size_t)max_B * max_ld);
+        m->delta.assign(L + 1, nullptr);
+        for (int l = 1; l <= L && rc == HB_OK; ++l) rc = dev_alloc(m, &m->delta[l], (size_t)max_B * m->ld[l]);
     } else {
         // bf16 mode: 2-byte buffers in both layouts; only the logits stay fp32
         const size_t ldB = (size_t)round_up((int)max_B, 8);
@@ -789,8 +863,13 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, csc_hist_elems(max_B, m->dims[0]));
     }
-    if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss_partials, (size_t)loss_grid_blocks(max_B, m->dims[L]) + 1);
-    if (rc == HB_OK) rc = dev_alloc(m, &m->d_counter, 4);
+    {
+        // one loss partial per block of whichever kernel computes the loss
+        size_t nblk = (size_t)loss_grid_blocks(max_B, m->dims[L]);
+        if (m->out_rows > 0 && (size_t)((max_B + out_layer_min_rows() - 1) / out_layer_min_rows()) > nblk)
+            nblk = (size_t)((max_B + out_layer_min_rows() - 1) / out_layer_min_rows());
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss_partials, nblk + 1);
+    }
     if (rc == HB_OK) rc = dev_alloc(m, &m->d_loss, 4);
     if (rc != HB_OK) { release_device(m); return rc; }
     hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&m->h_loss), 64, hipHostMallocDefault);
@@ -801,7 +880,6 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
     e = hipMemsetAsync(m->d_params, 0, sizeof(float) * (size_t)m->P, m->stream);
     if (e == hipSuccess && m->sparse)
         e = hipMemsetAsync(m->d_w1t, 0, sizeof(float) * (size_t)m->dims[0] * m->dims[1], m->stream);
-    if (e == hipSuccess) e = launch_fill_u32(m->d_counter, 4, 0u, m->stream);
     if (e == hipSuccess && dtype == HB_BF16_F32MASTER) {
         // zero weights -> zero bf16 copies (padding columns included)
         for (int l = 1; l <= L && e == hipSuccess; ++l) {

@@ -110,13 +110,47 @@ struct LossArgs {
     void *delta;      // B x ldd, receives d(mean loss)/dZ (fp32, or bf16 when delta_bf16); may be null
     int ldd;
     int delta_bf16;
-    float *block_partials;   // >= grid blocks
-    unsigned int *counter;   // zero before the first launch; the kernel leaves it zero
-    float *loss_out;         // 1 float: mean loss
-    float *loss_out2;        // optional second destination (caller's d_loss), may be null
+    float *block_partials;   // one loss sum per block (>= loss_grid_blocks entries)
 };
+// The mean loss is finished by the next consumer on the stream: sum of n block partials / B.
+struct LossFinalize {
+    const float *partials;
+    int n;                   // 0: nothing to do
+    long long B;
+    float *out;              // 1 float: mean loss
+    float *out2;             // optional second destination (the caller's d_loss), may be null
+};
+hipError_t launch_loss_finalize(const LossFinalize &f, hipStream_t stream,
+                                const LaunchEvents &ev = LaunchEvents());
 int loss_grid_blocks(long long B, int K);
 hipError_t launch_loss(const LossArgs &a, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
+
+// ---------------------------------------------------------------- fused narrow output layer
+struct OutLayerArgs {
+    const float *A;      // B x lda : A_{L-1}
+    int lda;
+    const float *W;      // K x d   : W_L (row-major, 16-byte aligned)
+    const float *bias;   // K
+    const int32_t *y;
+    long long B;
+    int d, K;            // d = d_{L-1} (multiple of 4), K = d_L <= 16
+    int loss, act;       // HB_LOSS_*, ACT_* of the hidden layers
+    int backward;        // 0: loss only
+    float *Dprev;        // B x ldp : D_{L-1} (may be null when L == 1 ... not used then)
+    int ldp;
+    float *dW_partial;   // [blocks][K x d]
+    float *db_partial;   // [blocks][K]
+    float *Z, *DL;       // optional copies of the logits / D_L (B x ldz), may be null
+    int ldz;
+    float *block_partials;   // one loss sum per block
+    int R;               // rows per block (set by the launcher)
+};
+// Largest rows-per-block for (d, K), or 0 when the fused kernel does not apply; the rows per
+// block actually used for a batch of B rows; the smallest value that can be.
+int out_layer_rows(int d, int K);
+int out_layer_rows_for_batch(int d, int K, long long B);
+int out_layer_min_rows();
+hipError_t launch_out_layer(OutLayerArgs a, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
 // ---------------------------------------------------------------- update
 // One segment = one parameter tensor: value[i] -= lr * sum_s partial[s*stride + i]   (STEP)
@@ -128,8 +162,6 @@ struct UpdateSeg {
     long long count;
     long long stride;
     int splits;
-    int pad;
-    void *shadow;   // bf16 copy of the tensor to refresh after the update (may be null)
 };
 constexpr int HB_MAX_SEGS = 40;
 struct UpdateArgs {
@@ -137,6 +169,7 @@ struct UpdateArgs {
     int n_seg;
     float lr;
     int write_grad;   // 0: update params; 1: write grad_out
+    LossFinalize fin; // fin.n > 0: one extra block row of the grid finishes the mean loss
 };
 hipError_t launch_update(const UpdateArgs &a, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
