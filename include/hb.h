@@ -175,7 +175,9 @@ enum {
     HB_K_SPMM_FWD = 5,   /* CSR first layer, forward */
     HB_K_SPARSE_DW = 6,  /* CSR first layer, gradient + update of the touched columns */
     HB_K_OTHER = 7,
-    HB_K_OUT_LAYER = 8   /* narrow output layer: forward + loss + delta + its gradients, fused */
+    HB_K_OUT_LAYER = 8,  /* narrow output layer: forward + loss + delta + its gradients, fused */
+    HB_K_BWD_PAIR = 9    /* backward-data and weight-gradient product of one layer in one launch;
+                            M, N, K are the backward-data shape, flops / bytes cover both */
 };
 typedef struct hb_kernel_stat {
     int32_t kind;            /* HB_K_* */

@@ -35,7 +35,7 @@ SIGNATURES = {
 }
 
 HB_K_NAMES = {0: "fwd_gemm", 1: "da_gemm", 2: "dw_gemm", 3: "loss", 4: "update", 5: "spmm_fwd",
-              6: "sparse_dw", 7: "other", 8: "out_layer"}
+              6: "sparse_dw", 7: "other", 8: "out_layer", 9: "bwd_pair"}
 
 
 class KernelStat(ctypes.Structure):

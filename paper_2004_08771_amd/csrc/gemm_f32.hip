@@ -149,8 +149,23 @@ __device__ __forceinline__ float sigmoidf_fast(float z)
     return __builtin_amdgcn_rcpf(1.0f + __expf(-z));  // v_rcp_f32: 1 ulp, no division sequence
 }
 
+// LDS floats one workgroup of this shape needs (two stages of an A and a B tile)
+template <int BM, int BN, int BK, bool A_KMAJ, bool B_KMAJ>
+constexpr int lds_floats()
+{
+    return 2 * (Tile<BM, BK, A_KMAJ>::FLOATS + Tile<BN, BK, B_KMAJ>::FLOATS);
+}
+
+// XCD-aware tile order: consecutive hardware workgroup ids go round-robin over the 8 XCDs,
+// so give each XCD a contiguous run of the T tiles (they share an A row panel in its L2).
+__device__ __forceinline__ int xcd_tile_order(int b, int T)
+{
+    return ((T & 7) == 0) ? (b & 7) * (T >> 3) + (b >> 3) : b;
+}
+
+// One output tile (index id in n-fastest order) of one K-slice (split) of C = A . B^T.
 template <int BM, int BN, int BK, int WAVES_M, bool A_KMAJ, bool B_KMAJ, int KIND>
-__global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
+__device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, int id, int split)
 {
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -159,21 +174,14 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
     using TA = Tile<BM, BK, A_KMAJ>;
     using TB = Tile<BN, BK, B_KMAJ>;
     constexpr int STAGE = TA::FLOATS + TB::FLOATS;
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
-    // XCD-aware tile order: consecutive hardware workgroup ids go round-robin over the 8
-    // XCDs, so give each XCD a contiguous run of tiles (they share an A row panel in L2).
-    int id = blockIdx.x;
-    const int T = gridDim.x;
-    if ((T & 7) == 0) id = (id & 7) * (T >> 3) + (id >> 3);
     const int tile_m = id / a.tiles_n, tile_n = id - tile_m * a.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int split = blockIdx.y;
     const int kbeg = split * a.k_chunk;
     const int kend = min(a.K, kbeg + a.k_chunk);
     const int nk = (kend - kbeg + BK - 1) / BK;
@@ -308,6 +316,34 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
     }
 }
 
+template <int BM, int BN, int BK, int WAVES_M, bool A_KMAJ, bool B_KMAJ, int KIND>
+__global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float smem[lds_floats<BM, BN, BK, A_KMAJ, B_KMAJ>()];
+    gemm_f32_tile<BM, BN, BK, WAVES_M, A_KMAJ, B_KMAJ, KIND>(a, smem, xcd_tile_order(blockIdx.x, gridDim.x),
+                                                             blockIdx.y);
+}
+
+// Backward of one hidden layer in ONE launch: the backward-data product D_{l-1} = (D_l W_l) f'
+// (64 x 64 x 32 tiles) and the weight-gradient product dW_l = D_l^T A_{l-1} (128 x 64 x 32
+// tiles x K-slices).  Both only read D_l, so they are
+// independent; sharing a launch lets the prologue / epilogue of one hide under the main loop
+// of the other and pays the per-launch latencies once.
+__global__ __launch_bounds__(NT) void gemm_f32_bwd_pair_kernel(GemmArgs da, GemmArgs dw, int n_dw)
+{
+    constexpr int LDS_DA = lds_floats<64, 64, 32, true, false>();
+    constexpr int LDS_DW = lds_floats<128, 64, 32, false, false>();
+    __shared__ __attribute__((aligned(16))) float smem[LDS_DA > LDS_DW ? LDS_DA : LDS_DW];
+    const int b = blockIdx.x;
+    if (b < n_dw) {  // the weight-gradient blocks are the longer ones: they are dispatched first
+        const int tiles = dw.tiles_m * dw.tiles_n;
+        gemm_f32_tile<128, 64, 32, 2, false, false, GEMM_DW>(dw, smem, xcd_tile_order(b % tiles, tiles), b / tiles);
+    } else {
+        const int n_da = gridDim.x - n_dw;
+        gemm_f32_tile<64, 64, 32, 2, true, false, GEMM_DA>(da, smem, xcd_tile_order(b - n_dw, n_da), 0);
+    }
+}
+
 int env_int(const char *name, int dflt)
 {
     const char *s = getenv(name);
@@ -364,9 +400,10 @@ struct SplitPlan {
 
 // Split-K plan for the weight-gradient product (its contraction runs over the batch):
 // enough slices to fill the device, each a multiple of BK long, none empty.
-SplitPlan plan_splits(int tiles, int K, int max_splits)
+SplitPlan plan_splits(int tiles, int K, int max_splits, int wgs = 0)
 {
-    int s = (target_wgs() + tiles - 1) / tiles;
+    if (wgs <= 0) wgs = target_wgs();
+    int s = (wgs + tiles - 1) / tiles;
     const int by_k = (K + 4 * K_CHUNK_ALIGN - 1) / (4 * K_CHUNK_ALIGN);  // slices of >= 128
     if (s > by_k) s = by_k;
     if (s > max_splits) s = max_splits;
@@ -404,6 +441,39 @@ hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *split
     if (sh.bn == 64 && sh.bk == 16) return launch_shape<128, 64, 16, 2>(kind, a, grid, stream, ev);
     if (sh.bn == 64 && sh.bk == 32) return launch_shape<128, 64, 32, 2>(kind, a, grid, stream, ev);
     return launch_shape<128, 128, 16, 2>(kind, a, grid, stream, ev);
+}
+
+
+// dA_l and dW_l of one hidden layer in one launch (see gemm_f32_bwd_pair_kernel).  Only for
+// shapes the fixed tile shapes of that kernel suit; the caller falls back to two launches
+// when this returns false from gemm_f32_pair_ok.
+bool gemm_f32_pair_ok(const GemmArgs &da, const GemmArgs &dw)
+{
+    static const int off = env_int("HB_NO_PAIR", 0);
+    return !off && da.M >= 64 && da.N >= 64 && da.K >= 32 && dw.M >= 128 && dw.N >= 64 && dw.K >= 32;
+}
+
+hipError_t launch_gemm_f32_bwd_pair(GemmArgs da, GemmArgs dw, int max_splits, int *splits_out,
+                                    hipStream_t stream, const LaunchEvents &ev)
+{
+    static const int pair_wgs = env_int("HB_PAIR_WGS", 256);  // weight-gradient blocks wanted (tuning aid)
+    da.tiles_m = (da.M + 63) / 64;
+    da.tiles_n = (da.N + 63) / 64;
+    da.splits = 1;
+    da.k_chunk = (da.K + K_CHUNK_ALIGN - 1) / K_CHUNK_ALIGN * K_CHUNK_ALIGN;
+    dw.tiles_m = (dw.M + 127) / 128;
+    dw.tiles_n = (dw.N + 63) / 64;
+    const long long n_da = (long long)da.tiles_m * da.tiles_n;
+    const long long t_dw = (long long)dw.tiles_m * dw.tiles_n;
+    if (n_da > 0x3fffffffLL || t_dw > 0x3fffffffLL) return hipErrorInvalidValue;
+    const SplitPlan sp = plan_splits((int)t_dw, dw.K, max_splits, pair_wgs);
+    dw.splits = sp.splits;
+    dw.k_chunk = sp.chunk;
+    if (splits_out) *splits_out = sp.splits;
+    const long long blocks = n_da + t_dw * sp.splits;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    return launch_kernel(gemm_f32_bwd_pair_kernel, dim3((unsigned)blocks), dim3(NT), stream, ev, da, dw,
+                         (int)(t_dw * sp.splits));
 }
 
 }  // namespace hb

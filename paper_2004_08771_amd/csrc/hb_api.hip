@@ -379,25 +379,54 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
     }
     for (int l = L_gemm; l >= 1; --l) {
         const float *delta_l = m->delta[l];
+        GemmArgs gda = {};  // D_{l-1} = (D_l W_l) * f'(A_{l-1})
         if (l > 1) {
-            GemmArgs g = {};
-            g.A = delta_l;
-            g.lda = m->ld[l];
-            g.B = m->d_params + m->w_off[l];
-            g.ldb = m->dims[l - 1];
-            g.C = m->delta[l - 1];
-            g.ldc = m->ld[l - 1];
-            g.M = Bi;
-            g.N = m->dims[l - 1];
-            g.K = m->dims[l];
-            g.a_vec = aligned16(g.A) && (g.lda % 4 == 0);
-            g.b_vec = aligned16(g.B) && (g.ldb % 4 == 0);
-            g.aux = m->acts[l - 1];
-            g.ldaux = m->ld[l - 1];
-            g.act = m->act;
-            HB_HIP(launch_gemm_f32(GEMM_DA, g, 1, nullptr, st,
-                                   prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
-                                              gemm_bytes(g.M, g.N, g.K, (int64_t)g.M * g.N))));
+            gda.A = delta_l;
+            gda.lda = m->ld[l];
+            gda.B = m->d_params + m->w_off[l];
+            gda.ldb = m->dims[l - 1];
+            gda.C = m->delta[l - 1];
+            gda.ldc = m->ld[l - 1];
+            gda.M = Bi;
+            gda.N = m->dims[l - 1];
+            gda.K = m->dims[l];
+            gda.a_vec = aligned16(gda.A) && (gda.lda % 4 == 0);
+            gda.b_vec = aligned16(gda.B) && (gda.ldb % 4 == 0);
+            gda.aux = m->acts[l - 1];
+            gda.ldaux = m->ld[l - 1];
+            gda.act = m->act;
+        }
+        GemmArgs gdw = {};  // dW_l = D_l^T A_{l-1} (split-K partials), db_l = column sums of D_l
+        gdw.A = delta_l;
+        gdw.lda = m->ld[l];
+        gdw.B = (l == 1) ? X : m->acts[l - 1];
+        gdw.ldb = (l == 1) ? m->dims[0] : m->ld[l - 1];
+        gdw.C = m->partial_w[l];
+        gdw.ldc = m->dims[l - 1];
+        gdw.c_split_stride = (long long)m->dims[l] * m->dims[l - 1];
+        gdw.M = m->dims[l];
+        gdw.N = m->dims[l - 1];
+        gdw.K = Bi;
+        gdw.a_vec = aligned16(gdw.A) && (gdw.lda % 4 == 0);
+        gdw.b_vec = aligned16(gdw.B) && (gdw.ldb % 4 == 0);
+        gdw.colsum = m->partial_b[l];
+        gdw.act = ACT_NONE;
+        const bool dense_dw = !(l == 1 && m->sparse);
+        int splits = 1;
+        bool dw_done = false;
+        if (l > 1 && dense_dw && gemm_f32_pair_ok(gda, gdw)) {
+            HB_HIP(launch_gemm_f32_bwd_pair(
+                gda, gdw, m->cap_splits[l], &splits, st,
+                prof_begin(m, HB_K_BWD_PAIR, l, gda.M, gda.N, gda.K,
+                           2.0 * gda.M * gda.N * gda.K + 2.0 * gdw.M * gdw.N * gdw.K,
+                           gemm_bytes(gda.M, gda.N, gda.K, (int64_t)gda.M * gda.N) +
+                               gemm_bytes(gdw.M, gdw.N, gdw.K, gdw.M))));
+            dw_done = true;
+        } else if (l > 1) {
+            HB_HIP(launch_gemm_f32(GEMM_DA, gda, 1, nullptr, st,
+                                   prof_begin(m, HB_K_DA_GEMM, l, gda.M, gda.N, gda.K,
+                                              2.0 * gda.M * gda.N * gda.K,
+                                              gemm_bytes(gda.M, gda.N, gda.K, (int64_t)gda.M * gda.N))));
         }
         if (l == 1 && m->sparse) {
             // db_1: column sums of delta_1; dW_1: column-segmented sums over the non-zeros,
@@ -448,25 +477,11 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
                                                    8.0 * touched * m->dims[1])));
             continue;
         }
-        GemmArgs g = {};
-        g.A = delta_l;
-        g.lda = m->ld[l];
-        g.B = (l == 1) ? X : m->acts[l - 1];
-        g.ldb = (l == 1) ? m->dims[0] : m->ld[l - 1];
-        g.C = m->partial_w[l];
-        g.ldc = m->dims[l - 1];
-        g.c_split_stride = (long long)m->dims[l] * m->dims[l - 1];
-        g.M = m->dims[l];
-        g.N = m->dims[l - 1];
-        g.K = Bi;
-        g.a_vec = aligned16(g.A) && (g.lda % 4 == 0);
-        g.b_vec = aligned16(g.B) && (g.ldb % 4 == 0);
-        g.colsum = m->partial_b[l];
-        g.act = ACT_NONE;
-        int splits = 1;
-        HB_HIP(launch_gemm_f32(GEMM_DW, g, m->cap_splits[l], &splits, sw_stream,
-                               prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
-                                          gemm_bytes(g.M, g.N, g.K, g.M))));
+        if (!dw_done)
+            HB_HIP(launch_gemm_f32(GEMM_DW, gdw, m->cap_splits[l], &splits, sw_stream,
+                                   prof_begin(m, HB_K_DW_GEMM, l, gdw.M, gdw.N, gdw.K,
+                                              2.0 * gdw.M * gdw.N * gdw.K,
+                                              gemm_bytes(gdw.M, gdw.N, gdw.K, gdw.M))));
 
         UpdateSeg &sw = ua.seg[ua.n_seg++];
         sw.param = m->d_params + m->w_off[l];

@@ -58,6 +58,13 @@ struct GemmArgs {
 hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *splits_out,
                            hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
+// The backward-data and the weight-gradient product of one hidden layer in a single launch
+// (both read the same D_l and are independent).  gemm_f32_pair_ok: the shapes suit the fixed
+// tile shapes of that kernel; otherwise launch the two products separately.
+bool gemm_f32_pair_ok(const GemmArgs &da, const GemmArgs &dw);
+hipError_t launch_gemm_f32_bwd_pair(GemmArgs da, GemmArgs dw, int max_splits, int *splits_out,
+                                    hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
+
 // Number of split-K slices launch_gemm_f32 will use for a DW product of this shape
 // (so that the caller can size the partial buffers).
 int gemm_f32_dw_splits(int M, int N, int K, int max_splits);
