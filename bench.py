@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -128,6 +130,14 @@ def main():
             j = i % n_batches
             model.batch_step_async(x_ptr[j], y_ptr[j], B, lr, d_loss)
 
+    if args.calibrate_copy:
+        # a copy kernel of known size: 256 MiB read + 256 MiB written, for scaling FETCH_SIZE / WRITE_SIZE
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     d_loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     for i in range(args.warmup):
         one_step(i, d_loss)
@@ -187,10 +197,12 @@ def main():
                          "avg_kernel_us": round(avg_s * 1e6, 3), "launches": g["n"],
                          "share_of_kernel_time": round(g["ms"] / total, 4),
                          "sum_kernel_us_per_step": round(1e3 * total / args.steps, 2)})
-        traffic_file = os.path.join(ROOT, "profiles", f"traffic_config{args.config}_B{B}.json")
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very
+        # command (measured offline, scaled by a plain copy kernel; see profiles/)
+        traffic_file = os.path.join(ROOT, "profiles", f"hbm_traffic_config{args.config}_B{B}.json")
         if os.path.exists(traffic_file):
             with open(traffic_file) as f:
-                roofline["traffic"] = json.load(f).get(name)
+                roofline["traffic"] = json.load(f).get("bytes_per_launch", {}).get(name)
         for k in kernels:
             for key in ("_total_ms", "_flops", "_bytes"):
                 k.pop(key)
@@ -218,12 +230,17 @@ def main():
 
         probe_rows = min(B, 64)
         rate = probe_rows / oracle_step(probe_rows)          # examples/s, B-independent
-        sample = int(min(B, max(probe_rows, rate * args.cpu_seconds)))
-        dt = oracle_step(sample)
-        cpu_baseline = {"value": round(sample / dt, 2), "unit": "examples/s", "cores": cores,
+        # whole batches first (up to 8 oracle steps), a fraction of one batch if even that is too slow
+        want = rate * args.cpu_seconds
+        if want >= B:
+            n_steps, sample = int(min(8, want // B)), B
+        else:
+            n_steps, sample = 1, int(max(probe_rows, want))
+        dt = sum(oracle_step(sample) for _ in range(n_steps))
+        cpu_baseline = {"value": round(n_steps * sample / dt, 2), "unit": "examples/s", "cores": cores,
                         "kind": "oracle",
-                        "sample": f"one fp64 oracle step (forward, backward, update) on the first {sample} "
-                                  f"rows of the same batch, {dt:.1f} s"}
+                        "sample": f"{n_steps} fp64 oracle step(s) (forward, backward, update) on the first "
+                                  f"{sample} rows of the same dataset, {dt:.1f} s"}
 
     out = {
         "metric": "training examples/sec per SGD batch step at B=4096; % of MFMA peak",
