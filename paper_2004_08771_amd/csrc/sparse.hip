@@ -36,11 +36,35 @@ __global__ __launch_bounds__(SP_NT) void spmm_fwd_kernel(SpmmArgs a)
         const int n4 = a.d1 >> 2;
         for (int q = threadIdx.x; q < n4; q += SP_NT) {
             float4 acc = reinterpret_cast<const float4 *>(a.bias)[q];
-            for (int p = beg; p < end; ++p) {
-                const int c = a.col_idx[p];
-                const float v = a.vals[p];
-                const float4 w = reinterpret_cast<const float4 *>(a.W1t + (size_t)c * a.ldw)[q];
-                acc.x += v * w.x; acc.y += v * w.y; acc.z += v * w.z; acc.w += v * w.w;
+            int p = beg;
+            for (; p + 8 <= end; p += 8) {  // eight row gathers in flight; added in index order
+                float4 w[8];
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    v[u] = a.vals[p + u];
+                    w[u] = reinterpret_cast<const float4 *>(a.W1t + (size_t)a.col_idx[p + u] * a.ldw)[q];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    acc.x += v[u] * w[u].x; acc.y += v[u] * w[u].y; acc.z += v[u] * w[u].z; acc.w += v[u] * w[u].w;
+                }
+            }
+            if (p < end) {  // the tail, also fetched together
+                float4 w[8];
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool ok = p + u < end;
+                    v[u] = ok ? a.vals[p + u] : 0.f;
+                    w[u] = ok ? reinterpret_cast<const float4 *>(a.W1t + (size_t)a.col_idx[p + u] * a.ldw)[q]
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (p + u < end) {
+                        acc.x += v[u] * w[u].x; acc.y += v[u] * w[u].y; acc.z += v[u] * w[u].z; acc.w += v[u] * w[u].w;
+                    }
             }
             acc.x = act_apply(acc.x, a.act); acc.y = act_apply(acc.y, a.act);
             acc.z = act_apply(acc.z, a.act); acc.w = act_apply(acc.w, a.act);
@@ -91,54 +115,86 @@ __global__ __launch_bounds__(256) void csc_colsum_kernel(int32_t *__restrict__ h
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= d0) return;
     int run = 0;
-    for (int b = 0; b < n_blocks; ++b) {
-        const int h = hist[(size_t)b * d0 + c];
-        hist[(size_t)b * d0 + c] = run;
-        run += h;
+    for (int b0 = 0; b0 < n_blocks; b0 += 16) {  // sixteen loads in flight, then the prefix
+        int h[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) h[u] = (b0 + u < n_blocks) ? hist[(size_t)(b0 + u) * d0 + c] : 0;
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            if (b0 + u < n_blocks) {
+                hist[(size_t)(b0 + u) * d0 + c] = run;
+                run += h[u];
+            }
     }
     cnt[c] = run;
 }
 
 // One workgroup: exclusive scans of cnt[0..n) (-> col_start) and of the chunk counts
-// ceil(cnt / CHUNK) (-> chunk_start); both get their totals at index n.
+// ceil(cnt / CHUNK) (-> chunk_start); both get their totals at index n.  Each of the 16
+// wavefronts owns a contiguous run of columns and walks it 64 columns at a time (coalesced),
+// scanning with shuffles and a running carry.
+__device__ __forceinline__ int wave_incl_scan(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+constexpr int SCAN_MAX_GROUPS = 40;  // 64-column groups per wavefront: 16 * 40 * 64 = 40,960 columns
+
 __global__ __launch_bounds__(1024) void col_scan_kernel(const int32_t *__restrict__ cnt, int n,
                                                         int32_t *__restrict__ col_start,
-                                                        int32_t *__restrict__ chunk_start)
+                                                        int32_t *__restrict__ chunk_start,
+                                                        int32_t *__restrict__ chunk_col)
 {
-    extern __shared__ int32_t s_cnt[];  // n entries
-    __shared__ int s_a[1024], s_b[1024];
-    const int tid = threadIdx.x;
-    for (int c = tid; c < n; c += 1024) s_cnt[c] = cnt[c];
-    __syncthreads();
-    const int per = (n + 1023) / 1024;
-    const int lo = min(n, tid * per), hi = min(n, lo + per);
+    __shared__ int w_a[16], w_b[16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per = ((n + 15) / 16 + 63) / 64 * 64;  // columns per wavefront, a multiple of 64
+    const int lo = min(n, wave * per), hi = min(n, lo + per);
+    // every count this lane will need, fetched in one go (one memory latency for the kernel)
+    int v[SCAN_MAX_GROUPS];
+#pragma unroll
+    for (int u = 0; u < SCAN_MAX_GROUPS; ++u) {
+        const int c = lo + u * 64 + lane;
+        v[u] = (c < hi) ? cnt[c] : 0;
+    }
     int sa = 0, sb = 0;
-    for (int c = lo; c < hi; ++c) {
-        sa += s_cnt[c];
-        sb += (s_cnt[c] + CHUNK - 1) / CHUNK;
+#pragma unroll
+    for (int u = 0; u < SCAN_MAX_GROUPS; ++u) {
+        sa += v[u];
+        sb += (v[u] + CHUNK - 1) / CHUNK;
     }
-    s_a[tid] = sa;
-    s_b[tid] = sb;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        sa += __shfl_xor(sa, o, 64);
+        sb += __shfl_xor(sb, o, 64);
+    }
+    if (lane == 0) { w_a[wave] = sa; w_b[wave] = sb; }
     __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {  // Hillis-Steele inclusive scan
-        int va = 0, vb = 0;
-        if (tid >= off) { va = s_a[tid - off]; vb = s_b[tid - off]; }
-        __syncthreads();
-        s_a[tid] += va;
-        s_b[tid] += vb;
-        __syncthreads();
+    int ca = 0, cb = 0;  // exclusive offset of this wavefront's run
+    for (int w = 0; w < wave; ++w) { ca += w_a[w]; cb += w_b[w]; }
+#pragma unroll
+    for (int u = 0; u < SCAN_MAX_GROUPS; ++u) {
+        const int c = lo + u * 64 + lane;
+        const int ch = (v[u] + CHUNK - 1) / CHUNK;
+        const int ia = wave_incl_scan(v[u], lane), ib = wave_incl_scan(ch, lane);
+        if (c < hi) {
+            col_start[c] = ca + ia - v[u];
+            const int first = cb + ib - ch;
+            chunk_start[c] = first;
+            for (int q = 0; q < ch; ++q) chunk_col[first + q] = c;  // which column a chunk belongs to
+        }
+        ca += __shfl(ia, 63, 64);
+        cb += __shfl(ib, 63, 64);
     }
-    int ra = s_a[tid] - sa, rb = s_b[tid] - sb;  // exclusive prefix of this thread's range
-    for (int c = lo; c < hi; ++c) {
-        const int v = s_cnt[c];
-        col_start[c] = ra;
-        chunk_start[c] = rb;
-        ra += v;
-        rb += (v + CHUNK - 1) / CHUNK;
-    }
-    if (tid == 1023) {
-        col_start[n] = s_a[1023];
-        chunk_start[n] = s_b[1023];
+    if (threadIdx.x == 0) {
+        int ta = 0, tb = 0;
+        for (int w = 0; w < 16; ++w) { ta += w_a[w]; tb += w_b[w]; }
+        col_start[n] = ta;
+        chunk_start[n] = tb;
     }
 }
 
@@ -153,18 +209,45 @@ __global__ __launch_bounds__(CSC_NT) void csc_place_kernel(const int32_t *__rest
 {
     extern __shared__ int32_t s_cur[];
     const int32_t *mine = hist + (size_t)blockIdx.x * d0;
-    for (int c = threadIdx.x; c < d0; c += CSC_NT) s_cur[c] = col_start[c] + mine[c];
+    // LDS holds how many entries of each column this block has placed so far; the column's
+    // base offset (col_start + this block's exclusive prefix) is fetched per non-zero, which
+    // touches far fewer words than initialising d0 cursors from global memory would
+    for (int c = threadIdx.x; c < d0; c += CSC_NT) s_cur[c] = 0;
     __syncthreads();
     const long long r0 = (long long)blockIdx.x * rows_per_block;
     const long long r1 = min(B, r0 + rows_per_block);
-    // one wavefront per row, lanes over the row's non-zeros
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (long long row = r0 + wave; row < r1; row += CSC_NT / 64) {
-        const int beg = row_ptr[row], end = row_ptr[row + 1];
-        for (int p = beg + lane; p < end; p += 64) {
-            const int pos = atomicAdd(&s_cur[col_idx[p]], 1);
-            csc_row[pos] = (int32_t)row;
-            csc_val[pos] = vals[p];
+    if (r0 >= r1) return;
+    // the block's slice of row_ptr sits behind the cursors in LDS: rows are found by bisection there
+    int32_t *s_rp = s_cur + d0;
+    const int nr = (int)(r1 - r0);
+    for (int i = threadIdx.x; i <= nr; i += CSC_NT) s_rp[i] = row_ptr[r0 + i];
+    __syncthreads();
+    const int beg = s_rp[0], end = s_rp[nr];
+    // one thread per non-zero of the block's contiguous range, four at a time so that the
+    // dependent loads (column -> base offsets -> position) of the four overlap
+    for (int p0 = beg + threadIdx.x; p0 < end; p0 += 4 * CSC_NT) {
+        int c[4], base[4];
+        float val[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int p = p0 + u * CSC_NT;
+            c[u] = (p < end) ? col_idx[p] : -1;
+            val[u] = (p < end) ? vals[p] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) base[u] = (c[u] >= 0) ? col_start[c[u]] + mine[c[u]] : 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (c[u] < 0) continue;
+            const int p = p0 + u * CSC_NT;
+            int lo = 0, hi = nr;  // s_rp[lo] <= p < s_rp[hi]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_rp[mid] <= p) lo = mid; else hi = mid;
+            }
+            const int pos = base[u] + atomicAdd(&s_cur[c[u]], 1);
+            csc_row[pos] = (int32_t)(r0 + lo);
+            csc_val[pos] = val[u];
         }
     }
 }
@@ -178,13 +261,7 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
     const int total_chunks = a.chunk_start[a.d0];
     const int chunk = blockIdx.x;
     if (chunk >= total_chunks) return;
-    // largest c with chunk_start[c] <= chunk (columns without entries have equal starts)
-    int lo = 0, hi = a.d0;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.chunk_start[mid] <= chunk) lo = mid; else hi = mid;
-    }
-    const int c = lo;
+    const int c = a.chunk_col[chunk];
     const int n_chunks = a.chunk_start[c + 1] - a.chunk_start[c];
     const int seg_beg = a.col_start[c], seg_end = a.col_start[c + 1];
     const int e_beg = seg_beg + (chunk - a.chunk_start[c]) * CHUNK;
@@ -195,10 +272,35 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
         const int n4 = a.d1 >> 2;
         for (int q = threadIdx.x; q < n4; q += SP_NT) {
             float4 g = {0.f, 0.f, 0.f, 0.f};
-            for (int e = e_beg; e < e_end; ++e) {
-                const float v = a.csc_val[e];
-                const float4 d = reinterpret_cast<const float4 *>(a.delta + (size_t)a.csc_row[e] * a.ldd)[q];
-                g.x += v * d.x; g.y += v * d.y; g.z += v * d.z; g.w += v * d.w;
+            int e = e_beg;
+            for (; e + 16 <= e_end; e += 16) {  // sixteen row gathers in flight; added in index order
+                float4 d[16];
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    v[u] = a.csc_val[e + u];
+                    d[u] = reinterpret_cast<const float4 *>(a.delta + (size_t)a.csc_row[e + u] * a.ldd)[q];
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    g.x += v[u] * d[u].x; g.y += v[u] * d[u].y; g.z += v[u] * d[u].z; g.w += v[u] * d[u].w;
+                }
+            }
+            if (e < e_end) {  // the tail, also fetched together (entries past the end read as zero)
+                float4 d[16];
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const bool ok = e + u < e_end;
+                    v[u] = ok ? a.csc_val[e + u] : 0.f;
+                    d[u] = ok ? reinterpret_cast<const float4 *>(a.delta + (size_t)a.csc_row[e + u] * a.ldd)[q]
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    if (e + u < e_end) {
+                        g.x += v[u] * d[u].x; g.y += v[u] * d[u].y; g.z += v[u] * d[u].z; g.w += v[u] * d[u].w;
+                    }
             }
             if (a.grad_out) {
                 float *o = a.grad_out + (size_t)(4 * q) * a.d0 + c;
@@ -286,28 +388,34 @@ int csc_blocks(long long B)
     return (int)nb;
 }
 
+// The per-block column histogram plus the block's slice of row_ptr must fit LDS, and the
+// single-workgroup scan keeps its columns in registers.
+bool csc_supported(int d0, long long max_B)
+{
+    if (d0 > 16 * SCAN_MAX_GROUPS * 64 - 4096) return false;  // 36,864 columns
+    const int nb = csc_blocks(max_B);
+    const long long rows_per_block = (max_B + nb - 1) / nb;
+    return ((long long)d0 + rows_per_block + 1) * (long long)sizeof(int32_t) <= 150 * 1024;
+}
+
 size_t csc_hist_elems(long long max_B, int d0) { return (size_t)csc_blocks(max_B) * (size_t)d0; }
 
-bool csc_supported(int d0) { return (size_t)d0 * sizeof(int32_t) <= 150 * 1024; }
 
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
                             long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
-                            int32_t *col_start, int32_t *chunk_start, int32_t *csc_row, float *csc_val,
-                            hipStream_t stream, const LaunchEvents &ev_hist,
+                            int32_t *col_start, int32_t *chunk_start, int32_t *chunk_col, int32_t *csc_row,
+                            float *csc_val, hipStream_t stream, const LaunchEvents &ev_hist,
                             const LaunchEvents &ev_scan, const LaunchEvents &ev_place)
 {
     (void)nnz;
     const int nb = csc_blocks(B);
     const int rows_per_block = (int)((B + nb - 1) / nb);
-    const size_t lds = (size_t)d0 * sizeof(int32_t);
+    const size_t lds = ((size_t)d0 + (size_t)rows_per_block + 1) * sizeof(int32_t);
     // more than 64 KB of dynamic LDS has to be requested per kernel
     static size_t lds_granted = 0;
     if (lds > 32 * 1024 && lds > lds_granted) {
         hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_hist_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (ea == hipSuccess)
-            ea = hipFuncSetAttribute(reinterpret_cast<const void *>(col_scan_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (ea == hipSuccess)
             ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_place_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -325,13 +433,8 @@ hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, cons
     e = launch_kernel(csc_colsum_kernel, dim3((unsigned)((d0 + 255) / 256)), dim3(256), stream, LaunchEvents(),
                       hist, nb, d0, cnt);
     if (e != hipSuccess) return e;
-    if (ev_scan.start)
-        hipExtLaunchKernelGGL(col_scan_kernel, dim3(1), dim3(1024), (unsigned)lds, stream, ev_scan.start,
-                              ev_scan.stop, 0, static_cast<const int32_t *>(cnt), d0, col_start, chunk_start);
-    else
-        hipLaunchKernelGGL(col_scan_kernel, dim3(1), dim3(1024), lds, stream,
-                           static_cast<const int32_t *>(cnt), d0, col_start, chunk_start);
-    e = hipGetLastError();
+    e = launch_kernel(col_scan_kernel, dim3(1), dim3(1024), stream, ev_scan, static_cast<const int32_t *>(cnt),
+                      d0, col_start, chunk_start, chunk_col);
     if (e != hipSuccess) return e;
     if (ev_place.start)
         hipExtLaunchKernelGGL(csc_place_kernel, dim3(nb), dim3(CSC_NT), (unsigned)lds, stream, ev_place.start,
