@@ -106,7 +106,7 @@ struct hb_model {
     int32_t *d_col_cnt = nullptr, *d_col_start = nullptr, *d_chunk_start = nullptr;
     int32_t *d_cursor = nullptr;  // per-block column histograms / cursors of the CSC build
     int32_t *d_csc_row = nullptr;
-    int32_t *d_chunk_col = nullptr;      // column of each gradient chunk (same capacity as the CSC arrays)
+    int4 *d_chunk_desc = nullptr;        // descriptor of each gradient chunk (capacity follows the CSC arrays)
     float *d_csc_val = nullptr;
     int64_t csc_cap = 0;
     int b1_splits = 1;
@@ -149,10 +149,10 @@ void release_device(hb_model *m)
     m->free_events.clear();
     if (m->d_csc_row) (void)hipFree(m->d_csc_row);
     if (m->d_csc_val) (void)hipFree(m->d_csc_val);
-    if (m->d_chunk_col) (void)hipFree(m->d_chunk_col);
+    if (m->d_chunk_desc) (void)hipFree(m->d_chunk_desc);
     m->d_csc_row = nullptr;
     m->d_csc_val = nullptr;
-    m->d_chunk_col = nullptr;
+    m->d_chunk_desc = nullptr;
     m->csc_cap = 0;
     for (void *p : m->owned) (void)hipFree(p);
     m->owned.clear();
@@ -230,16 +230,16 @@ int ensure_csc_capacity(hb_model *m, int64_t nnz)
     while (cap < nnz) cap *= 2;
     if (m->d_csc_row) (void)hipFree(m->d_csc_row);
     if (m->d_csc_val) (void)hipFree(m->d_csc_val);
-    if (m->d_chunk_col) (void)hipFree(m->d_chunk_col);
+    if (m->d_chunk_desc) (void)hipFree(m->d_chunk_desc);
     m->d_csc_row = nullptr;
     m->d_csc_val = nullptr;
-    m->d_chunk_col = nullptr;
+    m->d_chunk_desc = nullptr;
     m->csc_cap = 0;
     // chunks <= cap / CHUNK + d_0
     const size_t max_chunks = (size_t)cap / sparse_chunk() + (size_t)m->dims[0] + 1;
     if (hipMalloc(reinterpret_cast<void **>(&m->d_csc_row), sizeof(int32_t) * (size_t)cap) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->d_csc_val), sizeof(float) * (size_t)cap) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&m->d_chunk_col), sizeof(int32_t) * max_chunks) != hipSuccess)
+        hipMalloc(reinterpret_cast<void **>(&m->d_chunk_desc), sizeof(int4) * max_chunks) != hipSuccess)
         return fail(HB_ERR_ALLOC, "could not allocate the per-batch CSC workspace for %lld non-zeros",
                     (long long)nnz);
     m->csc_cap = cap;
@@ -450,15 +450,17 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sb.stride = m->dims[1];
             sb.splits = m->b1_splits;
             HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_cursor,
-                                    m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_chunk_col,
+                                    m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_chunk_desc,
                                     m->d_csc_row, m->d_csc_val, sw_stream,
                                     prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
-                                    prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
-                                    prof_begin(m, HB_K_OTHER, 4, 0, 0, 0, 0.0, 16.0 * in.nnz)));
+                                    prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0,
+                                               8.0 * (double)csc_hist_elems(B, m->dims[0])),
+                                    prof_begin(m, HB_K_OTHER, 4, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
+                                    prof_begin(m, HB_K_OTHER, 5, 0, 0, 0, 0.0, 16.0 * in.nnz)));
             SparseDwArgs sd = {};
             sd.col_start = m->d_col_start;
             sd.chunk_start = m->d_chunk_start;
-            sd.chunk_col = m->d_chunk_col;
+            sd.chunk_desc = m->d_chunk_desc;
             sd.csc_row = m->d_csc_row;
             sd.csc_val = m->d_csc_val;
             sd.delta = delta_l;
@@ -885,7 +887,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
     if (m->sparse && rc == HB_OK) {
         const size_t d0 = (size_t)m->dims[0];
         rc = dev_alloc(m, &m->d_w1t, d0 * m->dims[1]);
-        if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_cnt, d0 + 1);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_cnt, csc_cnt_elems(d0));
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_start, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, csc_hist_elems(max_B, m->dims[0]));

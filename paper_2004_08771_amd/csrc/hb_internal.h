@@ -205,7 +205,7 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream,
 struct SparseDwArgs {
     const int32_t *col_start;    // d_0 + 1: segment of each column in csc_row / csc_val
     const int32_t *chunk_start;  // d_0 + 1: first chunk of each column; [d_0] = number of chunks
-    const int32_t *chunk_col;    // column of each chunk
+    const int4 *chunk_desc;      // per chunk: {column, first entry, end entry, chunks of the column}
     const int32_t *csc_row;
     const float *csc_val;
     const float *delta;          // B x ldd
@@ -219,14 +219,17 @@ struct SparseDwArgs {
 };
 int sparse_chunk();
 // Per-batch CSC (column-segmented copy of the batch's non-zeros) by a multi-block counting
-// sort; hist is scratch of csc_hist_elems(max_B, d0) int32.  Needs csc_supported(d0, max_B):
+// sort; hist is scratch of csc_hist_elems(max_B, d0) int32, cnt of csc_cnt_elems(d0) int32.
+// Needs csc_supported(d0, max_B):
 // the column histogram of one block and its slice of row_ptr live in LDS.
 bool csc_supported(int d0, long long max_B);
 size_t csc_hist_elems(long long max_B, int d0);
+size_t csc_cnt_elems(int d0);
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
                             long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
-                            int32_t *col_start, int32_t *chunk_start, int32_t *chunk_col, int32_t *csc_row,
+                            int32_t *col_start, int32_t *chunk_start, int4 *chunk_desc, int32_t *csc_row,
                             float *csc_val, hipStream_t stream, const LaunchEvents &ev_hist = LaunchEvents(),
+                            const LaunchEvents &ev_colsum = LaunchEvents(),
                             const LaunchEvents &ev_scan = LaunchEvents(),
                             const LaunchEvents &ev_place = LaunchEvents());
 hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStream_t stream,

@@ -85,7 +85,8 @@ __global__ __launch_bounds__(SP_NT) void spmm_fwd_kernel(SpmmArgs a)
 // serialise).  Block b owns a contiguous range of rows:
 //   1. csc_hist_kernel   block-local column histogram in LDS -> hist[b][c]
 //   2. csc_colsum_kernel per column: exclusive prefix over blocks (in place) and total cnt[c]
-//   3. col_scan_kernel   exclusive scan of cnt over columns -> col_start, chunk_start
+//   3. col_scan_kernel   exclusive scan of cnt over columns -> col_start, chunk_start, and
+//                        the chunk descriptors of the gradient kernel
 //   4. csc_place_kernel  block b re-reads its rows; its LDS cursor of column c starts at
 //                        col_start[c] + hist[b][c]; LDS atomics hand out the positions.
 constexpr int CSC_NT = 1024;
@@ -109,30 +110,9 @@ __global__ __launch_bounds__(CSC_NT) void csc_hist_kernel(const int32_t *__restr
     for (int c = threadIdx.x; c < d0; c += CSC_NT) out[c] = s_hist[c];
 }
 
-__global__ __launch_bounds__(256) void csc_colsum_kernel(int32_t *__restrict__ hist, int n_blocks, int d0,
-                                                         int32_t *__restrict__ cnt)
-{
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= d0) return;
-    int run = 0;
-    for (int b0 = 0; b0 < n_blocks; b0 += 16) {  // sixteen loads in flight, then the prefix
-        int h[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) h[u] = (b0 + u < n_blocks) ? hist[(size_t)(b0 + u) * d0 + c] : 0;
-#pragma unroll
-        for (int u = 0; u < 16; ++u)
-            if (b0 + u < n_blocks) {
-                hist[(size_t)(b0 + u) * d0 + c] = run;
-                run += h[u];
-            }
-    }
-    cnt[c] = run;
-}
+// Columns are handled in groups of 256 (one workgroup each) by the next two kernels.
+constexpr int COLG = 256;
 
-// One workgroup: exclusive scans of cnt[0..n) (-> col_start) and of the chunk counts
-// ceil(cnt / CHUNK) (-> chunk_start); both get their totals at index n.  Each of the 16
-// wavefronts owns a contiguous run of columns and walks it 64 columns at a time (coalesced),
-// scanning with shuffles and a running carry.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane)
 {
 #pragma unroll
@@ -143,58 +123,109 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane)
     return v;
 }
 
-constexpr int SCAN_MAX_GROUPS = 40;  // 64-column groups per wavefront: 16 * 40 * 64 = 40,960 columns
-
-__global__ __launch_bounds__(1024) void col_scan_kernel(const int32_t *__restrict__ cnt, int n,
-                                                        int32_t *__restrict__ col_start,
-                                                        int32_t *__restrict__ chunk_start,
-                                                        int32_t *__restrict__ chunk_col)
+// Sum over the workgroup's four wavefronts of (a, b); every thread gets the result.
+__device__ __forceinline__ void group_sum2(int &a, int &b, int *red /* 8 ints of LDS */)
 {
-    __shared__ int w_a[16], w_b[16];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int per = ((n + 15) / 16 + 63) / 64 * 64;  // columns per wavefront, a multiple of 64
-    const int lo = min(n, wave * per), hi = min(n, lo + per);
-    // every count this lane will need, fetched in one go (one memory latency for the kernel)
-    int v[SCAN_MAX_GROUPS];
-#pragma unroll
-    for (int u = 0; u < SCAN_MAX_GROUPS; ++u) {
-        const int c = lo + u * 64 + lane;
-        v[u] = (c < hi) ? cnt[c] : 0;
-    }
-    int sa = 0, sb = 0;
-#pragma unroll
-    for (int u = 0; u < SCAN_MAX_GROUPS; ++u) {
-        sa += v[u];
-        sb += (v[u] + CHUNK - 1) / CHUNK;
-    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-        sa += __shfl_xor(sa, o, 64);
-        sb += __shfl_xor(sb, o, 64);
+        a += __shfl_xor(a, o, 64);
+        b += __shfl_xor(b, o, 64);
     }
-    if (lane == 0) { w_a[wave] = sa; w_b[wave] = sb; }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { red[wave] = a; red[4 + wave] = b; }
     __syncthreads();
-    int ca = 0, cb = 0;  // exclusive offset of this wavefront's run
-    for (int w = 0; w < wave; ++w) { ca += w_a[w]; cb += w_b[w]; }
+    a = red[0] + red[1] + red[2] + red[3];
+    b = red[4] + red[5] + red[6] + red[7];
+}
+
+// Per column: exclusive prefix of its counts over the row blocks (in place in hist) and the
+// total cnt[c]; per group of 256 columns: the group's entry and chunk totals
+// (group_tot[g], group_tot[n_groups + g]).
+__global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ hist, int n_blocks, int d0,
+                                                          int32_t *__restrict__ cnt,
+                                                          int32_t *__restrict__ group_tot)
+{
+    __shared__ int red[8];
+    const int c = blockIdx.x * COLG + threadIdx.x;
+    int run = 0;
+    if (c < d0) {
+        for (int b0 = 0; b0 < n_blocks; b0 += 16) {  // sixteen loads in flight, then the prefix
+            int h[16];
 #pragma unroll
-    for (int u = 0; u < SCAN_MAX_GROUPS; ++u) {
-        const int c = lo + u * 64 + lane;
-        const int ch = (v[u] + CHUNK - 1) / CHUNK;
-        const int ia = wave_incl_scan(v[u], lane), ib = wave_incl_scan(ch, lane);
-        if (c < hi) {
-            col_start[c] = ca + ia - v[u];
-            const int first = cb + ib - ch;
-            chunk_start[c] = first;
-            for (int q = 0; q < ch; ++q) chunk_col[first + q] = c;  // which column a chunk belongs to
+            for (int u = 0; u < 16; ++u) h[u] = (b0 + u < n_blocks) ? hist[(size_t)(b0 + u) * d0 + c] : 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (b0 + u < n_blocks) {
+                    hist[(size_t)(b0 + u) * d0 + c] = run;
+                    run += h[u];
+                }
         }
-        ca += __shfl(ia, 63, 64);
-        cb += __shfl(ib, 63, 64);
+        cnt[c] = run;
     }
+    int sa = run, sb = (run + CHUNK - 1) / CHUNK;
+    group_sum2(sa, sb, red);
     if (threadIdx.x == 0) {
-        int ta = 0, tb = 0;
-        for (int w = 0; w < 16; ++w) { ta += w_a[w]; tb += w_b[w]; }
-        col_start[n] = ta;
-        chunk_start[n] = tb;
+        group_tot[blockIdx.x] = sa;
+        group_tot[gridDim.x + blockIdx.x] = sb;
+    }
+}
+
+// Exclusive scans of cnt[0..n) (-> col_start) and of the chunk counts ceil(cnt / CHUNK)
+// (-> chunk_start), totals at index n, plus one descriptor per chunk {column, first entry,
+// end entry, chunks of the column} so that the gradient kernel finds its work with one load.
+// One workgroup per group of 256 columns: it adds up the totals of the groups before it,
+// scans its own columns with shuffles, and writes its outputs coalesced.  A column with more
+// than two chunks (the head of a skewed column distribution has hundreds) goes on an LDS
+// list and the whole workgroup writes its descriptors.
+// (A single-workgroup scan of all 21k columns took 20-60 us in three different forms: one
+// CU's shuffle latency and store issue rate bound it.)
+__global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restrict__ cnt,
+                                                        const int32_t *__restrict__ group_tot, int n,
+                                                        int32_t *__restrict__ col_start,
+                                                        int32_t *__restrict__ chunk_start,
+                                                        int4 *__restrict__ chunk_desc)
+{
+    __shared__ int red[8], w_a[4], w_b[4];
+    __shared__ int n_heavy;
+    __shared__ int4 heavy[COLG];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int g = blockIdx.x, n_groups = gridDim.x;
+    const int c = g * COLG + t;
+    const int v = (c < n) ? cnt[c] : 0;
+    int pa = 0, pb = 0;  // entries / chunks in the groups before this one
+    for (int j = t; j < g; j += COLG) {
+        pa += group_tot[j];
+        pb += group_tot[n_groups + j];
+    }
+    if (t == 0) n_heavy = 0;
+    group_sum2(pa, pb, red);  // its barrier also publishes n_heavy
+    const int ch = (v + CHUNK - 1) / CHUNK;
+    const int ia = wave_incl_scan(v, lane), ib = wave_incl_scan(ch, lane);
+    if (lane == 63) { w_a[wave] = ia; w_b[wave] = ib; }
+    __syncthreads();
+    int first_e = pa + ia - v, first_ch = pb + ib - ch;
+    for (int w = 0; w < wave; ++w) { first_e += w_a[w]; first_ch += w_b[w]; }
+    if (c < n) {
+        col_start[c] = first_e;
+        chunk_start[c] = first_ch;
+        if (c == n - 1) {
+            col_start[n] = first_e + v;
+            chunk_start[n] = first_ch + ch;
+        }
+        if (ch > 2)
+            heavy[atomicAdd(&n_heavy, 1)] = make_int4(c, first_e, v, first_ch);
+        else
+            for (int q = 0; q < ch; ++q)
+                chunk_desc[first_ch + q] = make_int4(c, first_e + q * CHUNK,
+                                                     min(first_e + v, first_e + (q + 1) * CHUNK), ch);
+    }
+    __syncthreads();
+    const int nh = n_heavy;
+    for (int k = 0; k < nh; ++k) {
+        const int4 h = heavy[k];  // {column, first entry, entries, first chunk}
+        const int hch = (h.z + CHUNK - 1) / CHUNK;
+        for (int q = t; q < hch; q += COLG)
+            chunk_desc[h.w + q] = make_int4(h.x, h.y + q * CHUNK, min(h.y + h.z, h.y + (q + 1) * CHUNK), hch);
     }
 }
 
@@ -258,15 +289,12 @@ __global__ __launch_bounds__(CSC_NT) void csc_place_kernel(const int32_t *__rest
 // gradient mode dW_1[:, c] (+)= g in the flat out x in layout.
 __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
 {
-    const int total_chunks = a.chunk_start[a.d0];
     const int chunk = blockIdx.x;
+    const int total_chunks = a.chunk_start[a.d0];
+    const int4 desc = a.chunk_desc[chunk];  // the launch covers at most the array's capacity
     if (chunk >= total_chunks) return;
-    const int c = a.chunk_col[chunk];
-    const int n_chunks = a.chunk_start[c + 1] - a.chunk_start[c];
-    const int seg_beg = a.col_start[c], seg_end = a.col_start[c + 1];
-    const int e_beg = seg_beg + (chunk - a.chunk_start[c]) * CHUNK;
-    const int e_end = min(seg_end, e_beg + CHUNK);
-    const bool single = (n_chunks == 1);
+    const int c = desc.x, e_beg = desc.y, e_end = desc.z;
+    const bool single = (desc.w == 1);
 
     if (a.vec) {
         const int n4 = a.d1 >> 2;
@@ -388,24 +416,26 @@ int csc_blocks(long long B)
     return (int)nb;
 }
 
-// The per-block column histogram plus the block's slice of row_ptr must fit LDS, and the
-// single-workgroup scan keeps its columns in registers.
+// The per-block column histogram plus the block's slice of row_ptr must fit LDS.
 bool csc_supported(int d0, long long max_B)
 {
-    if (d0 > 16 * SCAN_MAX_GROUPS * 64 - 4096) return false;  // 36,864 columns
     const int nb = csc_blocks(max_B);
     const long long rows_per_block = (max_B + nb - 1) / nb;
     return ((long long)d0 + rows_per_block + 1) * (long long)sizeof(int32_t) <= 150 * 1024;
 }
+
+// cnt[d0 + 1] followed by the per-group totals of the column scan
+size_t csc_cnt_elems(int d0) { return (size_t)d0 + 1 + 2 * (size_t)((d0 + COLG - 1) / COLG); }
 
 size_t csc_hist_elems(long long max_B, int d0) { return (size_t)csc_blocks(max_B) * (size_t)d0; }
 
 
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
                             long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
-                            int32_t *col_start, int32_t *chunk_start, int32_t *chunk_col, int32_t *csc_row,
+                            int32_t *col_start, int32_t *chunk_start, int4 *chunk_desc, int32_t *csc_row,
                             float *csc_val, hipStream_t stream, const LaunchEvents &ev_hist,
-                            const LaunchEvents &ev_scan, const LaunchEvents &ev_place)
+                            const LaunchEvents &ev_colsum, const LaunchEvents &ev_scan,
+                            const LaunchEvents &ev_place)
 {
     (void)nnz;
     const int nb = csc_blocks(B);
@@ -430,11 +460,14 @@ hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, cons
                            rows_per_block, d0, hist);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = launch_kernel(csc_colsum_kernel, dim3((unsigned)((d0 + 255) / 256)), dim3(256), stream, LaunchEvents(),
-                      hist, nb, d0, cnt);
+    const int n_groups = (d0 + COLG - 1) / COLG;
+    int32_t *group_tot = cnt + d0 + 1;  // cnt holds csc_cnt_elems(d0) words
+    e = launch_kernel(csc_colsum_kernel, dim3((unsigned)n_groups), dim3(COLG), stream, ev_colsum, hist, nb, d0,
+                      cnt, group_tot);
     if (e != hipSuccess) return e;
-    e = launch_kernel(col_scan_kernel, dim3(1), dim3(1024), stream, ev_scan, static_cast<const int32_t *>(cnt),
-                      d0, col_start, chunk_start, chunk_col);
+    e = launch_kernel(col_scan_kernel, dim3((unsigned)n_groups), dim3(COLG), stream, ev_scan,
+                      static_cast<const int32_t *>(cnt), static_cast<const int32_t *>(group_tot), d0, col_start,
+                      chunk_start, chunk_desc);
     if (e != hipSuccess) return e;
     if (ev_place.start)
         hipExtLaunchKernelGGL(csc_place_kernel, dim3(nb), dim3(CSC_NT), (unsigned)lds, stream, ev_place.start,
