@@ -3,8 +3,9 @@
 // SGD update (Section 3, Eq. (3): W <- W - eta g) fused with the reduction of the
 // split-K gradient partials, and the replica/global-model blend (Section 6.2).
 // All of these are HBM-bound streaming kernels: coalesced 16-byte accesses, wavefront
-// shuffles for the row reductions, no atomics on data (one atomic ticket per block for the
-// deterministic final loss sum).
+// shuffles for the row reductions, no atomics.  The loss kernel leaves one partial sum per
+// block; the kernel that runs next in the stream anyway (the update, or a one-block
+// finalise kernel in loss-only / gradient-only calls) adds them up in index order.
 #include "hb_internal.h"
 
 namespace hb {
@@ -24,8 +25,8 @@ __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
 // G lanes cooperate on one row (G = power of two <= 64).  Softmax cross-entropy:
 //   l_i = logsumexp(z_i) - z_i[c_i],  delta = (softmax(z_i) - onehot(c_i)) / B.
 // Logistic with one output: l_i = log(1 + exp(-y z)), delta = -y sigma(-y z) / B.
-// The mean loss is summed in a fixed order: per-thread, per-block tree, then the last
-// block to finish adds the block partials in index order.
+// The mean loss is summed in a fixed order: per-thread, per-block tree, then the block
+// partials in index order by loss_finalize() in a later kernel.
 template <int G>
 __global__ __launch_bounds__(LOSS_NT) void loss_kernel(LossArgs a)
 {

@@ -3,8 +3,9 @@
 // matrix-vector products become matrix-matrix products, the dominant cost).
 //
 // gfx950 design: 256-thread workgroups (4 wavefronts of 64), v_mfma_f32_32x32x2_f32
-// blocks, operands staged global -> registers -> LDS with a double-buffered LDS tile so
-// that the next tile's global loads are in flight while the current one is multiplied.
+// blocks, operands staged global -> registers -> LDS with a double-buffered LDS tile:
+// global loads run two k-tiles ahead, the next tile is written to the idle LDS stage
+// early in the current tile, fragments are read one MFMA step ahead, one barrier per tile.
 // K-major operands are read from LDS as 16-byte vectors along k (the k index is permuted
 // identically for both operands, which leaves the contraction unchanged); M-major
 // operands are read one float per lane with the 32 rows of a block on consecutive

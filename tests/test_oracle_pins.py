@@ -470,3 +470,54 @@ def test_bf16_storage_gradient_is_the_plain_gradient_up_to_storage_rounding():
     l_b, gb = oracle.batch_grad(dims0, SIG, CE, pr0, Xr0, y0)
     assert l_a == l_b                       # the loss sees no stored value
     assert np.linalg.norm(ga - gb) / np.linalg.norm(gb) < 2.0 ** -8
+
+
+@pytest.mark.parametrize("dims,act,loss", [((12, 10, 8, 5), SIG, CE), ((12, 10, 8, 5), RELU, CE),
+                                           ((9, 7, 2), RELU, LOGI), ((9, 7, 1), SIG, LOGI)])
+def test_bf16_storage_gradient_against_torch_with_the_roundings_written_out(dims, act, loss):
+    """Second route to the mixed-precision gradient: matrix products and the loss derivative
+    from torch (fp64, autograd for dl/dz_L), with a bf16 cast wherever a hidden activation or
+    a delta is stored.  A missing or misplaced rounding site, a derivative taken from the
+    unrounded activation, or a transposed operand in the oracle shows up here."""
+    torch = pytest.importorskip("torch")
+    B = 23
+    params, X, y = _rand_problem(dims, loss, B, seed=77, bias_scale=0.3)
+    params = params.astype(np.float32)
+    X = X.astype(np.float32)
+    l_o, g_o = oracle.batch_grad_bf16_storage(dims, act, loss, params, X, y)
+
+    def st(t):  # what a bf16 store keeps (through fp32, as a kernel would hold it)
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    Ws, bs = [], []
+    for l, (wo, bo) in enumerate(hi.param_offsets(dims), start=1):
+        W = torch.from_numpy(params[wo:wo + dims[l] * dims[l - 1]].reshape(dims[l], dims[l - 1]).copy())
+        Ws.append(st(W))                                                 # bf16 shadow of the weights
+        bs.append(torch.from_numpy(params[bo:bo + dims[l]].copy()).to(torch.float64))  # biases stay fp32
+    L = len(Ws)
+    acts = [st(torch.from_numpy(X))]
+    for l in range(L):
+        z = acts[-1] @ Ws[l].T + bs[l]
+        if l < L - 1:
+            z = st(torch.sigmoid(z) if act == SIG else torch.clamp(z, min=0.0))
+        acts.append(z)
+    zL = acts[-1].clone().requires_grad_(True)
+    yt = torch.from_numpy(y.astype(np.int64))
+    if loss == CE:
+        lt = torch.nn.functional.cross_entropy(zL, yt, reduction="mean")
+    elif dims[-1] == 2:
+        lt = torch.nn.functional.cross_entropy(zL, (yt + 1) // 2, reduction="mean")
+    else:
+        lt = torch.nn.functional.softplus(-yt.to(torch.float64) * zL[:, 0]).mean()
+    lt.backward()
+    assert l_o == pytest.approx(float(lt.detach()), rel=1e-12)
+    D = st(zL.grad)
+    grads = [None] * L
+    for l in range(L - 1, -1, -1):
+        grads[l] = (D.T @ acts[l], D.sum(dim=0))
+        if l > 0:
+            a = acts[l]
+            deriv = a * (1.0 - a) if act == SIG else (a > 0).to(torch.float64)
+            D = st((D @ Ws[l]) * deriv)
+    flat = np.concatenate([np.concatenate([gw.numpy().ravel(), gb.numpy().ravel()]) for gw, gb in grads])
+    np.testing.assert_allclose(g_o, flat, rtol=1e-9, atol=1e-15)
