@@ -105,6 +105,67 @@ constexpr size_t lds_bytes_bf16()
     return 2 * (size_t)(TileB<BM, BK>::ELEMS + TileB<BN, BK>::ELEMS) * sizeof(bf16_t);
 }
 
+// Epilogue shared by both kernels.  acc[i][j][v] = C(row, col) of the wavefront's block (i, j):
+// row = 8 (v / 4) + 4 h + (v % 4), col = r.  (mw, nw) is the wavefront's first row / column.
+template <int KIND, int TM, int TN>
+__device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)[TM][TN], int mw, int nw, int r,
+                                              int h)
+{
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = nw + j * 32 + r;
+        const bool n_ok = n < a.N;
+        float bias = 0.f;
+        if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {  // groups of 4 consecutive rows
+                const int mq = mw + i * 32 + 8 * q + 4 * h;
+                float x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int m = mq + e;
+                    float val = acc[i][j][4 * q + e];
+                    if (m < a.M && n_ok) {
+                        if (KIND == GEMM_FWD) {
+                            val = act_fwd(val + bias, a.act);
+                            if (a.C_f32) static_cast<float *>(a.C_f32)[(size_t)m * a.ldc + n] = val;
+                        } else if (KIND == GEMM_DA) {
+                            const float o = bf2f(static_cast<const bf16_t *>(a.aux)[(size_t)m * a.ldaux + n]);
+                            if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
+                            else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
+                        } else {  // GEMM_DW
+                            float *cf = static_cast<float *>(a.C_f32) + (size_t)m * a.ldc + n;
+                            if (a.write_grad) {
+                                *cf = val;
+                            } else {
+                                val = *cf - a.lr * val;  // Eq. (3) on the fp32 master weight
+                                *cf = val;
+                            }
+                        }
+                        if (a.C_bf16) static_cast<bf16_t *>(a.C_bf16)[(size_t)m * a.ldcb + n] = f2bf(val);
+                    }
+                    x[e] = val;
+                }
+                if (a.Ct_bf16 && n_ok && !(KIND == GEMM_DW && a.write_grad)) {
+                    bf16_t *ct = static_cast<bf16_t *>(a.Ct_bf16) + (size_t)n * a.ldct + mq;
+                    if (mq + 4 <= a.M && (a.ldct & 3) == 0) {
+                        uint2 pk;
+                        pk.x = (unsigned int)f2bf(x[0]) | ((unsigned int)f2bf(x[1]) << 16);
+                        pk.y = (unsigned int)f2bf(x[2]) | ((unsigned int)f2bf(x[3]) << 16);
+                        *reinterpret_cast<uint2 *>(ct) = pk;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (mq + e < a.M) ct[e] = f2bf(x[e]);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Workgroup tile BM x BN, four wavefronts as 2 x 2, each (BM/2) x (BN/2) = TM x TN blocks of
 // 32 x 32.  Same three-level software pipeline as the fp32 kernel: global loads two k-tiles
 // ahead, LDS double-buffered and written early, fragments of the next k-step read under the
@@ -198,60 +259,259 @@ __global__ __launch_bounds__(NT, 2) void gemm_bf16_nt_kernel(GemmBf16Args a)  //
         mfma_step((G - 1) & 1);
     }
 
-    // ---- epilogue.  acc[i][j][v] = C(row, col): row = 8 (v / 4) + 4 h + (v % 4), col = r
+    epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * WM, n0 + wn * WN, r, h);
+}
+
+// ---- 256 x 256 x 64 kernel with LDS-direct loads ------------------------------------------
+// Used when both operands allow 16-byte loads and the product is large enough for 256 x 256
+// tiles.  512 threads: eight wavefronts as 2 x 4, each 128 x 64 (4 x 2 MFMA blocks), two per
+// SIMD.  Differences from the kernel above:
+//   * operand tiles go global -> LDS directly (global_load_lds_dwordx4: lane i of a wavefront
+//     writes its 16 bytes at LDS base + 16 i), no staging registers and no ds_write;
+//   * a k-tile row is 128 bytes, one whole cache line: with 64-byte rows every line was
+//     fetched twice from L2 (the 32 KB L1 does not keep it for an iteration), and the
+//     L2 -> L1 path (64 B/clk/CU) became the limit; the square tile needs 32 B/clk/CU at
+//     full MFMA rate;
+//   * rows are not padded; the eight 16-byte chunks of tile row R are stored at slot
+//     c ^ swz(R), which keeps both the direct loads (a wavefront fills 1 KB contiguously) and
+//     the MFMA fragment reads free of bank conflicts;
+//   * out-of-range rows of an edge tile are clamped to the last valid row when loading (their
+//     results are never stored), so the main loop has no guards; a K tail shorter than a tile
+//     is multiplied after the loop from a masked, register-staged copy.
+// LDS holds two stages of the A tile and three of the B tile (32 KB each: all 160 KB).  Per
+// iteration every wavefront issues eight loads, two under each of the four MFMA groups (all
+// at once they fill the address queue of the vector memory unit and the MFMA pipes idle while
+// it drains): A of tile kt+1 under the last group of kt-1 and the first of kt, B of tile kt+2
+// under groups two and three of kt, so that every load has at least two MFMA groups (B: more
+// than an iteration) to land; an L2 round trip measured here takes ~550 cycles on average.
+// Waits and barriers inside the main loop are written out by hand: at a workgroup barrier the
+// compiler would also wait for the direct loads that were only just issued.
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// slot permutation of tile row R: bit 0 of the chunk index (the half-wavefront h of a fragment
+// read) is never mixed with the row bits that vary inside one 16-lane group
+__device__ __forceinline__ int swz(int R)
+{
+    const int q = (R >> 1) & 7;
+    return ((q & 3) << 1) | (q >> 2);
+}
+
+constexpr int DMA_NT = 512;
+constexpr int DMA_BM = 256, DMA_BN = 256, DMA_BK = 64;
+constexpr int DMA_ROW_BYTES = DMA_BK * 2;  // 128
+constexpr int DMA_A_BYTES = DMA_BM * DMA_ROW_BYTES, DMA_B_BYTES = DMA_BN * DMA_ROW_BYTES;
+constexpr int DMA_A_STAGES = 2, DMA_B_STAGES = 3;
+constexpr int DMA_B_BASE = DMA_A_STAGES * DMA_A_BYTES;
+constexpr size_t DMA_LDS_BYTES = (size_t)DMA_B_BASE + (size_t)DMA_B_STAGES * DMA_B_BYTES;  // 163,840: all of a CU's LDS
+
+template <int KIND>
+__global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a)
+{
+    constexpr int BM = DMA_BM, BN = DMA_BN, BK = DMA_BK;
+    constexpr int TM = 4, TN = 2;  // 32 x 32 blocks per wavefront: 128 x 64
+    constexpr int G = BK / 16;     // MFMA k-steps per tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS bases of the direct loads are scalars
+    const int r = lane & 31, h = lane >> 5;
+    const int wm = wave & 1, wn = wave >> 1;
+
+    int id = blockIdx.x;
+    const int T = gridDim.x;
+    if ((T & 7) == 0) id = (id & 7) * (T >> 3) + (id >> 3);  // XCD-aware tile order
+    const int tile_m = id / a.tiles_n, tile_n = id - tile_m * a.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int nkf = a.K / BK;  // full k-tiles
+
+    const unsigned char *__restrict__ Ab = static_cast<const unsigned char *>(a.A);
+    const unsigned char *__restrict__ Bb = static_cast<const unsigned char *>(a.B);
+
+    // ---- global side of the direct loads.  One wavefront load covers 8 tile rows (1 KB):
+    // lane -> (row lane / 8, slot lane % 8); the wavefront takes row blocks wave, wave + 8, ..
+    const int blk_row = lane >> 3;
+    unsigned offA[4], offB[4];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + r;
-        const bool n_ok = n < a.N;
-        float bias = 0.f;
-        if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+    for (int v = 0; v < 4; ++v) {
+        const int R = (wave + 8 * v) * 8 + blk_row;
+        const int chunk = (lane & 7) ^ swz(R);  // the chunk whose slot is lane % 8
+        offA[v] = (unsigned)((size_t)min(m0 + R, a.M - 1) * (size_t)a.lda * 2 + chunk * 16);
+        offB[v] = (unsigned)((size_t)min(n0 + R, a.N - 1) * (size_t)a.ldb * 2 + chunk * 16);
+    }
+    // loads first .. first + 1 of the wavefront's four of an A / B tile (tile t -> given stage)
+    auto issue_a = [&](int t, int stage, int first) {
+        unsigned char *st = smem_raw + stage * DMA_A_BYTES;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+        for (int v = first; v < first + 2; ++v)
+            __builtin_amdgcn_global_load_lds((gptr_t)(Ab + (size_t)t * DMA_ROW_BYTES + offA[v]),
+                                             (lptr_t)(st + (wave + 8 * v) * 1024), 16, 0, 0);
+    };
+    auto issue_b = [&](int t, int stage, int first) {
+        unsigned char *st = smem_raw + DMA_B_BASE + stage * DMA_B_BYTES;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {  // groups of 4 consecutive rows
-                const int mq = m0 + wm * WM + i * 32 + 8 * q + 4 * h;
-                float x[4];
+        for (int v = first; v < first + 2; ++v)
+            __builtin_amdgcn_global_load_lds((gptr_t)(Bb + (size_t)t * DMA_ROW_BYTES + offB[v]),
+                                             (lptr_t)(st + (wave + 8 * v) * 1024), 16, 0, 0);
+    };
+
+    // ---- LDS side of the fragment reads: lane (r, h) reads chunk 2 kk + h of its row.  The
+    // block offsets i * 32 rows leave (R >> 1) & 7 unchanged, so the swizzle depends on r only.
+    const int fr = swz(r);
+    const int a_off = (wm * 128 + r) * DMA_ROW_BYTES + ((h ^ fr) << 4);  // k-step kk: a_off ^ (kk << 5)
+    const int b_off = DMA_B_BASE + (wn * 64 + r) * DMA_ROW_BYTES + ((h ^ fr) << 4);
+    v8bf fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int slot, int sa, int sb, int kk) {
+        const unsigned char *pa = smem_raw + sa * DMA_A_BYTES;
+        const unsigned char *pb = smem_raw + sb * DMA_B_BYTES;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int m = mq + e;
-                    float val = acc[i][j][4 * q + e];
-                    if (m < a.M && n_ok) {
-                        if (KIND == GEMM_FWD) {
-                            val = act_fwd(val + bias, a.act);
-                            if (a.C_f32) static_cast<float *>(a.C_f32)[(size_t)m * a.ldc + n] = val;
-                        } else if (KIND == GEMM_DA) {
-                            const float o = bf2f(static_cast<const bf16_t *>(a.aux)[(size_t)m * a.ldaux + n]);
-                            if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
-                            else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
-                        } else {  // GEMM_DW
-                            float *cf = static_cast<float *>(a.C_f32) + (size_t)m * a.ldc + n;
-                            if (a.write_grad) {
-                                *cf = val;
-                            } else {
-                                val = *cf - a.lr * val;  // Eq. (3) on the fp32 master weight
-                                *cf = val;
-                            }
-                        }
-                        if (a.C_bf16) static_cast<bf16_t *>(a.C_bf16)[(size_t)m * a.ldcb + n] = f2bf(val);
+        for (int i = 0; i < TM; ++i)
+            fa[slot][i] = *reinterpret_cast<const v8bf *>(pa + ((a_off ^ (kk << 5)) + i * 32 * DMA_ROW_BYTES));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[slot][j] = *reinterpret_cast<const v8bf *>(pb + ((b_off ^ (kk << 5)) + j * 32 * DMA_ROW_BYTES));
+    };
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    auto mfma_step = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+    };
+    // One MFMA group: the eight MFMAs of the k-step whose fragments are in `slot`, and in
+    // their shadow (a wavefront can issue other instructions while its MFMA executes) the
+    // requests for the next group's fragments, two after each of the first three MFMAs, and
+    // two direct loads after the fifth.  Clumped in front of the group instead, these
+    // requests are issued by both wavefronts of a SIMD at the same time (the barrier keeps
+    // them in step) and the MFMA pipe idles meanwhile.  Only the requests are conditional,
+    // so that there is one MFMA stream.
+    auto group = [&](int slot, bool rd, int sa, int sb, int kk, bool ld, bool is_a, int t, int stage, int first) {
+        const unsigned char *pa = smem_raw + sa * DMA_A_BYTES;
+        const unsigned char *pb = smem_raw + sb * DMA_B_BYTES;
+        const int rs = slot ^ 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+                const int b = i * TN + j;
+                __builtin_amdgcn_sched_barrier(0);
+                if (b < 2) {
+                    if (rd) {
+#pragma unroll
+                        for (int q = 2 * b; q < 2 * b + 2; ++q)
+                            fa[rs][q] = *reinterpret_cast<const v8bf *>(pa + ((a_off ^ (kk << 5)) + q * 32 * DMA_ROW_BYTES));
                     }
-                    x[e] = val;
-                }
-                if (a.Ct_bf16 && n_ok && !(KIND == GEMM_DW && a.write_grad)) {
-                    bf16_t *ct = static_cast<bf16_t *>(a.Ct_bf16) + (size_t)n * a.ldct + mq;
-                    if (mq + 4 <= a.M && (a.ldct & 3) == 0) {
-                        uint2 pk;
-                        pk.x = (unsigned int)f2bf(x[0]) | ((unsigned int)f2bf(x[1]) << 16);
-                        pk.y = (unsigned int)f2bf(x[2]) | ((unsigned int)f2bf(x[3]) << 16);
-                        *reinterpret_cast<uint2 *>(ct) = pk;
-                    } else {
+                } else if (b == 2) {
+                    if (rd) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (mq + e < a.M) ct[e] = f2bf(x[e]);
+                        for (int q = 0; q < TN; ++q)
+                            fb[rs][q] = *reinterpret_cast<const v8bf *>(pb + ((b_off ^ (kk << 5)) + q * 32 * DMA_ROW_BYTES));
+                    }
+                } else if (b == 4) {
+                    if (ld) {
+                        if (is_a) issue_a(t, stage, first);
+                        else issue_b(t, stage, first);
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
+    };
+
+    if (nkf > 0) {
+        issue_a(0, 0, 0);
+        issue_a(0, 0, 2);
+        issue_b(0, 0, 0);
+        issue_b(0, 0, 2);
+        if (nkf > 1) {
+            issue_b(1, 1, 0);
+            issue_b(1, 1, 2);
+            issue_a(1, 1, 0);
+            asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");  // tile 0 landed
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+        read_frags(0, 0, 0, 0);
+        static_assert(G == 4, "the load schedule below is written for four k-steps per tile");
+        int b_cur = 0, b_nxt = 1, b_ld = 2;  // B stages of tiles kt, kt+1, kt+2
+        for (int kt = 0; kt < nkf; ++kt) {
+            const int a_cur = kt & 1;
+            const bool next = (kt + 1 < nkf), next2 = (kt + 2 < nkf);
+            // The explicit lgkmcnt(0) at the head of a group tells the compiler that the
+            // fragments requested during the previous group have arrived (they have: five
+            // MFMAs lie in between); it cannot track them across the small branches.
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            group(0, true, a_cur, b_cur, 1, next, true, kt + 1, a_cur ^ 1, 2);   // + second half of A(kt+1)
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            group(1, true, a_cur, b_cur, 2, next2, false, kt + 2, b_ld, 0);      // + B(kt+2): its stage held B(kt-1)
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            group(0, true, a_cur, b_cur, 3, next2, false, kt + 2, b_ld, 2);
+            // Tile kt+1 must have landed (this wavefront's share; the barrier covers the others');
+            // the four loads of B(kt+2) just issued may stay in flight.  This wavefront's reads of
+            // tile kt must be done before anyone overwrites its stages.
+            if (next2) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) again, this time visible to the compiler
+            // last k-step of tile kt; k-step 0 of tile kt+1 is requested from the stages that have
+            // just been completed, and the first half of A(kt+2) goes into the stage just released
+            group(1, next, a_cur ^ 1, b_nxt, 0, next2, true, kt + 2, a_cur, 0);
+            const int t = b_cur;
+            b_cur = b_nxt;
+            b_nxt = b_ld;
+            b_ld = t;
         }
     }
+
+    // ---- K tail (fewer than BK columns left): masked copy through registers into stage 0
+    const int ktail = a.K - nkf * BK;
+    if (ktail > 0) {
+        __syncthreads();  // everybody is done with the main loop's stages
+        const int kbase = nkf * BK;
+#pragma unroll
+        for (int v = 0; v < (BM + BN) * 8 / DMA_NT; ++v) {  // 16-byte chunks of both tiles over the workgroup
+            const int idx = tid + v * DMA_NT;
+            const bool isA = idx < BM * 8;
+            const int q = isA ? idx : idx - BM * 8;
+            const int R = q >> 3, c = q & 7;
+            const int k = kbase + c * 8;
+            uint4 x = {0u, 0u, 0u, 0u};
+            if (k < a.K) {  // rows are padded to 8 elements, so the 16 bytes are in bounds
+                const int grow = isA ? min(m0 + R, a.M - 1) : min(n0 + R, a.N - 1);
+                const unsigned char *p = isA ? Ab + ((size_t)grow * (size_t)a.lda + k) * 2
+                                             : Bb + ((size_t)grow * (size_t)a.ldb + k) * 2;
+                x = *reinterpret_cast<const uint4 *>(p);
+                const int valid = a.K - k;  // elements of this chunk that belong to the matrix
+                if (valid < 8) {
+                    unsigned int w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (2 * e >= valid) w[e] = 0u;
+                        else if (2 * e + 1 >= valid) w[e] &= 0xffffu;
+                    }
+                    x = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            *reinterpret_cast<uint4 *>(smem_raw + (isA ? 0 : DMA_B_BASE) + R * DMA_ROW_BYTES +
+                                       ((c ^ swz(R)) << 4)) = x;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < G; ++kk) {
+            read_frags(kk & 1, 0, 0, kk);
+            mfma_step(kk & 1);
+        }
+    }
+
+    epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * 128, n0 + wn * 64, r, h);
 }
 
 // out[c][r] = in[r][c] for bf16 matrices (R x C, leading dimensions ldi / ldo), 64 x 64 tiles
@@ -339,17 +599,47 @@ int env_int_bf16(const char *name, int dflt)
     return (v && *v) ? atoi(v) : dflt;
 }
 
+
+hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, const LaunchEvents &ev)
+{
+    void (*k)(GemmBf16Args) = kind == GEMM_FWD  ? gemm_bf16_dma_kernel<GEMM_FWD>
+                              : kind == GEMM_DA ? gemm_bf16_dma_kernel<GEMM_DA>
+                                                : gemm_bf16_dma_kernel<GEMM_DW>;
+    static bool attr_set[3] = {false, false, false};
+    if (!attr_set[kind]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)DMA_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set[kind] = true;
+    }
+    a.tiles_m = (a.M + DMA_BM - 1) / DMA_BM;
+    a.tiles_n = (a.N + DMA_BN - 1) / DMA_BN;
+    const long long tiles = (long long)a.tiles_m * a.tiles_n;
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)tiles), block(DMA_NT);
+    if (ev.start)
+        hipExtLaunchKernelGGL(k, grid, block, (unsigned)DMA_LDS_BYTES, stream, ev.start, ev.stop, 0, a);
+    else
+        hipLaunchKernelGGL(k, grid, block, DMA_LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, const LaunchEvents &ev)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
-    // 256 x 128 tiles (4 x 2 MFMA blocks per wavefront: 6 fragment reads per 8 MFMAs) when they
-    // still give two workgroups per CU, else 128 x 128.  HB_BF16_TILE = 1 / 2 forces (tuning aid).
+    // The 256 x 256 LDS-direct kernel when both operands allow it and its tiles cover at least
+    // half of the CUs; else 256 x 128 tiles when they give two workgroups per CU, else 128 x 128.
+    // HB_BF16_TILE = 1 / 2 / 3 / 4 forces a kernel (tuning aid; 4 = 256 x 128, 1 = LDS-direct).
     static const int forced = env_int_bf16("HB_BF16_TILE", 0);
+    const long long dma_tiles = (long long)((a.M + DMA_BM - 1) / DMA_BM) * ((a.N + DMA_BN - 1) / DMA_BN);
     const long long big_tiles = (long long)((a.M + 255) / 256) * ((a.N + 127) / 128);
-    const bool big = forced == 1 ? true : forced == 2 ? false : forced == 3 ? false : big_tiles >= 512;
-    if (big) return launch_shape_bf16<256, 128, 32>(kind, a, stream, ev);
+    // the LDS-direct kernel addresses each operand with 32-bit byte offsets from its base
+    const bool dma_ok = a.a_vec && a.b_vec && (unsigned long long)a.M * (unsigned long long)a.lda * 2 < (1ull << 32) &&
+                        (unsigned long long)a.N * (unsigned long long)a.ldb * 2 < (1ull << 32);
+    if (dma_ok && (forced == 1 || (forced == 0 && dma_tiles >= 128))) return launch_dma_bf16(kind, a, stream, ev);
+    if (forced == 4 || (forced == 0 && big_tiles >= 512)) return launch_shape_bf16<256, 128, 32>(kind, a, stream, ev);
     if (forced == 3) return launch_shape_bf16<128, 128, 32>(kind, a, stream, ev);
     return launch_shape_bf16<128, 128, 64>(kind, a, stream, ev);
 }
