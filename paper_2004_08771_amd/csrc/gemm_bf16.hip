@@ -123,6 +123,20 @@ __device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)
             for (int q = 0; q < 4; ++q) {  // groups of 4 consecutive rows
                 const int mq = mw + i * 32 + 8 * q + 4 * h;
                 float x[4];
+                // backward-data: the four activations this lane needs are adjacent in the
+                // transposed copy (the same access pattern as the transposed store below); its
+                // rows are padded to a multiple of 4, so the 8 bytes are in bounds whenever
+                // the first of the four rows is
+                float o4[4] = {0.f, 0.f, 0.f, 0.f};
+                const bool use_t = (KIND == GEMM_DA) && a.aux_t != nullptr && (a.ldauxt & 3) == 0;
+                if (KIND == GEMM_DA && use_t && n_ok && mq < a.M) {
+                    const uint2 pk = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.aux_t) +
+                                                                      (size_t)n * a.ldauxt + mq);
+                    o4[0] = __uint_as_float(pk.x << 16);
+                    o4[1] = __uint_as_float(pk.x & 0xffff0000u);
+                    o4[2] = __uint_as_float(pk.y << 16);
+                    o4[3] = __uint_as_float(pk.y & 0xffff0000u);
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int m = mq + e;
@@ -132,7 +146,8 @@ __device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)
                             val = act_fwd(val + bias, a.act);
                             if (a.C_f32) static_cast<float *>(a.C_f32)[(size_t)m * a.ldc + n] = val;
                         } else if (KIND == GEMM_DA) {
-                            const float o = bf2f(static_cast<const bf16_t *>(a.aux)[(size_t)m * a.ldaux + n]);
+                            const float o = use_t ? o4[e]
+                                                  : bf2f(static_cast<const bf16_t *>(a.aux)[(size_t)m * a.ldaux + n]);
                             if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
                             else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
                         } else {  // GEMM_DW
@@ -558,7 +573,28 @@ __global__ __launch_bounds__(256) void rowsum_bias_kernel(const bf16_t *__restri
     if (j >= d) return;
     const bf16_t *row = Dt + (size_t)j * ld;
     float s = 0.f;
-    for (long long b = lane; b < B; b += 64) s += bf2f(row[b]);
+    long long b0 = 0;
+    if ((ld & 7) == 0 && (reinterpret_cast<size_t>(Dt) & 15) == 0) {
+        // 16 bytes (8 values) per lane and load, four loads in flight
+        const long long nvec = B >> 3;
+        const uint4 *rv = reinterpret_cast<const uint4 *>(row);
+        for (long long v0 = 0; v0 < nvec; v0 += 256) {
+            uint4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const long long v = v0 + u * 64 + lane;
+                x[u] = (v < nvec) ? rv[v] : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned int w[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s += __uint_as_float(w[e] << 16) + __uint_as_float(w[e] & 0xffff0000u);
+            }
+        }
+        b0 = nvec << 3;
+    }
+    for (long long b = b0 + lane; b < B; b += 64) s += bf2f(row[b]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
     if (lane == 0) {

@@ -602,6 +602,8 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.b_vec = 1;
             g.aux = m->act_bf[l - 1];
             g.ldaux = m->ld8[l - 1];
+            g.aux_t = m->act_t[l - 1];  // written by the forward pass of layer l-1
+            g.ldauxt = ldB;
             g.act = m->act;
             g.C_bf16 = m->delta_bf[(l - 1) & 1];
             g.ldcb = m->ld8[l - 1];

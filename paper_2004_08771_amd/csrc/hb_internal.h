@@ -88,8 +88,10 @@ struct GemmBf16Args {
     void *Ct_bf16;
     long long ldct;
     const float *bias;
-    const void *aux;
+    const void *aux;       // backward-data: the layer's bf16 activations [M x ldaux] ...
     long long ldaux;
+    const void *aux_t;     // ... and, optional, their transposed copy [N x ldauxt]: four rows per 8-byte load
+    long long ldauxt;
     int act;
     int write_grad;
     float lr;

@@ -478,6 +478,10 @@ def check_bf16_case(dims, act, loss, params, X, y, lr):
     ((33, 17, 5, 2), hi.ACT_RELU, hi.LOSS_LOGISTIC, 77),
     ((48, 1), hi.ACT_SIGMOID, hi.LOSS_LOGISTIC, 200),
     ((200, 264, 136, 7), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 1),
+    # large enough for the 256 x 256 kernel in the first forward product (K = 72: one k-tile
+    # and a tail) and the backward-data product (K = 136: two and a tail), with ragged edges
+    # in every dimension: 4001 = 15 * 256 + 161 rows, 2050 = 8 * 256 + 2 columns
+    ((72, 2050, 136), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 4001),
 ])
 def test_bf16_small_shapes_match_oracle(dims, act, loss, B):
     params, X, y = _problem(dims, loss, B, seed=500 + B + len(dims), bias_scale=0.2)
