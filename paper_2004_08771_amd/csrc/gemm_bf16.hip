@@ -106,66 +106,103 @@ constexpr size_t lds_bytes_bf16()
 }
 
 // Epilogue shared by both kernels.  acc[i][j][v] = C(row, col) of the wavefront's block (i, j):
-// row = 8 (v / 4) + 4 h + (v % 4), col = r.  (mw, nw) is the wavefront's first row / column.
-template <int KIND, int TM, int TN>
-__device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)[TM][TN], int mw, int nw, int r,
-                                              int h)
+// row = 8 (v / 4) + 4 h + (v % 4), col = r.  (mw, nw) is the wavefront's first row / column and
+// must be wavefront-uniform: every address below is a scalar base (row, column block) plus a
+// per-lane byte offset that does not change during the epilogue, so the 128 outputs of a lane
+// cost no address registers.
+// FULL: the wavefront's tile lies inside the matrix and the 8-byte accesses are aligned; no
+// guards, and what a column block needs from memory (bias, the activations of the
+// backward-data derivative, the fp32 master weights of the fused update) is requested before
+// its first use, so that those loads are in flight together instead of one round trip each.
+template <int KIND, int TM, int TN, bool FULL>
+__device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (&acc)[TM][TN], int mw, int nw, int r,
+                                                   int h)
 {
+    const bool has_cf = a.C_f32 != nullptr, has_cb = a.C_bf16 != nullptr;
+    const bool has_ct = a.Ct_bf16 != nullptr && !(KIND == GEMM_DW && a.write_grad);
+    const bool use_t = (KIND == GEMM_DA) && a.aux_t != nullptr && (a.ldauxt & 3) == 0;
+    const bool ct_vec = (a.ldct & 3) == 0;
+    // per-lane byte offsets (row part 4 h, column part r)
+    const unsigned lo_cf = (unsigned)(4 * h * (int)a.ldc + r) * 4u;
+    const unsigned lo_cb = (unsigned)(4 * h * (int)a.ldcb + r) * 2u;
+    const unsigned lo_ct = (unsigned)(r * (int)a.ldct + 4 * h) * 2u;
+    const unsigned lo_at = (unsigned)(r * (int)a.ldauxt + 4 * h) * 2u;
+    const unsigned lo_ax = (unsigned)(4 * h * (int)a.ldaux + r) * 2u;
+    unsigned char *const cf0 = static_cast<unsigned char *>(a.C_f32);
+    unsigned char *const cb0 = static_cast<unsigned char *>(a.C_bf16);
+    unsigned char *const ct0 = static_cast<unsigned char *>(a.Ct_bf16);
+    const unsigned char *const at0 = static_cast<const unsigned char *>(a.aux_t);
+    const unsigned char *const ax0 = static_cast<const unsigned char *>(a.aux);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int n = nw + j * 32 + r;
-        const bool n_ok = n < a.N;
+        const int nb = nw + j * 32;  // uniform
+        const int n = nb + r;
+        const bool n_ok = FULL || n < a.N;
         float bias = 0.f;
         if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+        uint2 ot[TM][4];
+        if (KIND == GEMM_DA && FULL) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    ot[i][q] = *reinterpret_cast<const uint2 *>(
+                        at0 + ((size_t)nb * a.ldauxt + (mw + i * 32 + 8 * q)) * 2 + lo_at);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            float w[16];
+            if (KIND == GEMM_DW && FULL && !a.write_grad) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    w[v] = *reinterpret_cast<const float *>(
+                        cf0 + ((size_t)(mw + i * 32 + 8 * (v >> 2) + (v & 3)) * a.ldc + nb) * 4 + lo_cf);
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {  // groups of 4 consecutive rows
-                const int mq = mw + i * 32 + 8 * q + 4 * h;
-                float x[4];
-                // backward-data: the four activations this lane needs are adjacent in the
-                // transposed copy (the same access pattern as the transposed store below); its
-                // rows are padded to a multiple of 4, so the 8 bytes are in bounds whenever
-                // the first of the four rows is
-                float o4[4] = {0.f, 0.f, 0.f, 0.f};
-                const bool use_t = (KIND == GEMM_DA) && a.aux_t != nullptr && (a.ldauxt & 3) == 0;
-                if (KIND == GEMM_DA && use_t && n_ok && mq < a.M) {
-                    const uint2 pk = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.aux_t) +
-                                                                      (size_t)n * a.ldauxt + mq);
-                    o4[0] = __uint_as_float(pk.x << 16);
-                    o4[1] = __uint_as_float(pk.x & 0xffff0000u);
-                    o4[2] = __uint_as_float(pk.y << 16);
-                    o4[3] = __uint_as_float(pk.y & 0xffff0000u);
+                const int mb = mw + i * 32 + 8 * q;  // uniform; this lane's rows are mb + 4 h + e
+                const int mq = mb + 4 * h;
+                uint2 o4 = {0u, 0u};
+                if (KIND == GEMM_DA) {
+                    if (FULL) o4 = ot[i][q];
+                    else if (use_t && n_ok && mq < a.M)  // rows of the copy are padded to 4: in bounds
+                        o4 = *reinterpret_cast<const uint2 *>(at0 + ((size_t)nb * a.ldauxt + mb) * 2 + lo_at);
                 }
+                float x[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int m = mq + e;
                     float val = acc[i][j][4 * q + e];
-                    if (m < a.M && n_ok) {
+                    if (FULL || (mq + e < a.M && n_ok)) {
                         if (KIND == GEMM_FWD) {
                             val = act_fwd(val + bias, a.act);
-                            if (a.C_f32) static_cast<float *>(a.C_f32)[(size_t)m * a.ldc + n] = val;
+                            if (has_cf)
+                                *reinterpret_cast<float *>(cf0 + ((size_t)(mb + e) * a.ldc + nb) * 4 + lo_cf) = val;
                         } else if (KIND == GEMM_DA) {
-                            const float o = use_t ? o4[e]
-                                                  : bf2f(static_cast<const bf16_t *>(a.aux)[(size_t)m * a.ldaux + n]);
+                            float o;
+                            if (FULL || use_t) {
+                                const unsigned int pw = (e < 2) ? o4.x : o4.y;
+                                o = __uint_as_float((e & 1) ? (pw & 0xffff0000u) : (pw << 16));
+                            } else {
+                                o = bf2f(*reinterpret_cast<const bf16_t *>(ax0 + ((size_t)(mb + e) * a.ldaux + nb) * 2 +
+                                                                            lo_ax));
+                            }
                             if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
                             else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
                         } else {  // GEMM_DW
-                            float *cf = static_cast<float *>(a.C_f32) + (size_t)m * a.ldc + n;
-                            if (a.write_grad) {
-                                *cf = val;
-                            } else {
-                                val = *cf - a.lr * val;  // Eq. (3) on the fp32 master weight
-                                *cf = val;
-                            }
+                            float *cf = reinterpret_cast<float *>(cf0 + ((size_t)(mb + e) * a.ldc + nb) * 4 + lo_cf);
+                            if (!a.write_grad) val = (FULL ? w[4 * q + e] : *cf) - a.lr * val;  // Eq. (3), fp32 master
+                            *cf = val;
                         }
-                        if (a.C_bf16) static_cast<bf16_t *>(a.C_bf16)[(size_t)m * a.ldcb + n] = f2bf(val);
+                        if (has_cb)
+                            *reinterpret_cast<bf16_t *>(cb0 + ((size_t)(mb + e) * a.ldcb + nb) * 2 + lo_cb) = f2bf(val);
                     }
                     x[e] = val;
                 }
-                if (a.Ct_bf16 && n_ok && !(KIND == GEMM_DW && a.write_grad)) {
-                    bf16_t *ct = static_cast<bf16_t *>(a.Ct_bf16) + (size_t)n * a.ldct + mq;
-                    if (mq + 4 <= a.M && (a.ldct & 3) == 0) {
+                if (has_ct && n_ok) {
+                    unsigned char *ct = ct0 + ((size_t)nb * a.ldct + mb) * 2 + lo_ct;
+                    if (FULL || (mq + 4 <= a.M && ct_vec)) {
                         uint2 pk;
                         pk.x = (unsigned int)f2bf(x[0]) | ((unsigned int)f2bf(x[1]) << 16);
                         pk.y = (unsigned int)f2bf(x[2]) | ((unsigned int)f2bf(x[3]) << 16);
@@ -173,12 +210,26 @@ __device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (mq + e < a.M) ct[e] = f2bf(x[e]);
+                            if (mq + e < a.M) reinterpret_cast<bf16_t *>(ct)[e] = f2bf(x[e]);
                     }
                 }
+                // keep the scheduler from pulling later groups' conversions up: with 128
+                // accumulators live it runs out of registers
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
+}
+
+template <int KIND, int TM, int TN>
+__device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)[TM][TN], int mw, int nw, int r,
+                                              int h)
+{
+    const bool full = (mw + 32 * TM <= a.M) && (nw + 32 * TN <= a.N) &&
+                      (a.Ct_bf16 == nullptr || (a.ldct & 3) == 0) &&
+                      (KIND != GEMM_DA || (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
+    if (full) epilogue_bf16_impl<KIND, TM, TN, true>(a, acc, mw, nw, r, h);
+    else epilogue_bf16_impl<KIND, TM, TN, false>(a, acc, mw, nw, r, h);
 }
 
 // Workgroup tile BM x BN, four wavefronts as 2 x 2, each (BM/2) x (BN/2) = TM x TN blocks of
@@ -274,7 +325,8 @@ __global__ __launch_bounds__(NT, 2) void gemm_bf16_nt_kernel(GemmBf16Args a)  //
         mfma_step((G - 1) & 1);
     }
 
-    epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * WM, n0 + wn * WN, r, h);
+    epilogue_bf16<KIND, TM, TN>(a, acc, __builtin_amdgcn_readfirstlane(m0 + wm * WM),
+                                __builtin_amdgcn_readfirstlane(n0 + wn * WN), r, h);
 }
 
 // ---- 256 x 256 x 64 kernel with LDS-direct loads ------------------------------------------
