@@ -391,10 +391,13 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
     if ((T & 7) == 0) id = (id & 7) * (T >> 3) + (id >> 3);  // XCD-aware tile order
     const int tile_m = id / a.tiles_n, tile_n = id - tile_m * a.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int nkf = a.K / BK;  // full k-tiles
+    // slice of the contraction handled by this workgroup (blockIdx.y; the whole of it unless split)
+    const int kbeg = (a.k_chunk > 0) ? (int)blockIdx.y * a.k_chunk : 0;
+    const int klen = (a.k_chunk > 0) ? min(a.K - kbeg, a.k_chunk) : a.K;
+    const int nkf = klen / BK;  // full k-tiles
 
-    const unsigned char *__restrict__ Ab = static_cast<const unsigned char *>(a.A);
-    const unsigned char *__restrict__ Bb = static_cast<const unsigned char *>(a.B);
+    const unsigned char *__restrict__ Ab = static_cast<const unsigned char *>(a.A) + (size_t)kbeg * 2;
+    const unsigned char *__restrict__ Bb = static_cast<const unsigned char *>(a.B) + (size_t)kbeg * 2;
 
     // ---- global side of the direct loads.  One wavefront load covers 8 tile rows (1 KB):
     // lane -> (row lane / 8, slot lane % 8); the wavefront takes row blocks wave, wave + 8, ..
@@ -539,10 +542,10 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
     }
 
     // ---- K tail (fewer than BK columns left): masked copy through registers into stage 0
-    const int ktail = a.K - nkf * BK;
+    const int ktail = klen - nkf * BK;
     if (ktail > 0) {
         __syncthreads();  // everybody is done with the main loop's stages
-        const int kbase = nkf * BK;
+        const int kbase = nkf * BK;  // relative to the slice
 #pragma unroll
         for (int v = 0; v < (BM + BN) * 8 / DMA_NT; ++v) {  // 16-byte chunks of both tiles over the workgroup
             const int idx = tid + v * DMA_NT;
@@ -551,12 +554,12 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
             const int R = q >> 3, c = q & 7;
             const int k = kbase + c * 8;
             uint4 x = {0u, 0u, 0u, 0u};
-            if (k < a.K) {  // rows are padded to 8 elements, so the 16 bytes are in bounds
+            if (k < klen) {  // rows are padded to 8 elements, so the 16 bytes are in bounds
                 const int grow = isA ? min(m0 + R, a.M - 1) : min(n0 + R, a.N - 1);
                 const unsigned char *p = isA ? Ab + ((size_t)grow * (size_t)a.lda + k) * 2
                                              : Bb + ((size_t)grow * (size_t)a.ldb + k) * 2;
                 x = *reinterpret_cast<const uint4 *>(p);
-                const int valid = a.K - k;  // elements of this chunk that belong to the matrix
+                const int valid = klen - k;  // elements of this chunk that belong to the slice
                 if (valid < 8) {
                     unsigned int w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
@@ -578,7 +581,13 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
         }
     }
 
-    epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * 128, n0 + wn * 64, r, h);
+    if (KIND == GEMM_DW && a.k_chunk > 0) {
+        GemmBf16Args as = a;  // this slice's partial product
+        as.C_f32 = static_cast<float *>(a.C_f32) + (size_t)blockIdx.y * (size_t)a.c_split_stride;
+        epilogue_bf16<KIND, TM, TN>(as, acc, m0 + wm * 128, n0 + wn * 64, r, h);
+    } else {
+        epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * 128, n0 + wn * 64, r, h);
+    }
 }
 
 // out[c][r] = in[r][c] for bf16 matrices (R x C, leading dimensions ldi / ldo), 64 x 64 tiles
@@ -612,6 +621,41 @@ __global__ __launch_bounds__(256) void shadow_kernel(const float *__restrict__ W
     __syncthreads();
     for (int k = ty; k < 64; k += 4)
         if (c0 + k < C && r0 + tx < R) shadow_t[(size_t)(c0 + k) * ldt + r0 + tx] = t[tx][k];
+}
+
+// Sum of the slices of a split weight gradient, then Eq. (3) on the fp32 master weights or a
+// plain store of the gradient.  Slices are added in index order (deterministic).
+__global__ __launch_bounds__(256) void dw_reduce_kernel(const float *__restrict__ partial, int splits,
+                                                        long long stride, long long count,
+                                                        float *__restrict__ master, float *__restrict__ grad,
+                                                        float lr)
+{
+    const bool vec = ((stride & 3) == 0) && ((count & 3) == 0) && ((reinterpret_cast<size_t>(partial) & 15) == 0) &&
+                     ((reinterpret_cast<size_t>(grad ? grad : master) & 15) == 0);
+    const long long step = (long long)gridDim.x * 256;
+    if (vec) {
+        for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < (count >> 2); q += step) {
+            float4 s = {0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < splits; ++k) {
+                const float4 p = *reinterpret_cast<const float4 *>(partial + (size_t)k * stride + 4 * q);
+                s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+            }
+            if (grad) {
+                *reinterpret_cast<float4 *>(grad + 4 * q) = s;
+            } else {
+                float4 w = *reinterpret_cast<float4 *>(master + 4 * q);
+                w.x -= lr * s.x; w.y -= lr * s.y; w.z -= lr * s.z; w.w -= lr * s.w;
+                *reinterpret_cast<float4 *>(master + 4 * q) = w;
+            }
+        }
+    } else {
+        for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count; i += step) {
+            float s = 0.f;
+            for (int k = 0; k < splits; ++k) s += partial[(size_t)k * stride + i];
+            if (grad) grad[i] = s;
+            else master[i] -= lr * s;
+        }
+    }
 }
 
 // Bias gradient from the transposed delta (one wavefront per output unit j):
@@ -704,7 +748,8 @@ hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, co
     a.tiles_n = (a.N + DMA_BN - 1) / DMA_BN;
     const long long tiles = (long long)a.tiles_m * a.tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)tiles), block(DMA_NT);
+    const int splits = (kind == GEMM_DW && a.k_chunk > 0) ? (a.K + a.k_chunk - 1) / a.k_chunk : 1;
+    const dim3 grid((unsigned)tiles, (unsigned)splits), block(DMA_NT);
     if (ev.start)
         hipExtLaunchKernelGGL(k, grid, block, (unsigned)DMA_LDS_BYTES, stream, ev.start, ev.stop, 0, a);
     else
@@ -726,10 +771,39 @@ hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, c
     // the LDS-direct kernel addresses each operand with 32-bit byte offsets from its base
     const bool dma_ok = a.a_vec && a.b_vec && (unsigned long long)a.M * (unsigned long long)a.lda * 2 < (1ull << 32) &&
                         (unsigned long long)a.N * (unsigned long long)a.ldb * 2 < (1ull << 32);
+    if (a.k_chunk > 0) {  // split weight gradient: only the LDS-direct kernel implements it
+        if (kind != GEMM_DW || !dma_ok || !a.write_grad || a.C_bf16 || a.Ct_bf16 || (a.k_chunk % DMA_BK) != 0)
+            return hipErrorInvalidValue;
+        return launch_dma_bf16(kind, a, stream, ev);
+    }
     if (dma_ok && (forced == 1 || (forced == 0 && dma_tiles >= 128))) return launch_dma_bf16(kind, a, stream, ev);
     if (forced == 4 || (forced == 0 && big_tiles >= 512)) return launch_shape_bf16<256, 128, 32>(kind, a, stream, ev);
     if (forced == 3) return launch_shape_bf16<128, 128, 32>(kind, a, stream, ev);
     return launch_shape_bf16<128, 128, 64>(kind, a, stream, ev);
+}
+
+int gemm_bf16_dw_splits(int M, int N, int K, long long lda, long long ldb)
+{
+    if ((unsigned long long)M * (unsigned long long)lda * 2 >= (1ull << 32) ||
+        (unsigned long long)N * (unsigned long long)ldb * 2 >= (1ull << 32) || (lda & 7) || (ldb & 7))
+        return 1;
+    const long long tiles = (long long)((M + DMA_BM - 1) / DMA_BM) * ((N + DMA_BN - 1) / DMA_BN);
+    if (tiles > 128 || K < 2048) return 1;
+    long long s = 256 / tiles;  // fill the chip once
+    if (s > 8) s = 8;
+    if (s > K / 1024) s = K / 1024;  // at least 16 k-tiles per slice
+    return s < 2 ? 1 : (int)s;
+}
+
+hipError_t launch_dw_reduce(const float *partial, int splits, long long stride, long long count, float *master,
+                            float *grad, float lr, hipStream_t stream, const LaunchEvents &ev)
+{
+    if (count <= 0) return hipSuccess;
+    const long long n4 = (count + 3) / 4;
+    long long blocks = (n4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    return launch_kernel(dw_reduce_kernel, dim3((unsigned)blocks), dim3(256), stream, ev, partial, splits, stride,
+                         count, master, grad, lr);
 }
 
 hipError_t launch_transpose_bf16(const void *in, long long ldi, void *out, long long ldo, int R, int C,

@@ -106,6 +106,7 @@ struct hb_model {
     int32_t *d_col_cnt = nullptr, *d_col_start = nullptr, *d_chunk_start = nullptr;
     int32_t *d_cursor = nullptr;  // per-block column histograms / cursors of the CSC build
     int32_t *d_csc_row = nullptr;
+    float *dw_partial = nullptr;         // bf16 mode: slices of a split weight gradient (largest layer that splits)
     int4 *d_chunk_desc = nullptr;        // descriptor of each gradient chunk (capacity follows the CSC arrays)
     float *d_csc_val = nullptr;
     int64_t csc_cap = 0;
@@ -636,10 +637,35 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.Ct_bf16 = m->shadow_t[l];
             g.ldct = m->ld8[l];
         }
-        HB_HIP(launch_gemm_bf16(GEMM_DW, g, st,
-                                prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
-                                           2.0 * ((double)g.M * g.K + (double)g.N * g.K) +
-                                               (grad_mode ? 4.0 : 12.0) * g.M * g.N)));
+        const int sp = m->dw_partial ? gemm_bf16_dw_splits(g.M, g.N, g.K, g.lda, g.ldb) : 1;
+        if (sp > 1) {
+            // too few tiles for the chip: slices of the batch give partial products, summed (and
+            // applied to the master weights) by a second kernel; the bf16 copies are refreshed after
+            GemmBf16Args gs = g;
+            gs.write_grad = 1;
+            gs.C_f32 = m->dw_partial;
+            gs.C_bf16 = nullptr;
+            gs.Ct_bf16 = nullptr;
+            gs.k_chunk = (int)round_up((g.K + sp - 1) / sp, 64);
+            gs.c_split_stride = (long long)g.M * g.N;
+            const int slices = (g.K + gs.k_chunk - 1) / gs.k_chunk;
+            HB_HIP(launch_gemm_bf16(GEMM_DW, gs, st,
+                                    prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                               2.0 * ((double)g.M * g.K + (double)g.N * g.K) +
+                                                   4.0 * slices * g.M * g.N)));
+            HB_HIP(launch_dw_reduce(m->dw_partial, slices, gs.c_split_stride, gs.c_split_stride,
+                                    m->d_params + m->w_off[l], grad_mode ? d_grad_flat + m->w_off[l] : nullptr, lr,
+                                    st, prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)slices * g.M * g.N,
+                                                   4.0 * (slices + 2) * g.M * g.N)));
+            if (!grad_mode)
+                HB_HIP(launch_shadow(m->d_params + m->w_off[l], m->dims[l], m->dims[l - 1], m->shadow[l],
+                                     m->ld8[l - 1], m->shadow_t[l], m->ld8[l], st));
+        } else {
+            HB_HIP(launch_gemm_bf16(GEMM_DW, g, st,
+                                    prof_begin(m, HB_K_DW_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
+                                               2.0 * ((double)g.M * g.K + (double)g.N * g.K) +
+                                                   (grad_mode ? 4.0 : 12.0) * g.M * g.N)));
+        }
         HB_HIP(launch_rowsum_bias(m->delta_t[l & 1], ldB, m->dims[l], B, m->d_params + m->b_off[l],
                                   grad_mode ? d_grad_flat + m->b_off[l] : nullptr, lr, st,
                                   prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)B * m->dims[l],
@@ -884,6 +910,17 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
             m->delta_bf[i] = p;
             if (rc == HB_OK) rc = dev_alloc(m, &p, (size_t)max_d * ldB);
             m->delta_t[i] = p;
+        }
+        {
+            // weight gradients with too few 256 x 256 tiles are split over the batch (most slices
+            // at max_B: the count does not decrease with the batch)
+            size_t need = 0;
+            for (int l = 1; l <= L; ++l) {
+                const int sp = gemm_bf16_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, ldB, ldB);
+                const size_t n = (sp > 1) ? (size_t)sp * m->dims[l] * m->dims[l - 1] : 0;
+                if (n > need) need = n;
+            }
+            if (need > 0 && rc == HB_OK) rc = dev_alloc(m, &m->dw_partial, need);
         }
     }
     if (m->sparse && rc == HB_OK) {

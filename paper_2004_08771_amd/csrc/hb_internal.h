@@ -96,9 +96,20 @@ struct GemmBf16Args {
     int write_grad;
     float lr;
     int tiles_m, tiles_n;
+    // weight gradient split over the contraction (the batch): slice s covers k in
+    // [s k_chunk, (s+1) k_chunk) and writes its plain fp32 partial product at
+    // C_f32 + s c_split_stride (write_grad form, no bf16 outputs).  0: no split.
+    int k_chunk;
+    long long c_split_stride;
 };
 hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream,
                             const LaunchEvents &ev = LaunchEvents());
+// Slices for a weight-gradient product whose 256 x 256 tiles would leave half of the CUs (or
+// more) idle; 1 = do not split.  Non-decreasing in K.
+int gemm_bf16_dw_splits(int M, int N, int K, long long lda, long long ldb);
+// out[i] = sum_s partial[s * stride + i]  (grad != null: written there)  or  master[i] -= lr * sum
+hipError_t launch_dw_reduce(const float *partial, int splits, long long stride, long long count, float *master,
+                            float *grad, float lr, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 hipError_t launch_transpose_bf16(const void *in, long long ldi, void *out, long long ldo, int R, int C,
                                  hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 // bf16 copies (row-major and transposed) of an fp32 matrix W [R x C]
