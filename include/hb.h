@@ -194,6 +194,60 @@ int hb_profile_read(hb_model *m, hb_kernel_stat *out, int32_t cap, int32_t *n_ou
 /* Library version string, e.g. for logs. */
 const char *hb_version(void);
 
+/*
+ * ---- Adaptive Hogbatch scheduling and the GPU worker's loop --------------------------------
+ *
+ * hb_sched is the coordinator's ScheduleWork handler of Algorithm 2 (Section 6.3): host-only
+ * state, no device calls.  It keeps, for each of n_workers workers E, the number of model
+ * updates u^E last reported and the batch size b^E with thresholds min_b^E <= b^E <=
+ * max_b^E, the factor alpha (> 1; the paper's default is 2) and the examples of the current
+ * epoch not yet handed out, a contiguous range [cursor, n_examples).
+ *
+ * hb_sched_request(s, E, u, &begin, &count) is one ScheduleWork message: it records u^E = u;
+ * if u^E is below the smallest update count of all OTHER workers, b^E <- max(b^E / alpha,
+ * min_b^E); else if it is above their largest, b^E <- min(b^E * alpha, max_b^E) (b^E / alpha
+ * and b^E * alpha rounded to the nearest integer, at least 1; a single worker is never
+ * rescaled); then, if b^E examples are left, *begin / *count name the next b^E of them
+ * (they are removed from the epoch), else *count = 0: nothing is sent and the worker is
+ * done for this epoch.  Requests are served one at a time (internally locked), as the
+ * coordinator serves them serially.  u is a double because a CPU worker reports
+ * t * beta updates per batch (Algorithm 2, CPU worker).
+ * hb_sched_new_epoch makes the whole training set available again (Section 6.1: the process
+ * is restarted with the full dataset); update counts and batch sizes carry over.
+ * The arrays min_b, max_b, init_b have n_workers entries (HOST pointers, copied).
+ */
+typedef struct hb_sched hb_sched;
+hb_sched *hb_sched_create(int64_t n_examples, int32_t n_workers, const int64_t *min_b, const int64_t *max_b,
+                          const int64_t *init_b, double alpha);
+void hb_sched_destroy(hb_sched *s);
+int hb_sched_request(hb_sched *s, int32_t worker, double updates, int64_t *begin, int64_t *count);
+int hb_sched_new_epoch(hb_sched *s);
+int64_t hb_sched_batch_size(const hb_sched *s, int32_t worker); /* current b^E; -1 on error */
+int64_t hb_sched_remaining(const hb_sched *s);                  /* examples left in the epoch; -1 on error */
+
+/*
+ * The GPU worker's share of one epoch (Section 5.1, GPU workers; Section 6.2): until the
+ * coordinator sends nothing more, ask for a batch (reporting one model update per step taken),
+ * copy its rows from the HOST-resident training data to the device on a copy stream while the
+ * previous batch is still computing, and run the step on the replica with
+ * lr = lr_per_example * b (learning rate proportional to the batch size, Section 6.2).
+ * Every merge_every steps (and once at the end if any step is unmerged) the replica is merged
+ * with host_model as hb_model_merge(m, host_model, merge_weight) does; merge_every = 0 or
+ * host_model = NULL: never.
+ *   host_X  n_examples x d_0 row-major in HOST memory (fp32, or bfloat16 in the bf16 mode),
+ *           page-locked memory makes the copies asynchronous;  host_y  n_examples int32.
+ *   *updates (in/out, may be NULL -> starts at 0): the worker's update count u^E, carried
+ *   from epoch to epoch;  *steps_out, *loss_sum_out (may be NULL): steps taken in this call and
+ *   the sum of their pre-update mean losses.
+ * The request for batch k+1 is made while batch k computes, with the update count batch k
+ * will have produced.  Dense input only (HB_ERR_UNSUPPORTED for a CSR model); the scheduler's
+ * max_b of this worker must not exceed the model's max_B.  Synchronises the model's stream
+ * before returning.
+ */
+int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X, const int32_t *host_y,
+                        float lr_per_example, float *host_model, int32_t merge_every, float merge_weight,
+                        double *updates, int64_t *steps_out, double *loss_sum_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,15 @@ SIGNATURES["hb_last_error_code"] = (_int, [])
 SIGNATURES["hb_profile_enable"] = (_int, [_vp, _int])
 SIGNATURES["hb_profile_read"] = (_int, [_vp, ctypes.POINTER(KernelStat), _i32, _i32p])
 
+_i64p, _f64, _f64p = ctypes.POINTER(ctypes.c_int64), ctypes.c_double, ctypes.POINTER(ctypes.c_double)
+SIGNATURES["hb_sched_create"] = (_vp, [_i64, _i32, _i64p, _i64p, _i64p, _f64])
+SIGNATURES["hb_sched_destroy"] = (None, [_vp])
+SIGNATURES["hb_sched_request"] = (_int, [_vp, _i32, _f64, _i64p, _i64p])
+SIGNATURES["hb_sched_new_epoch"] = (_int, [_vp])
+SIGNATURES["hb_sched_batch_size"] = (_i64, [_vp, _i32])
+SIGNATURES["hb_sched_remaining"] = (_i64, [_vp])
+SIGNATURES["hb_worker_run_epoch"] = (_int, [_vp, _vp, _i32, _vp, _vp, _f32, _vp, _i32, _f32, _f64p, _i64p, _f64p])
+
 _lib = None
 
 
@@ -178,3 +187,52 @@ class Model:
         n = ctypes.c_int32(0)
         _check(lib().hb_profile_read(self._h, buf, cap, ctypes.byref(n)))
         return [{f: getattr(buf[i], f) for f, _ in KernelStat._fields_} for i in range(n.value)]
+
+    def worker_run_epoch(self, sched, worker, host_X, host_y, lr_per_example, host_model=None, merge_every=0,
+                         merge_weight=1.0, updates=0.0):
+        """hb_worker_run_epoch.  Returns (updates, steps, loss_sum)."""
+        u = ctypes.c_double(float(updates))
+        steps = ctypes.c_int64(0)
+        loss_sum = ctypes.c_double(0.0)
+        _check(lib().hb_worker_run_epoch(self._h, sched._h, int(worker), _ptr(host_X), _ptr(host_y),
+                                         float(lr_per_example), _ptr(host_model), int(merge_every),
+                                         float(merge_weight), ctypes.byref(u), ctypes.byref(steps),
+                                         ctypes.byref(loss_sum)))
+        return u.value, steps.value, loss_sum.value
+
+
+class Sched:
+    """Owner of one hb_sched handle (Algorithm 2, ScheduleWork).  Host-only: needs no GPU."""
+
+    def __init__(self, n_examples, min_b, max_b, init_b, alpha=2.0):
+        n = len(init_b)
+        arr = lambda v: (ctypes.c_int64 * n)(*[int(x) for x in v])
+        self._h = lib().hb_sched_create(int(n_examples), n, arr(min_b), arr(max_b), arr(init_b), float(alpha))
+        if not self._h:
+            raise HbError(int(lib().hb_last_error_code()), last_error())
+
+    def destroy(self):
+        if self._h:
+            lib().hb_sched_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def request(self, worker, updates):
+        """(begin, count); count == 0: nothing sent."""
+        b, c = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(lib().hb_sched_request(self._h, int(worker), float(updates), ctypes.byref(b), ctypes.byref(c)))
+        return b.value, c.value
+
+    def new_epoch(self):
+        _check(lib().hb_sched_new_epoch(self._h))
+
+    def batch_size(self, worker) -> int:
+        return int(lib().hb_sched_batch_size(self._h, int(worker)))
+
+    def remaining(self) -> int:
+        return int(lib().hb_sched_remaining(self._h))

@@ -715,6 +715,33 @@ int fetch_loss(hb_model *m, float *out)
 
 }  // namespace
 
+namespace hb {
+
+bool model_info(const hb_model *m, ModelInfo *out)
+{
+    if (check_handle(m, true) != HB_OK) return false;
+    out->d0 = m->dims[0];
+    out->d_out = m->dims[m->L];
+    out->dtype = m->dtype;
+    out->sparse = m->sparse ? 1 : 0;
+    out->max_B = m->max_B;
+    out->P = m->P;
+    out->stream = m->stream;
+    return true;
+}
+
+int set_error(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    g_err_code = code;
+    return code;
+}
+
+}  // namespace hb
+
 extern "C" {
 
 const char *hb_last_error(void) { return g_err; }

@@ -5,6 +5,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+struct hb_model;
+
 namespace hb {
 
 // Optional pair of events attached to one kernel dispatch: their elapsed time is that
@@ -250,5 +252,18 @@ hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStre
 hipError_t launch_colsum(const float *delta, int ldd, long long B, int d, int splits, float *partial,
                          hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 hipError_t launch_transpose(const float *in, float *out, int R, int C, hipStream_t stream);
+
+// ---------------------------------------------------------------- for the worker loop (worker.hip)
+struct ModelInfo {
+    int d0, d_out;
+    int dtype;          // HB_F32 / HB_BF16_F32MASTER
+    int sparse;
+    long long max_B, P;
+    hipStream_t stream;
+};
+// false (and the thread's error text set) if m is null or not configured
+bool model_info(const hb_model *m, ModelInfo *out);
+// records the calling thread's error text and code; returns code
+int set_error(int code, const char *fmt, ...);
 
 }  // namespace hb

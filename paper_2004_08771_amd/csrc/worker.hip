@@ -1,0 +1,273 @@
+// Coordinator-side batch scheduling of Adaptive Hogbatch (Algorithm 2 of the paper,
+// ScheduleWork handler; Section 6.3) and the GPU worker's loop around the mini-batch step
+// (Section 5.1: the GPU worker is the exclusive interface of its device and pays the
+// host-to-device transfer of every batch; Section 6.2: deep copy of the global model, push
+// after updating).  Host code only: the step itself is hb_batch_step_async.
+//
+// gfx950 / HIP design of the loop: two device staging buffers and a copy stream; the rows of
+// batch k+1 travel over PCIe while batch k computes, ordered by events in both directions
+// (a buffer is refilled only after the step that read it has finished).  Everything stays at
+// the default stream priority.
+#include "hb_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <mutex>
+#include <vector>
+
+#include "../../include/hb.h"
+
+struct hb_sched {
+    int64_t n = 0, cursor = 0;
+    double alpha = 2.0;
+    std::vector<int64_t> min_b, max_b, b;
+    std::vector<double> u;
+    std::mutex lock;  // the coordinator serves requests serially
+};
+
+namespace {
+
+int64_t round_half_away(double x) { return (int64_t)std::floor(x + 0.5); }
+
+}  // namespace
+
+extern "C" {
+
+hb_sched *hb_sched_create(int64_t n_examples, int32_t n_workers, const int64_t *min_b, const int64_t *max_b,
+                          const int64_t *init_b, double alpha)
+{
+    if (n_examples < 0 || n_workers < 1 || !min_b || !max_b || !init_b || !(alpha > 1.0) || !std::isfinite(alpha)) {
+        hb::set_error(HB_ERR_INVALID, "hb_sched_create: need n_examples >= 0, n_workers >= 1, threshold arrays, alpha > 1");
+        return nullptr;
+    }
+    for (int32_t w = 0; w < n_workers; ++w)
+        if (min_b[w] < 1 || init_b[w] < min_b[w] || max_b[w] < init_b[w]) {
+            hb::set_error(HB_ERR_INVALID, "hb_sched_create: worker %d needs 1 <= min_b <= init_b <= max_b", (int)w);
+            return nullptr;
+        }
+    hb_sched *s = new (std::nothrow) hb_sched;
+    if (!s) {
+        hb::set_error(HB_ERR_ALLOC, "hb_sched_create: out of host memory");
+        return nullptr;
+    }
+    s->n = n_examples;
+    s->alpha = alpha;
+    s->min_b.assign(min_b, min_b + n_workers);
+    s->max_b.assign(max_b, max_b + n_workers);
+    s->b.assign(init_b, init_b + n_workers);
+    s->u.assign(n_workers, 0.0);
+    return s;
+}
+
+void hb_sched_destroy(hb_sched *s) { delete s; }
+
+int hb_sched_request(hb_sched *s, int32_t worker, double updates, int64_t *begin, int64_t *count)
+{
+    if (!s || !begin || !count) return hb::set_error(HB_ERR_INVALID, "hb_sched_request: NULL argument");
+    if (worker < 0 || worker >= (int32_t)s->b.size())
+        return hb::set_error(HB_ERR_INVALID, "hb_sched_request: worker %d is outside [0, %d)", (int)worker,
+                             (int)s->b.size());
+    if (!(updates >= 0.0) || !std::isfinite(updates))
+        return hb::set_error(HB_ERR_INVALID, "hb_sched_request: update count must be finite and >= 0");
+    std::lock_guard<std::mutex> g(s->lock);
+    s->u[worker] = updates;
+    // smallest / largest update count of all other workers
+    bool any = false;
+    double min_u = 0.0, max_u = 0.0;
+    for (size_t w = 0; w < s->u.size(); ++w) {
+        if ((int32_t)w == worker) continue;
+        if (!any || s->u[w] < min_u) min_u = s->u[w];
+        if (!any || s->u[w] > max_u) max_u = s->u[w];
+        any = true;
+    }
+    int64_t &b = s->b[worker];
+    if (any) {
+        if (updates < min_u) {  // lagging: smaller batches, more updates
+            int64_t nb = round_half_away((double)b / s->alpha);
+            if (nb < 1) nb = 1;
+            b = nb > s->min_b[worker] ? nb : s->min_b[worker];
+        } else if (updates > max_u) {  // ahead: larger batches, fewer updates
+            const int64_t nb = round_half_away((double)b * s->alpha);
+            b = nb < s->max_b[worker] ? nb : s->max_b[worker];
+        }
+    }
+    *begin = s->cursor;
+    if (b <= s->n - s->cursor) {
+        *count = b;
+        s->cursor += b;
+    } else {
+        *count = 0;  // nothing is sent: the worker is done for this epoch
+    }
+    return HB_OK;
+}
+
+int hb_sched_new_epoch(hb_sched *s)
+{
+    if (!s) return hb::set_error(HB_ERR_INVALID, "hb_sched_new_epoch: NULL scheduler");
+    std::lock_guard<std::mutex> g(s->lock);
+    s->cursor = 0;
+    return HB_OK;
+}
+
+int64_t hb_sched_batch_size(const hb_sched *s, int32_t worker)
+{
+    if (!s || worker < 0 || worker >= (int32_t)s->b.size()) {
+        hb::set_error(HB_ERR_INVALID, "hb_sched_batch_size: bad scheduler or worker");
+        return -1;
+    }
+    return s->b[worker];
+}
+
+int64_t hb_sched_remaining(const hb_sched *s)
+{
+    if (!s) {
+        hb::set_error(HB_ERR_INVALID, "hb_sched_remaining: NULL scheduler");
+        return -1;
+    }
+    return s->n - s->cursor;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Device side of the double buffering; released on every exit path.
+struct Staging {
+    void *x[2] = {nullptr, nullptr};
+    int32_t *y[2] = {nullptr, nullptr};
+    float *loss = nullptr;       // one slot per step of a window, device
+    float *loss_host = nullptr;  // page-locked mirror
+    hipStream_t copy = nullptr;
+    hipEvent_t filled[2] = {nullptr, nullptr};    // the copy into buffer i has finished
+    hipEvent_t consumed[2] = {nullptr, nullptr};  // the step reading buffer i has finished
+    ~Staging()
+    {
+        for (int i = 0; i < 2; ++i) {
+            if (x[i]) (void)hipFree(x[i]);
+            if (y[i]) (void)hipFree(y[i]);
+            if (filled[i]) (void)hipEventDestroy(filled[i]);
+            if (consumed[i]) (void)hipEventDestroy(consumed[i]);
+        }
+        if (loss) (void)hipFree(loss);
+        if (loss_host) (void)hipHostFree(loss_host);
+        if (copy) (void)hipStreamDestroy(copy);
+    }
+};
+
+constexpr int LOSS_WINDOW = 256;  // losses are fetched in windows of this many steps
+
+#define WK_HIP(call)                                                                               \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return hb::set_error(HB_ERR_DEVICE, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), \
+                                 __FILE__, __LINE__);                                              \
+    } while (0)
+
+}  // namespace
+
+extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X,
+                                   const int32_t *host_y, float lr_per_example, float *host_model,
+                                   int32_t merge_every, float merge_weight, double *updates, int64_t *steps_out,
+                                   double *loss_sum_out)
+{
+    hb::ModelInfo mi;
+    if (!hb::model_info(m, &mi)) return hb_last_error_code();
+    if (!s || !host_X || !host_y) return hb::set_error(HB_ERR_INVALID, "hb_worker_run_epoch: NULL argument");
+    if (worker < 0 || worker >= (int32_t)s->b.size())
+        return hb::set_error(HB_ERR_INVALID, "hb_worker_run_epoch: worker %d is outside [0, %d)", (int)worker,
+                             (int)s->b.size());
+    if (mi.sparse) return hb::set_error(HB_ERR_UNSUPPORTED, "hb_worker_run_epoch: dense input only");
+    if (s->max_b[worker] > mi.max_B)
+        return hb::set_error(HB_ERR_INVALID, "the scheduler's max_b (%lld) of this worker exceeds the model's max_B (%lld)",
+                             (long long)s->max_b[worker], (long long)mi.max_B);
+    if (!(lr_per_example >= 0.f) || !std::isfinite(lr_per_example))
+        return hb::set_error(HB_ERR_INVALID, "lr_per_example must be finite and >= 0");
+    if (merge_every < 0 || (merge_every > 0 && host_model && !(merge_weight >= 0.f && merge_weight <= 1.f)))
+        return hb::set_error(HB_ERR_INVALID, "merge_every must be >= 0 and merge_weight in [0, 1]");
+    const bool merging = merge_every > 0 && host_model != nullptr;
+
+    const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
+    const size_t row_bytes = elem * (size_t)mi.d0;
+    const int64_t cap = s->max_b[worker];
+    Staging st;
+    for (int i = 0; i < 2; ++i) {
+        WK_HIP(hipMalloc(&st.x[i], row_bytes * (size_t)cap));
+        WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.y[i]), sizeof(int32_t) * (size_t)cap));
+        WK_HIP(hipEventCreateWithFlags(&st.filled[i], hipEventDisableTiming));
+        WK_HIP(hipEventCreateWithFlags(&st.consumed[i], hipEventDisableTiming));
+    }
+    WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.loss), sizeof(float) * LOSS_WINDOW));
+    WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&st.loss_host), sizeof(float) * LOSS_WINDOW, hipHostMallocDefault));
+    WK_HIP(hipStreamCreateWithFlags(&st.copy, hipStreamNonBlocking));  // default priority
+
+    double u = updates ? *updates : 0.0;
+    int64_t steps = 0;
+    double loss_sum = 0.0;
+    int in_window = 0;
+    int64_t since_merge = 0;
+    auto flush_losses = [&]() -> int {
+        if (in_window == 0) return HB_OK;
+        WK_HIP(hipMemcpyAsync(st.loss_host, st.loss, sizeof(float) * in_window, hipMemcpyDeviceToHost, mi.stream));
+        WK_HIP(hipStreamSynchronize(mi.stream));
+        for (int i = 0; i < in_window; ++i) loss_sum += st.loss_host[i];
+        in_window = 0;
+        return HB_OK;
+    };
+    // ask for a batch and start its transfer into staging buffer `buf`
+    auto fetch = [&](int buf, double u_report, int64_t *count) -> int {
+        int64_t begin = 0;
+        int rc = hb_sched_request(s, worker, u_report, &begin, count);
+        if (rc != HB_OK || *count == 0) return rc;
+        if (*count > cap) return hb::set_error(HB_ERR_STATE, "scheduler handed out %lld rows, more than max_b", (long long)*count);
+        // the buffer's previous reader must be done before it is overwritten
+        WK_HIP(hipStreamWaitEvent(st.copy, st.consumed[buf], 0));
+        WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
+                              row_bytes * (size_t)*count, hipMemcpyHostToDevice, st.copy));
+        WK_HIP(hipMemcpyAsync(st.y[buf], host_y + begin, sizeof(int32_t) * (size_t)*count, hipMemcpyHostToDevice,
+                              st.copy));
+        WK_HIP(hipEventRecord(st.filled[buf], st.copy));
+        return HB_OK;
+    };
+
+    for (int i = 0; i < 2; ++i) WK_HIP(hipEventRecord(st.consumed[i], mi.stream));  // both buffers start free
+    int64_t cur = 0, nxt = 0;
+    int rc = fetch(0, u, &cur);
+    if (rc != HB_OK) return rc;
+    int buf = 0;
+    while (cur > 0) {
+        // batch k+1 is requested now, with the update count batch k will have produced
+        rc = fetch(buf ^ 1, u + 1.0, &nxt);
+        if (rc != HB_OK) return rc;
+        WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
+        rc = hb_batch_step_async(m, st.x[buf], st.y[buf], cur, lr_per_example * (float)cur, st.loss + in_window);
+        if (rc != HB_OK) return rc;
+        WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
+        u += 1.0;
+        ++steps;
+        ++since_merge;
+        if (++in_window == LOSS_WINDOW) {
+            rc = flush_losses();
+            if (rc != HB_OK) return rc;
+        }
+        if (merging && since_merge >= merge_every) {
+            rc = hb_model_merge(m, host_model, merge_weight);
+            if (rc != HB_OK) return rc;
+            since_merge = 0;
+        }
+        cur = nxt;
+        buf ^= 1;
+    }
+    rc = flush_losses();
+    if (rc != HB_OK) return rc;
+    if (merging && since_merge > 0) {
+        rc = hb_model_merge(m, host_model, merge_weight);
+        if (rc != HB_OK) return rc;
+    }
+    WK_HIP(hipStreamSynchronize(st.copy));
+    WK_HIP(hipStreamSynchronize(mi.stream));
+    if (updates) *updates = u;
+    if (steps_out) *steps_out = steps;
+    if (loss_sum_out) *loss_sum_out = loss_sum;
+    return HB_OK;
+}

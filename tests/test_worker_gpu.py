@@ -1,0 +1,136 @@
+"""GPU worker loop (hb_worker_run_epoch) against the fp64 oracle: the sequence of batches the
+scheduler hands out is replayed with oracle.batch_step (lr proportional to the batch size,
+Section 6.2) and, where merging is on, oracle.model_merge.  The loop prefetches: the request
+for batch k+1 is made while batch k computes, reporting the update count batch k will have
+produced."""
+import numpy as np
+import pytest
+
+import hb_inputs as hi
+import oracle
+from oracle.sched import AdaptiveSchedule
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _data(n, dims, seed):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[-1], size=n).astype(np.int32)
+    params = hi.xavier_uniform_params(dims, rng, bias_scale=0.1)
+    return X, y, params
+
+
+def _replay(sched, worker, u0, dims, act, loss, params, X, y, lr_pe, host_model=None, merge_every=0, w=1.0):
+    """What the worker loop must do, step by step, on the oracle."""
+    p = params.astype(np.float64)
+    H = None if host_model is None else host_model.astype(np.float64)
+    u, steps, loss_sum, since = float(u0), 0, 0.0, 0
+    begin, count = sched.request(worker, u)
+    while count > 0:
+        nb, nc = sched.request(worker, u + 1.0)
+        l, p = oracle.batch_step(dims, act, loss, p, X[begin:begin + count], y[begin:begin + count],
+                                 float(np.float32(lr_pe) * np.float32(count)))
+        loss_sum += l
+        u += 1.0
+        steps += 1
+        since += 1
+        if H is not None and merge_every > 0 and since >= merge_every:
+            p, H = oracle.model_merge(p, H, w)
+            since = 0
+        begin, count = nb, nc
+    if H is not None and merge_every > 0 and since > 0:
+        p, H = oracle.model_merge(p, H, w)
+    return p, H, u, steps, loss_sum
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
+
+
+def test_single_worker_epoch_matches_sequential_oracle_steps():
+    import paper_2004_08771_amd as hb
+    import torch
+    dims, act, loss = (54, 32, 7), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    n = 4096 + 40                                  # 64 full batches and a tail that is dropped
+    X, y, params = _data(n, dims, 7)
+    lr_pe = 0.1 / 64
+    ref_p, _, ref_u, ref_steps, ref_loss = _replay(AdaptiveSchedule(n, [16], [64], [64]), 0, 0, dims, act, loss,
+                                                   params, X, y, lr_pe)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 64)
+    m.set_params(params)
+    s = hb.Sched(n, [16], [64], [64])
+    hX = torch.from_numpy(X).pin_memory()
+    hy = torch.from_numpy(y).pin_memory()
+    u, steps, loss_sum = m.worker_run_epoch(s, 0, hX, hy, lr_pe)
+    got = np.empty_like(params)
+    m.get_params(got)
+    assert (u, steps) == (ref_u, ref_steps) == (64.0, 64)
+    assert s.remaining() == 40
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+    # second epoch: the update count carries over, the data starts again
+    s.new_epoch()
+    u2, steps2, _ = m.worker_run_epoch(s, 0, hX, hy, lr_pe, updates=u)
+    assert (u2, steps2) == (128.0, 64)
+    m.destroy()
+
+
+def test_adaptive_batch_sizes_pageable_memory_and_merging():
+    """Two workers at the coordinator; the other (CPU) worker has taken its share and reported
+    many updates, so the GPU worker's batch shrinks from request to request (alpha = 1.5, ragged
+    sizes).  Data in ordinary pageable memory; replica and host model blended every 3 steps."""
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (40, 96, 48, 5), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE
+    n = 6000
+    X, y, params = _data(n, dims, 9)
+    host0 = (params + np.random.default_rng(3).standard_normal(params.size).astype(np.float32) * 0.01).astype(np.float32)
+    lr_pe = 0.05 / 512
+    mk = lambda make: make(n, [1, 50], [8, 700], [1, 700], 1.5)
+
+    def cpu_share(s):                 # the CPU worker: 40 batches, 8 updates each
+        uc = 0.0
+        for _ in range(40):
+            s.request(0, uc)
+            uc += 8.0
+
+    so = mk(AdaptiveSchedule)
+    cpu_share(so)
+    ref_p, ref_H, ref_u, ref_steps, ref_loss = _replay(so, 1, 0, dims, act, loss, params, X, y, lr_pe,
+                                                       host_model=host0, merge_every=3, w=0.25)
+    assert ref_steps > 8 and so.b[1] == 50          # the batch size went all the way down
+
+    sl = mk(hb.Sched)
+    cpu_share(sl)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 700)
+    m.set_params(params)
+    H = host0.copy()
+    u, steps, loss_sum = m.worker_run_epoch(sl, 1, X, y, lr_pe, host_model=H, merge_every=3, merge_weight=0.25)
+    got = np.empty_like(params)
+    m.get_params(got)
+    m.destroy()
+    assert (u, steps) == (ref_u, ref_steps)
+    assert sl.batch_size(1) == 50 and sl.remaining() == so.remaining()
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+    assert _rel(H, ref_H) <= TOL
+
+
+def test_worker_argument_errors():
+    import paper_2004_08771_amd as hb
+    dims = (8, 4, 3)
+    X, y, params = _data(64, dims, 1)
+    m = hb.Model(dims, hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE).configure(hb.HB_F32, 16)
+    m.set_params(params)
+    s = hb.Sched(64, [4], [32], [32])               # max_b above the model's max_B
+    with pytest.raises(hb.HbError):
+        m.worker_run_epoch(s, 0, X, y, 0.01)
+    s2 = hb.Sched(64, [4], [16], [16])
+    with pytest.raises(hb.HbError):
+        m.worker_run_epoch(s2, 3, X, y, 0.01)       # no such worker
+    with pytest.raises(hb.HbError):
+        m.worker_run_epoch(s2, 0, None, y, 0.01)
+    assert m.worker_run_epoch(s2, 0, X, y, 0.01)[1] == 4
+    m.destroy()
