@@ -107,6 +107,8 @@ struct hb_model {
     int32_t *d_cursor = nullptr;  // per-block column histograms / cursors of the CSC build
     int32_t *d_csc_row = nullptr;
     float *dw_partial = nullptr;         // bf16 mode: slices of a split weight gradient (largest layer that splits)
+    void *worker_state = nullptr;        // staging buffers of the worker loop (worker.hip), kept between epochs
+    void (*worker_state_free)(void *) = nullptr;
     int4 *d_chunk_desc = nullptr;        // descriptor of each gradient chunk (capacity follows the CSC arrays)
     float *d_csc_val = nullptr;
     int64_t csc_cap = 0;
@@ -730,6 +732,12 @@ bool model_info(const hb_model *m, ModelInfo *out)
     return true;
 }
 
+void **model_worker_slot(hb_model *m, void (*deleter)(void *))
+{
+    m->worker_state_free = deleter;
+    return &m->worker_state;
+}
+
 int set_error(int code, const char *fmt, ...)
 {
     va_list ap;
@@ -997,6 +1005,7 @@ void hb_model_destroy(hb_model *m)
 {
     if (!m) return;
     if (m->configured) (void)hipStreamSynchronize(m->stream);
+    if (m->worker_state && m->worker_state_free) m->worker_state_free(m->worker_state);
     release_device(m);
     delete m;
 }

@@ -263,6 +263,9 @@ struct ModelInfo {
 };
 // false (and the thread's error text set) if m is null or not configured
 bool model_info(const hb_model *m, ModelInfo *out);
+// slot in the handle where the worker loop keeps its staging buffers between calls; the
+// deleter runs in hb_model_destroy
+void **model_worker_slot(hb_model *m, void (*deleter)(void *));
 // records the calling thread's error text and code; returns code
 int set_error(int code, const char *fmt, ...);
 

@@ -131,8 +131,11 @@ int64_t hb_sched_remaining(const hb_sched *s)
 
 namespace {
 
-// Device side of the double buffering; released on every exit path.
+// Device side of the double buffering.  Lives in the model handle from the first epoch on
+// (re-created when a larger capacity is needed), released by hb_model_destroy.
 struct Staging {
+    int64_t cap = 0;
+    size_t row_bytes = 0;
     void *x[2] = {nullptr, nullptr};
     int32_t *y[2] = {nullptr, nullptr};
     float *loss = nullptr;       // one slot per step of a window, device
@@ -142,6 +145,7 @@ struct Staging {
     hipEvent_t consumed[2] = {nullptr, nullptr};  // the step reading buffer i has finished
     ~Staging()
     {
+        if (copy) (void)hipStreamSynchronize(copy);
         for (int i = 0; i < 2; ++i) {
             if (x[i]) (void)hipFree(x[i]);
             if (y[i]) (void)hipFree(y[i]);
@@ -190,16 +194,33 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
     const size_t row_bytes = elem * (size_t)mi.d0;
     const int64_t cap = s->max_b[worker];
-    Staging st;
-    for (int i = 0; i < 2; ++i) {
-        WK_HIP(hipMalloc(&st.x[i], row_bytes * (size_t)cap));
-        WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.y[i]), sizeof(int32_t) * (size_t)cap));
-        WK_HIP(hipEventCreateWithFlags(&st.filled[i], hipEventDisableTiming));
-        WK_HIP(hipEventCreateWithFlags(&st.consumed[i], hipEventDisableTiming));
+    void **slot = hb::model_worker_slot(m, [](void *p) { delete static_cast<Staging *>(p); });
+    Staging *sp = static_cast<Staging *>(*slot);
+    if (sp && (sp->cap < cap || sp->row_bytes != row_bytes)) {
+        WK_HIP(hipStreamSynchronize(mi.stream));
+        delete sp;
+        sp = nullptr;
+        *slot = nullptr;
     }
-    WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.loss), sizeof(float) * LOSS_WINDOW));
-    WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&st.loss_host), sizeof(float) * LOSS_WINDOW, hipHostMallocDefault));
-    WK_HIP(hipStreamCreateWithFlags(&st.copy, hipStreamNonBlocking));  // default priority
+    if (!sp) {
+        sp = new (std::nothrow) Staging;
+        if (!sp) return hb::set_error(HB_ERR_ALLOC, "hb_worker_run_epoch: out of host memory");
+        *slot = sp;  // owned by the handle from here on, also if an allocation below fails
+        sp->cap = 0;
+        sp->row_bytes = row_bytes;
+        for (int i = 0; i < 2; ++i) {
+            WK_HIP(hipMalloc(&sp->x[i], row_bytes * (size_t)cap));
+            WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->y[i]), sizeof(int32_t) * (size_t)cap));
+            WK_HIP(hipEventCreateWithFlags(&sp->filled[i], hipEventDisableTiming));
+            WK_HIP(hipEventCreateWithFlags(&sp->consumed[i], hipEventDisableTiming));
+        }
+        WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->loss), sizeof(float) * LOSS_WINDOW));
+        WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&sp->loss_host), sizeof(float) * LOSS_WINDOW,
+                             hipHostMallocDefault));
+        WK_HIP(hipStreamCreateWithFlags(&sp->copy, hipStreamNonBlocking));  // default priority
+        sp->cap = cap;
+    }
+    Staging &st = *sp;
 
     double u = updates ? *updates : 0.0;
     int64_t steps = 0;
