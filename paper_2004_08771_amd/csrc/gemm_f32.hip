@@ -246,6 +246,80 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                         fa[slot][i][s], fb[slot][j][s], acc[i][j][chain % CHAINS], 0, 0, 0);
     };
 
+    // Interior tiles with 16-byte aligned rows and a whole number of k-tiles take a loop without
+    // any guard, in which every memory operation has a fixed place between the MFMAs of a
+    // group (a wavefront can issue other instructions while its MFMA executes): the fragment
+    // reads of the next group after the group's first MFMA, the LDS write of tile kt+1 in
+    // group 0, the global loads of tile kt+2 in group 1.  The explicit lgkmcnt(0) at the head
+    // of a group tells the compiler that the reads of the previous group have arrived; left
+    // to itself it places the reads next to their first use and waits for them there.
+    const bool fast = (G == 4) && a_in && b_in && a.a_vec != 0 && a.b_vec != 0 && nk > 0 &&
+                      ((kend - kbeg) % BK == 0) && !a.no_fast_loop;
+    if (fast) {
+        auto group = [&](int slot, int chain, auto &&extra) {
+            bool first = true;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        acc[i][j][chain % CHAINS] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                            fa[slot][i][s], fb[slot][j][s], acc[i][j][chain % CHAINS], 0, 0, 0);
+                        if (first) {
+                            first = false;
+                            __builtin_amdgcn_sched_barrier(0);
+                            extra();
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+        };
+        TA::load_fast(ra, A, a.lda, m0, kbeg, true, tid);
+        TB::load_fast(rb, Bm, a.ldb, n0, kbeg, true, tid);
+        TA::store(smem, ra, tid);
+        TB::store(smem + TA::FLOATS, rb, tid);
+        if (nk > 1) {
+            TA::load_fast(ra, A, a.lda, m0, kbeg + BK, true, tid);
+            TB::load_fast(rb, Bm, a.ldb, n0, kbeg + BK, true, tid);
+        }
+        __syncthreads();
+        read_frags(0, smem, smem + TA::FLOATS, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const float *As = smem + (kt & 1) * STAGE;
+            const float *Bs = As + TA::FLOATS;
+            float *An = smem + ((kt + 1) & 1) * STAGE;
+            const bool next = (kt + 1 < nk), next2 = (kt + 2 < nk);
+            if (KIND == GEMM_DW && !A_KMAJ) {
+                if (do_colsum && tid < BM) {
+#pragma unroll
+                    for (int k = 0; k < BK; ++k) colsum += As[k * TA::LD + tid];
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+            group(0, 0, [&]() {
+                read_frags(1, As, Bs, 1);
+                if (next) {  // tile kt+1 -> the stage nobody reads during this iteration
+                    TA::store(An, ra, tid);
+                    TB::store(An + TA::FLOATS, rb, tid);
+                }
+            });
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            group(1, 1, [&]() {
+                read_frags(0, As, Bs, 2);
+                if (next2) {
+                    TA::load_fast(ra, A, a.lda, m0, kbeg + (kt + 2) * BK, true, tid);
+                    TB::load_fast(rb, Bm, a.ldb, n0, kbeg + (kt + 2) * BK, true, tid);
+                }
+            });
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            group(0, 2, [&]() { read_frags(1, As, Bs, 3); });
+            __syncthreads();  // tile kt fully read by everyone, tile kt+1 fully written
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            group(1, 3, [&]() {
+                if (next) read_frags(0, An, An + TA::FLOATS, 0);
+            });
+        }
+    } else {
     if (nk > 0) {
         load_tile(0);
         TA::store(smem, ra, tid);
@@ -278,6 +352,7 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
         __syncthreads();  // tile kt fully read by everyone, tile kt+1 fully written
         if (kt + 1 < nk) read_frags(0, An, An + TA::FLOATS, 0);
         mfma_group((G - 1) & 1, G - 1);
+    }
     }
 
     // ---- epilogue.  acc[i][j][v] is C(row, col) with
@@ -427,6 +502,8 @@ hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *split
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     const Shape sh = pick_shape(kind, a.M, a.N);
+    static const int no_fast = env_int("HB_GEMM_NOFAST", 0);
+    a.no_fast_loop = no_fast;
     a.tiles_m = (a.M + sh.bm - 1) / sh.bm;
     a.tiles_n = (a.N + sh.bn - 1) / sh.bn;
     const long long tiles = (long long)a.tiles_m * a.tiles_n;
@@ -458,6 +535,8 @@ hipError_t launch_gemm_f32_bwd_pair(GemmArgs da, GemmArgs dw, int max_splits, in
                                     hipStream_t stream, const LaunchEvents &ev)
 {
     static const int pair_wgs = env_int("HB_PAIR_WGS", 256);  // weight-gradient blocks wanted (tuning aid)
+    static const int no_fast = env_int("HB_GEMM_NOFAST", 0);
+    da.no_fast_loop = dw.no_fast_loop = no_fast;
     da.tiles_m = (da.M + 63) / 64;
     da.tiles_n = (da.N + 63) / 64;
     da.splits = 1;

@@ -53,6 +53,7 @@ struct GemmArgs {
     float *colsum;             // DW: column sums of A (= bias gradient partials) [splits][M], may be null
     int act;                   // ACT_*
     int tiles_m, tiles_n;
+    int no_fast_loop;          // tuning aid (HB_GEMM_NOFAST): always take the guarded main loop
 };
 
 // Chooses the tile shape for (kind, M, N, K), fills tiles/splits (splits <= max_splits)
