@@ -248,6 +248,17 @@ int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *ho
                         float lr_per_example, float *host_model, int32_t merge_every, float merge_weight,
                         double *updates, int64_t *steps_out, double *loss_sum_out);
 
+/*
+ * Loss of the replica over a HOST-resident dataset (the evaluation stage of Section 5.2: the
+ * loss is computed at the end of an epoch, by a forward pass over all examples in sub-batches
+ * that fit the device): rows [0, n_examples) are sent in pieces of at most `batch` rows
+ * (<= max_B) through the same double-buffered transfer as the worker loop, hb_batch_loss's
+ * forward pass runs on each, and *mean_loss receives the mean over all n_examples (the piece
+ * means weighted by their sizes, accumulated in double).  The replica is not modified.
+ */
+int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples, int64_t batch,
+                        double *mean_loss);
+
 #ifdef __cplusplus
 }
 #endif

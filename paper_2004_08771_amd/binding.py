@@ -58,6 +58,7 @@ SIGNATURES["hb_sched_new_epoch"] = (_int, [_vp])
 SIGNATURES["hb_sched_batch_size"] = (_i64, [_vp, _i32])
 SIGNATURES["hb_sched_remaining"] = (_i64, [_vp])
 SIGNATURES["hb_worker_run_epoch"] = (_int, [_vp, _vp, _i32, _vp, _vp, _f32, _vp, _i32, _f32, _f64p, _i64p, _f64p])
+SIGNATURES["hb_worker_eval_loss"] = (_int, [_vp, _vp, _vp, _i64, _i64, _f64p])
 
 _lib = None
 
@@ -199,6 +200,12 @@ class Model:
                                          float(merge_weight), ctypes.byref(u), ctypes.byref(steps),
                                          ctypes.byref(loss_sum)))
         return u.value, steps.value, loss_sum.value
+
+    def worker_eval_loss(self, host_X, host_y, n_examples, batch) -> float:
+        out = ctypes.c_double(0.0)
+        _check(lib().hb_worker_eval_loss(self._h, _ptr(host_X), _ptr(host_y), int(n_examples), int(batch),
+                                         ctypes.byref(out)))
+        return out.value
 
 
 class Sched:

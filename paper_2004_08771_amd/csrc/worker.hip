@@ -168,6 +168,39 @@ constexpr int LOSS_WINDOW = 256;  // losses are fetched in windows of this many 
                                  __FILE__, __LINE__);                                              \
     } while (0)
 
+// The handle's staging buffers, (re)created for at least `cap` rows of `row_bytes` bytes.
+int acquire_staging(hb_model *m, const hb::ModelInfo &mi, int64_t cap, size_t row_bytes, Staging **out)
+{
+    void **slot = hb::model_worker_slot(m, [](void *p) { delete static_cast<Staging *>(p); });
+    Staging *sp = static_cast<Staging *>(*slot);
+    if (sp && (sp->cap < cap || sp->row_bytes != row_bytes)) {
+        WK_HIP(hipStreamSynchronize(mi.stream));
+        delete sp;
+        sp = nullptr;
+        *slot = nullptr;
+    }
+    if (!sp) {
+        sp = new (std::nothrow) Staging;
+        if (!sp) return hb::set_error(HB_ERR_ALLOC, "hb_worker_run_epoch: out of host memory");
+        *slot = sp;  // owned by the handle from here on, also if an allocation below fails
+        sp->cap = 0;
+        sp->row_bytes = row_bytes;
+        for (int i = 0; i < 2; ++i) {
+            WK_HIP(hipMalloc(&sp->x[i], row_bytes * (size_t)cap));
+            WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->y[i]), sizeof(int32_t) * (size_t)cap));
+            WK_HIP(hipEventCreateWithFlags(&sp->filled[i], hipEventDisableTiming));
+            WK_HIP(hipEventCreateWithFlags(&sp->consumed[i], hipEventDisableTiming));
+        }
+        WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->loss), sizeof(float) * LOSS_WINDOW));
+        WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&sp->loss_host), sizeof(float) * LOSS_WINDOW,
+                             hipHostMallocDefault));
+        WK_HIP(hipStreamCreateWithFlags(&sp->copy, hipStreamNonBlocking));  // default priority
+        sp->cap = cap;
+    }
+    *out = sp;
+    return HB_OK;
+}
+
 }  // namespace
 
 extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X,
@@ -194,31 +227,10 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
     const size_t row_bytes = elem * (size_t)mi.d0;
     const int64_t cap = s->max_b[worker];
-    void **slot = hb::model_worker_slot(m, [](void *p) { delete static_cast<Staging *>(p); });
-    Staging *sp = static_cast<Staging *>(*slot);
-    if (sp && (sp->cap < cap || sp->row_bytes != row_bytes)) {
-        WK_HIP(hipStreamSynchronize(mi.stream));
-        delete sp;
-        sp = nullptr;
-        *slot = nullptr;
-    }
-    if (!sp) {
-        sp = new (std::nothrow) Staging;
-        if (!sp) return hb::set_error(HB_ERR_ALLOC, "hb_worker_run_epoch: out of host memory");
-        *slot = sp;  // owned by the handle from here on, also if an allocation below fails
-        sp->cap = 0;
-        sp->row_bytes = row_bytes;
-        for (int i = 0; i < 2; ++i) {
-            WK_HIP(hipMalloc(&sp->x[i], row_bytes * (size_t)cap));
-            WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->y[i]), sizeof(int32_t) * (size_t)cap));
-            WK_HIP(hipEventCreateWithFlags(&sp->filled[i], hipEventDisableTiming));
-            WK_HIP(hipEventCreateWithFlags(&sp->consumed[i], hipEventDisableTiming));
-        }
-        WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->loss), sizeof(float) * LOSS_WINDOW));
-        WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&sp->loss_host), sizeof(float) * LOSS_WINDOW,
-                             hipHostMallocDefault));
-        WK_HIP(hipStreamCreateWithFlags(&sp->copy, hipStreamNonBlocking));  // default priority
-        sp->cap = cap;
+    Staging *sp = nullptr;
+    {
+        const int rc_st = acquire_staging(m, mi, cap, row_bytes, &sp);
+        if (rc_st != HB_OK) return rc_st;
     }
     Staging &st = *sp;
 
@@ -290,5 +302,58 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     if (updates) *updates = u;
     if (steps_out) *steps_out = steps;
     if (loss_sum_out) *loss_sum_out = loss_sum;
+    return HB_OK;
+}
+
+extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples,
+                                   int64_t batch, double *mean_loss)
+{
+    hb::ModelInfo mi;
+    if (!hb::model_info(m, &mi)) return hb_last_error_code();
+    if (!host_X || !host_y || !mean_loss) return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: NULL argument");
+    if (mi.sparse) return hb::set_error(HB_ERR_UNSUPPORTED, "hb_worker_eval_loss: dense input only");
+    if (n_examples < 1) return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: n_examples must be >= 1");
+    if (batch < 1 || batch > mi.max_B)
+        return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: batch = %lld is outside [1, max_B = %lld]",
+                             (long long)batch, (long long)mi.max_B);
+    const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
+    const size_t row_bytes = elem * (size_t)mi.d0;
+    Staging *sp = nullptr;
+    int rc = acquire_staging(m, mi, batch, row_bytes, &sp);
+    if (rc != HB_OK) return rc;
+    Staging &st = *sp;
+    auto send = [&](int buf, int64_t begin, int64_t count) -> int {
+        WK_HIP(hipStreamWaitEvent(st.copy, st.consumed[buf], 0));
+        WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
+                              row_bytes * (size_t)count, hipMemcpyHostToDevice, st.copy));
+        WK_HIP(hipMemcpyAsync(st.y[buf], host_y + begin, sizeof(int32_t) * (size_t)count, hipMemcpyHostToDevice,
+                              st.copy));
+        WK_HIP(hipEventRecord(st.filled[buf], st.copy));
+        return HB_OK;
+    };
+    for (int i = 0; i < 2; ++i) WK_HIP(hipEventRecord(st.consumed[i], mi.stream));
+    double sum = 0.0;
+    int buf = 0;
+    int64_t begin = 0, count = n_examples < batch ? n_examples : batch;
+    rc = send(0, begin, count);
+    if (rc != HB_OK) return rc;
+    while (count > 0) {
+        const int64_t nbegin = begin + count;
+        const int64_t ncount = (n_examples - nbegin) < batch ? (n_examples - nbegin) : batch;
+        if (ncount > 0) {  // the next piece travels while this one is evaluated
+            rc = send(buf ^ 1, nbegin, ncount);
+            if (rc != HB_OK) return rc;
+        }
+        WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
+        const float l = hb_batch_loss(m, st.x[buf], st.y[buf], count);  // synchronises the model's stream
+        if (l != l) return hb_last_error_code();
+        WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
+        sum += (double)l * (double)count;
+        begin = nbegin;
+        count = ncount;
+        buf ^= 1;
+    }
+    WK_HIP(hipStreamSynchronize(st.copy));
+    *mean_loss = sum / (double)n_examples;
     return HB_OK;
 }

@@ -134,3 +134,32 @@ def test_worker_argument_errors():
         m.worker_run_epoch(s2, 0, None, y, 0.01)
     assert m.worker_run_epoch(s2, 0, X, y, 0.01)[1] == 4
     m.destroy()
+
+
+def test_epoch_loss_evaluation_matches_oracle_mean_loss():
+    """Section 5.2's evaluation stage: forward-only mean loss over host-resident data in pieces
+    (a ragged last piece), fp32 and bf16."""
+    import paper_2004_08771_amd as hb
+    import torch
+    dims, act, loss = (54, 64, 32, 7), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    n = 3000
+    X, y, params = _data(n, dims, 21)
+    ref = oracle.batch_loss(dims, act, loss, params.astype(np.float64), X, y)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 512)
+    m.set_params(params)
+    before = np.empty_like(params); m.get_params(before)
+    got = m.worker_eval_loss(X, y, n, 512)             # 5 pieces of 512 and one of 440
+    after = np.empty_like(params); m.get_params(after)
+    assert abs(got - ref) <= TOL * abs(ref)
+    assert abs(m.worker_eval_loss(X, y, n, 7) - ref) <= TOL * abs(ref)
+    np.testing.assert_array_equal(before, after)
+    with pytest.raises(hb.HbError):
+        m.worker_eval_loss(X, y, n, 513)               # above max_B
+    m.destroy()
+    Xb = torch.from_numpy(X).to(torch.bfloat16)
+    refb = oracle.batch_loss(dims, act, loss, oracle.round_weights_bf16(dims, params), oracle.bf16_round(X), y)
+    mb = hb.Model(dims, act, loss).configure(hb.HB_BF16_F32MASTER, 1024)
+    mb.set_params(params)
+    gotb = mb.worker_eval_loss(Xb, y, n, 1024)
+    mb.destroy()
+    assert abs(gotb - refb) <= 2e-2 * abs(refb)
