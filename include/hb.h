@@ -259,6 +259,24 @@ int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *ho
 int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples, int64_t batch,
                         double *mean_loss);
 
+/*
+ * The CPU worker's share of one epoch (Algorithm 2, CPU worker; Sections 6.1-6.3), host code
+ * only: until the coordinator sends nothing more, ask for a batch, split it into `threads`
+ * contiguous sub-batches (sizes differ by at most one), let one thread per sub-batch compute
+ * the mean gradient of its sub-batch on the SHARED fp32 host model (Eq. (1)-(2)) and apply it
+ * with lr = lr_per_example * (sub-batch size) (Eq. (3)) without locks or atomics, then count
+ * threads * beta model updates (beta in (0, 1]: the fraction of conflicting updates assumed to
+ * survive).  With a batch of `threads` examples this is Hogwild.  The network is described as
+ * for hb_mlp_create; host_model uses the flat layout; host_X is fp32.  *updates is in/out as
+ * for the GPU worker; *batches_out, *loss_sum_out (may be NULL): batches taken and the sum
+ * over batches and threads of the sub-batch mean losses.  With threads = 1 the result is
+ * deterministic: plain sequential mini-batch SGD in fp32.
+ */
+int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_t *layer_dims, int32_t n_dims, int activation,
+                            int loss, const float *host_X, const int32_t *host_y, float *host_model,
+                            float lr_per_example, int32_t threads, double beta, double *updates,
+                            int64_t *batches_out, double *loss_sum_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,8 @@ SIGNATURES["hb_sched_batch_size"] = (_i64, [_vp, _i32])
 SIGNATURES["hb_sched_remaining"] = (_i64, [_vp])
 SIGNATURES["hb_worker_run_epoch"] = (_int, [_vp, _vp, _i32, _vp, _vp, _f32, _vp, _i32, _f32, _f64p, _i64p, _f64p])
 SIGNATURES["hb_worker_eval_loss"] = (_int, [_vp, _vp, _vp, _i64, _i64, _f64p])
+SIGNATURES["hb_cpu_worker_run_epoch"] = (_int, [_vp, _i32, _i32p, _i32, _int, _int, _vp, _vp, _vp, _f32, _i32, _f64,
+                                                _f64p, _i64p, _f64p])
 
 _lib = None
 
@@ -243,3 +245,17 @@ class Sched:
 
     def remaining(self) -> int:
         return int(lib().hb_sched_remaining(self._h))
+
+
+def cpu_worker_run_epoch(sched, worker, layer_dims, activation, loss, host_X, host_y, host_model, lr_per_example,
+                         threads=1, beta=1.0, updates=0.0):
+    """hb_cpu_worker_run_epoch.  Returns (updates, batches, loss_sum).  Host-only."""
+    dims = (ctypes.c_int32 * len(layer_dims))(*[int(d) for d in layer_dims])
+    u = ctypes.c_double(float(updates))
+    nb = ctypes.c_int64(0)
+    ls = ctypes.c_double(0.0)
+    _check(lib().hb_cpu_worker_run_epoch(sched._h, int(worker), dims, len(layer_dims), int(activation), int(loss),
+                                         _ptr(host_X), _ptr(host_y), _ptr(host_model), float(lr_per_example),
+                                         int(threads), float(beta), ctypes.byref(u), ctypes.byref(nb),
+                                         ctypes.byref(ls)))
+    return u.value, nb.value, ls.value

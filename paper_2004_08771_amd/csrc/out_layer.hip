@@ -12,6 +12,8 @@
 // has about one block per CU (R = 16 at B = 4096).  512 threads per block.
 #include "hb_internal.h"
 
+#include <stdlib.h>
+
 namespace hb {
 namespace {
 
@@ -215,6 +217,8 @@ int out_layer_rows_for_batch(int d, int K, long long B)
     if (rmax == 0) return 0;
     int R = out_layer_min_rows();
     while (R < rmax && (long long)R * 2 * 256 <= B) R <<= 1;
+    static const int forced = getenv("HB_OL_ROWS") ? atoi(getenv("HB_OL_ROWS")) : 0;  // tuning aid: 8, 16, 32, 64
+    if (forced >= out_layer_min_rows() && forced <= rmax && (forced & (forced - 1)) == 0) R = forced;
     return R;
 }
 

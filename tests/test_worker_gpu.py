@@ -163,3 +163,48 @@ def test_epoch_loss_evaluation_matches_oracle_mean_loss():
     gotb = mb.worker_eval_loss(Xb, y, n, 1024)
     mb.destroy()
     assert abs(gotb - refb) <= 2e-2 * abs(refb)
+
+
+def test_cpu_and_gpu_workers_share_an_epoch():
+    """CPU+GPU Adaptive Hogbatch end to end on synthetic data: one scheduler, one shared host
+    model, a CPU worker (Hogwild threads) and the GPU worker running concurrently, the GPU
+    replica blended into the host model after every step.  The interleaving is not
+    deterministic; what must hold is what the algorithm fixes."""
+    import threading
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (32, 64, 32, 6), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    n = 20000
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    teacher = rng.standard_normal((dims[0], dims[-1]))
+    y = np.argmax(X @ teacher, axis=1).astype(np.int32)
+    params = hi.xavier_uniform_params(dims, rng)
+    before = oracle.batch_loss(dims, act, loss, params, X, y)
+    H = params.copy()
+    t = 4
+    s = hb.Sched(n, [t, 64], [8 * t, 1024], [t, 1024], 2.0)      # CPU starts at its lower, GPU at its upper threshold
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 1024)
+    m.set_params(params)
+    out = {}
+
+    def gpu():
+        out["gpu"] = m.worker_run_epoch(s, 1, X, y, 0.02 / 64, host_model=H, merge_every=1, merge_weight=0.5)
+
+    def cpu():
+        out["cpu"] = hb.cpu_worker_run_epoch(s, 0, dims, act, loss, X, y, H, 0.02 / 64, threads=t, beta=1.0)
+
+    th = [threading.Thread(target=gpu), threading.Thread(target=cpu)]
+    for x in th:
+        x.start()
+    for x in th:
+        x.join(timeout=100)
+    assert "gpu" in out and "cpu" in out
+    ug, steps, _ = out["gpu"]
+    uc, batches, _ = out["cpu"]
+    m.destroy()
+    assert steps >= 1 and batches >= 1 and ug == steps and uc == batches * t
+    assert s.remaining() < 64                                    # less than the GPU worker's smallest batch is left
+    assert t <= s.batch_size(0) <= 8 * t and 64 <= s.batch_size(1) <= 1024
+    assert np.all(np.isfinite(H))
+    after = oracle.batch_loss(dims, act, loss, H, X, y)
+    assert after < before
