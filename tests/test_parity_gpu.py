@@ -181,6 +181,18 @@ def test_config3(B):
 
 
 # ---------------------------------------------------------------- async variant + merge
+@pytest.mark.parametrize("dims,B", [
+    ((54, 512, 512, 512, 512, 512, 512, 2), 1000),            # the paper's covtype network: 6 x 512 hidden, 2 labels
+    ((500, 512, 512, 512, 512, 512, 512, 512, 512, 983), 512),  # delicious-shaped: 8 x 512 hidden, 983 outputs
+])
+def test_paper_shaped_deep_nets(dims, B):
+    """The networks of the paper's experiments (Table 2 / Section 7.1: 6 to 8 hidden layers of
+    512 sigmoid units; the 983-way output takes the separate loss kernel instead of the fused
+    narrow output layer) on synthetic data of their shapes."""
+    params, X, y = _problem(dims, hi.LOSS_SOFTMAX_CE, B, seed=900 + len(dims), bias_scale=0.1)
+    check_case(dims, hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, params, X, y, lr=0.1)
+
+
 def test_async_step_matches_sync_and_writes_device_loss():
     torch = _torch()
     dims, act, loss = (54, 64, 64, 7), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
