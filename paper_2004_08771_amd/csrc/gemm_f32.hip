@@ -420,6 +420,177 @@ __global__ __launch_bounds__(NT) void gemm_f32_bwd_pair_kernel(GemmArgs da, Gemm
     }
 }
 
+// ---- small products: one 32 x 32 output block per workgroup, the contraction split over
+// the four wavefronts.
+//
+// With few output tiles (a small batch) the 64 x 64 kernel leaves most compute units idle
+// while each wavefront walks the whole contraction alone: K / 2 dependent-issue MFMAs of 64
+// cycles each are the run time, whatever the batch.  Here every workgroup owns one 32 x 32
+// block and its wavefront w takes the k-groups {w, w + 4, ...} of every k-tile, so the MFMA
+// chain per wavefront is a quarter as long and four times as many workgroups exist.  The four
+// partial blocks meet in LDS (the tile stages are free by then) and every wavefront finishes
+// eight rows of the block with the fused epilogue.
+template <int BK, bool A_KMAJ, bool B_KMAJ, int KIND>
+__device__ __forceinline__ void gemm_f32_small_tile(const GemmArgs &a, float *smem, int id, int split)
+{
+    using TA = Tile<32, BK, A_KMAJ>;
+    using TB = Tile<32, BK, B_KMAJ>;
+    constexpr int STAGE = TA::FLOATS + TB::FLOATS;
+    constexpr int G = BK / 8;  // k-groups of 8 per tile
+    static_assert(G % 4 == 0, "k-groups are dealt to four wavefronts");
+    constexpr int Q = G / 4;   // k-groups per wavefront and tile
+    constexpr int RED_LD = 40, RED = 32 * RED_LD;  // 4 rows apart = 32 banks apart
+    static_assert(2 * STAGE >= 4 * RED, "partial blocks reuse the tile stages");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+
+    const int tile_m = id / a.tiles_n, tile_n = id - tile_m * a.tiles_n;
+    const int m0 = tile_m * 32, n0 = tile_n * 32;
+    const int kbeg = split * a.k_chunk;
+    const int kend = min(a.K, kbeg + a.k_chunk);
+    const int nk = (kend - kbeg + BK - 1) / BK;
+
+    const float *__restrict__ A = static_cast<const float *>(a.A);
+    const float *__restrict__ Bm = static_cast<const float *>(a.B);
+
+    v16f acc[2];  // two independent MFMA chains
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+
+    const bool a_in = (m0 + 32 <= a.M), b_in = (n0 + 32 <= a.N);
+    float colsum = 0.f;
+    const bool do_colsum = (KIND == GEMM_DW) && a.colsum != nullptr && tile_n == 0;
+
+    v4f ra[TA::VPT], rb[TB::VPT];
+    auto load_tile = [&](int t) {
+        const int k0 = kbeg + t * BK;
+        const bool kfull = (k0 + BK <= kend);
+        if (a_in && kfull) TA::load_fast(ra, A, a.lda, m0, k0, a.a_vec != 0, tid);
+        else TA::load(ra, A, a.lda, m0, a.M, k0, kend, a.a_vec != 0, tid);
+        if (b_in && kfull) TB::load_fast(rb, Bm, a.ldb, n0, k0, a.b_vec != 0, tid);
+        else TB::load(rb, Bm, a.ldb, n0, a.N, k0, kend, a.b_vec != 0, tid);
+    };
+    v4f fa[Q], fb[Q];
+    auto read_frags = [&](const float *As, const float *Bs) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            fa[q] = TA::frag(As, r, wave + 4 * q, h);
+            fb[q] = TB::frag(Bs, r, wave + 4 * q, h);
+        }
+    };
+
+    // global loads run two k-tiles ahead, the LDS write one tile ahead, the fragments of tile
+    // kt+1 are read right after the barrier of tile kt, under its last MFMAs
+    load_tile(0);
+    TA::store(smem, ra, tid);
+    TB::store(smem + TA::FLOATS, rb, tid);
+    if (nk > 1) load_tile(1);
+    __syncthreads();
+    read_frags(smem, smem + TA::FLOATS);
+    for (int kt = 0; kt < nk; ++kt) {
+        const float *As = smem + (kt & 1) * STAGE;
+        float *An = smem + ((kt + 1) & 1) * STAGE;
+        const bool next = (kt + 1 < nk);
+        if (next) {
+            TA::store(An, ra, tid);
+            TB::store(An + TA::FLOATS, rb, tid);
+        }
+        if (kt + 2 < nk) load_tile(kt + 2);
+        if (KIND == GEMM_DW && !A_KMAJ) {
+            if (do_colsum && tid < 32) {
+#pragma unroll
+                for (int k = 0; k < BK; ++k) colsum += As[k * TA::LD + tid];
+            }
+        }
+        v4f ca[Q], cb[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            ca[q] = fa[q];
+            cb[q] = fb[q];
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+                acc[q & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[q][s], cb[q][s], acc[q & 1], 0, 0, 0);
+        __syncthreads();  // tile kt read by everyone (fragments are in registers), tile kt+1 written
+        if (next) read_frags(An, An + TA::FLOATS);
+#pragma unroll
+        for (int s = 2; s < 4; ++s)
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+                acc[q & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[q][s], cb[q][s], acc[q & 1], 0, 0, 0);
+    }
+
+    // ---- the four partial blocks meet in LDS.  acc[.][v] is C(row, col) with
+    //      row = 8 (v / 4) + 4 h + (v % 4), col = r.  After the loop's last barrier nobody
+    //      reads a tile stage any more (the DW column sums read theirs before it).
+    float *mine = smem + wave * RED;
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+        mine[(8 * (v >> 2) + 4 * h + (v & 3)) * RED_LD + r] = acc[0][v] + acc[1][v];
+    __syncthreads();
+
+    float *__restrict__ C = static_cast<float *>(a.C) + (size_t)split * a.c_split_stride;
+    const int n = n0 + r;
+    const bool n_ok = n < a.N;
+    float bias = 0.f;
+    if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int row = 8 * wave + 2 * p + h;
+        const int m = m0 + row;
+        float x = smem[row * RED_LD + r] + smem[RED + row * RED_LD + r] +
+                  (smem[2 * RED + row * RED_LD + r] + smem[3 * RED + row * RED_LD + r]);
+        if (m < a.M && n_ok) {
+            if (KIND == GEMM_FWD) {
+                x += bias;
+                if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
+                else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
+            } else if (KIND == GEMM_DA) {
+                const float o = static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
+                if (a.act == ACT_SIGMOID) x *= o * (1.f - o);
+                else if (a.act == ACT_RELU) x = (o > 0.f) ? x : 0.f;
+            }
+            C[(size_t)m * a.ldc + n] = x;
+        }
+    }
+    if (KIND == GEMM_DW) {
+        if (do_colsum && tid < 32 && m0 + tid < a.M)
+            a.colsum[(size_t)split * a.M + m0 + tid] = colsum;
+    }
+}
+
+constexpr int SMALL_BK = 64;
+
+template <bool A_KMAJ, bool B_KMAJ, int KIND>
+__global__ __launch_bounds__(NT) void gemm_f32_small_kernel(GemmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float smem[lds_floats<32, 32, SMALL_BK, A_KMAJ, B_KMAJ>()];
+    gemm_f32_small_tile<SMALL_BK, A_KMAJ, B_KMAJ, KIND>(a, smem, xcd_tile_order(blockIdx.x, gridDim.x),
+                                                       blockIdx.y);
+}
+
+// The backward pair of one hidden layer (see gemm_f32_bwd_pair_kernel) for small batches.
+__global__ __launch_bounds__(NT) void gemm_f32_small_pair_kernel(GemmArgs da, GemmArgs dw, int n_dw)
+{
+    constexpr int LDS_DA = lds_floats<32, 32, SMALL_BK, true, false>();
+    constexpr int LDS_DW = lds_floats<32, 32, SMALL_BK, false, false>();
+    __shared__ __attribute__((aligned(16))) float smem[LDS_DA > LDS_DW ? LDS_DA : LDS_DW];
+    const int b = blockIdx.x;
+    if (b < n_dw) {
+        const int tiles = dw.tiles_m * dw.tiles_n;
+        gemm_f32_small_tile<SMALL_BK, false, false, GEMM_DW>(dw, smem, xcd_tile_order(b % tiles, tiles), b / tiles);
+    } else {
+        const int n_da = gridDim.x - n_dw;
+        gemm_f32_small_tile<SMALL_BK, true, false, GEMM_DA>(da, smem, xcd_tile_order(b - n_dw, n_da), 0);
+    }
+}
+
 int env_int(const char *name, int dflt)
 {
     const char *s = getenv(name);
@@ -488,19 +659,78 @@ SplitPlan plan_splits(int tiles, int K, int max_splits, int wgs = 0)
     return {(K + chunk - 1) / chunk, chunk};
 }
 
+// Products with fewer 64 x 64 output tiles than this (forward / backward-data), or a
+// contraction shorter than small_k_max() (weight gradient, whose contraction is the batch),
+// go to the 32 x 32 split-wavefront kernel.  HB_GEMM_SMALL_TILES / HB_GEMM_SMALL_K: tuning aids
+// (0 switches the small kernels off).
+int small_tiles_max()
+{
+    static const int v = env_int("HB_GEMM_SMALL_TILES", 256);
+    return v;
+}
+int small_k_max()
+{
+    static const int v = env_int("HB_GEMM_SMALL_K", 2048);
+    return v;
+}
+bool small_out(int M, int N, int K)
+{
+    static const int forced = env_int("HB_GEMM_TILE", 0);
+    return forced == 0 && K >= 64 && (long long)((M + 63) / 64) * ((N + 63) / 64) < small_tiles_max();
+}
+bool small_dw(int K)
+{
+    static const int forced = env_int("HB_GEMM_TILE", 0);
+    return forced == 0 && K >= 64 && K < small_k_max();
+}
+// K-slices of the small weight-gradient kernel: one up to K = 768, then about 512 long
+// (multiples of its k-tile)
+SplitPlan plan_small_splits(int K, int max_splits)
+{
+    int s = (K <= 768) ? 1 : (K + 511) / 512;
+    if (s > max_splits) s = max_splits;
+    if (s < 1) s = 1;
+    const int chunk = ((K + s - 1) / s + SMALL_BK - 1) / SMALL_BK * SMALL_BK;
+    return {(K + chunk - 1) / chunk, chunk};
+}
+
 }  // namespace
 
 int gemm_f32_dw_splits(int M, int N, int K, int max_splits)
 {
     const Shape sh = pick_shape(GEMM_DW, M, N);
     const int tiles = ((M + sh.bm - 1) / sh.bm) * ((N + sh.bn - 1) / sh.bn);
-    return plan_splits(tiles, K, max_splits).splits;
+    const int big = plan_splits(tiles, K, max_splits).splits;
+    const int ks = K < small_k_max() ? K : small_k_max() - 1;  // longest contraction of the small kernel
+    const int small = (ks >= 64) ? plan_small_splits(ks, max_splits).splits : 1;
+    return big > small ? big : small;
 }
 
 hipError_t launch_gemm_f32(GemmKind kind, GemmArgs a, int max_splits, int *splits_out,
                            hipStream_t stream, const LaunchEvents &ev)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
+    if (kind == GEMM_DW ? small_dw(a.K) : small_out(a.M, a.N, a.K)) {
+        a.tiles_m = (a.M + 31) / 32;
+        a.tiles_n = (a.N + 31) / 32;
+        const long long tiles = (long long)a.tiles_m * a.tiles_n;
+        if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+        SplitPlan sp = {1, (a.K + SMALL_BK - 1) / SMALL_BK * SMALL_BK};
+        if (kind == GEMM_DW) sp = plan_small_splits(a.K, max_splits);
+        a.splits = sp.splits;
+        a.k_chunk = sp.chunk;
+        if (splits_out) *splits_out = sp.splits;
+        const dim3 grid((unsigned)tiles, (unsigned)sp.splits, 1);
+        switch (kind) {
+        case GEMM_FWD:
+            return launch_kernel(gemm_f32_small_kernel<true, true, GEMM_FWD>, grid, dim3(NT), stream, ev, a);
+        case GEMM_DA:
+            return launch_kernel(gemm_f32_small_kernel<true, false, GEMM_DA>, grid, dim3(NT), stream, ev, a);
+        case GEMM_DW:
+            return launch_kernel(gemm_f32_small_kernel<false, false, GEMM_DW>, grid, dim3(NT), stream, ev, a);
+        }
+        return hipErrorInvalidValue;
+    }
     const Shape sh = pick_shape(kind, a.M, a.N);
     static const int no_fast = env_int("HB_GEMM_NOFAST", 0);
     a.no_fast_loop = no_fast;
@@ -537,6 +767,24 @@ hipError_t launch_gemm_f32_bwd_pair(GemmArgs da, GemmArgs dw, int max_splits, in
     static const int pair_wgs = env_int("HB_PAIR_WGS", 256);  // weight-gradient blocks wanted (tuning aid)
     static const int no_fast = env_int("HB_GEMM_NOFAST", 0);
     da.no_fast_loop = dw.no_fast_loop = no_fast;
+    if (small_out(da.M, da.N, da.K) && small_dw(dw.K)) {
+        da.tiles_m = (da.M + 31) / 32;
+        da.tiles_n = (da.N + 31) / 32;
+        da.splits = 1;
+        da.k_chunk = (da.K + SMALL_BK - 1) / SMALL_BK * SMALL_BK;
+        dw.tiles_m = (dw.M + 31) / 32;
+        dw.tiles_n = (dw.N + 31) / 32;
+        const long long n_da = (long long)da.tiles_m * da.tiles_n;
+        const long long t_dw = (long long)dw.tiles_m * dw.tiles_n;
+        const SplitPlan sp = plan_small_splits(dw.K, max_splits);
+        dw.splits = sp.splits;
+        dw.k_chunk = sp.chunk;
+        if (splits_out) *splits_out = sp.splits;
+        const long long blocks = n_da + t_dw * sp.splits;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        return launch_kernel(gemm_f32_small_pair_kernel, dim3((unsigned)blocks), dim3(NT), stream, ev, da, dw,
+                             (int)(t_dw * sp.splits));
+    }
     da.tiles_m = (da.M + 63) / 64;
     da.tiles_n = (da.N + 63) / 64;
     da.splits = 1;

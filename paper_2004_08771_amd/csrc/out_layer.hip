@@ -22,10 +22,15 @@ constexpr int OL_KMAX = 16;  // widest output handled here
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
+// K (the number of outputs) is a template parameter: every loop over the outputs unrolls
+// without a branch, so the LDS reads and lane exchanges of all outputs are in flight together
+// instead of one round trip per output.
+template <int K>
 __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
 {
+    static_assert(K >= 1 && K <= OL_KMAX, "output width");
     extern __shared__ __attribute__((aligned(16))) float sm[];
-    const int d = a.d, K = a.K, R = a.R;
+    const int d = a.d, R = a.R;
     const int lda_s = d + 4;                    // LDS row stride of the activation tile
     float *sW = sm;                             // K x d
     float *sD = sW + (size_t)K * d;             // R x OL_KMAX : D_L
@@ -36,33 +41,46 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
     const long long r0 = (long long)blockIdx.x * R;
     const int d4 = d >> 2;
 
-    // ---- P1: activations, weights, bias -> LDS (16-byte coalesced)
-    for (int base = tid; base < R * d4; base += 4 * OL_NT) {  // four loads in flight per thread
-        float4 v[4];
-        int off[4];
+    // ---- P1: activations, weights, bias -> LDS (16-byte coalesced).  Everything the block
+    // needs from memory is requested before the first wait: the label of the thread's row,
+    // the first four activation vectors per thread, then weights and bias.
+    const int TPR = OL_NT / R;                  // 8 .. 64, power of two
+    const int row = tid / TPR, c = tid - row * TPR;
+    const bool row_ok = (r0 + row < a.B);
+    int yi = 0;
+    if (c == 0 && row_ok) yi = a.y[r0 + row];
+    float4 v[4];
+    int off[4];
+    auto load_a = [&](int base) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int idx = base + u * OL_NT;
             v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             off[u] = -1;
             if (idx < R * d4) {
-                const int row = idx / d4, c4 = idx - row * d4;
-                off[u] = row * lda_s + 4 * c4;
-                if (r0 + row < a.B) v[u] = ld4(a.A + (size_t)(r0 + row) * a.lda + 4 * c4);
+                const int ar = idx / d4, c4 = idx - ar * d4;
+                off[u] = ar * lda_s + 4 * c4;
+                if (r0 + ar < a.B) v[u] = ld4(a.A + (size_t)(r0 + ar) * a.lda + 4 * c4);
             }
         }
+    };
+    auto store_a = [&]() {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
             if (off[u] >= 0) *reinterpret_cast<float4 *>(&sA[off[u]]) = v[u];
-    }
+    };
+    load_a(tid);
     for (int idx = tid; idx < K * d4; idx += OL_NT)
         *reinterpret_cast<float4 *>(&sW[4 * idx]) = ld4(a.W + 4 * (size_t)idx);
     if (tid < K) sB[tid] = a.bias[tid];
+    store_a();
+    for (int base = tid + 4 * OL_NT; base < R * d4; base += 4 * OL_NT) {
+        load_a(base);
+        store_a();
+    }
     __syncthreads();
 
     // ---- P2: logits.  TPR adjacent lanes share a row, each takes every TPR-th float4 of k
-    const int TPR = OL_NT / R;                  // 8 .. 64, power of two
-    const int row = tid / TPR, c = tid - row * TPR;
     float z[OL_KMAX];
 #pragma unroll
     for (int j = 0; j < OL_KMAX; ++j) z[j] = 0.f;
@@ -75,21 +93,24 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
                 z[j] += x.x * w.x + x.y * w.y + x.z * w.z + x.w * w.w;
             }
     }
+    for (int o = TPR >> 1; o > 0; o >>= 1) {  // all K exchanges of a step are issued together
+        float t[OL_KMAX];
 #pragma unroll
-    for (int j = 0; j < OL_KMAX; ++j)
-        if (j < K)
-            for (int o = TPR >> 1; o > 0; o >>= 1) z[j] += __shfl_xor(z[j], o, 64);
+        for (int j = 0; j < OL_KMAX; ++j)
+            if (j < K) t[j] = __shfl_xor(z[j], o, 64);
+#pragma unroll
+        for (int j = 0; j < OL_KMAX; ++j)
+            if (j < K) z[j] += t[j];
+    }
 
     // ---- P3: loss and D_L for the row (one lane per row)
     float row_loss = 0.f;
-    const bool row_ok = (r0 + row < a.B);
     if (c == 0) {
         const float invB = 1.0f / (float)a.B;
         float dl[OL_KMAX];
 #pragma unroll
         for (int j = 0; j < OL_KMAX; ++j) dl[j] = 0.f;
         if (row_ok) {
-            const int yi = a.y[r0 + row];
 #pragma unroll
             for (int j = 0; j < OL_KMAX; ++j)
                 if (j < K) z[j] += sB[j];
@@ -118,10 +139,14 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
                 for (int j = 0; j < OL_KMAX; ++j)
                     if (j < K) dl[j] = (__expf(z[j] - lse) - (j == cls ? 1.f : 0.f)) * invB;
             }
-            if (a.Z)
+            if (a.Z) {
+#pragma unroll
                 for (int j = 0; j < K; ++j) a.Z[(size_t)(r0 + row) * a.ldz + j] = z[j];
-            if (a.DL)
+            }
+            if (a.DL) {
+#pragma unroll
                 for (int j = 0; j < K; ++j) a.DL[(size_t)(r0 + row) * a.ldz + j] = dl[j];
+            }
         }
 #pragma unroll
         for (int j = 0; j < OL_KMAX; ++j) sD[row * OL_KMAX + j] = dl[j];  // zero rows past B
@@ -145,10 +170,14 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
             const int i = idx / d4, c4 = idx - i * d4;
             if (r0 + i >= a.B) continue;
             float4 s = {0.f, 0.f, 0.f, 0.f};
+            alignas(16) float dl[OL_KMAX];
+#pragma unroll
+            for (int q = 0; q < (K + 3) / 4; ++q)
+                *reinterpret_cast<float4 *>(&dl[4 * q]) = *reinterpret_cast<const float4 *>(&sD[i * OL_KMAX + 4 * q]);
 #pragma unroll
             for (int j = 0; j < OL_KMAX; ++j)
                 if (j < K) {
-                    const float dj = sD[i * OL_KMAX + j];
+                    const float dj = dl[j];
                     const float4 w = *reinterpret_cast<const float4 *>(&sW[j * d + 4 * c4]);
                     s.x += dj * w.x; s.y += dj * w.y; s.z += dj * w.z; s.w += dj * w.w;
                 }
@@ -171,12 +200,17 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
         float4 g[OL_KMAX];
 #pragma unroll
         for (int j = 0; j < OL_KMAX; ++j) g[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int i = 0; i < R; ++i) {
+#pragma unroll 4
+        for (int i = 0; i < R; ++i) {  // R is a multiple of 8
             const float4 x = *reinterpret_cast<const float4 *>(&sA[i * lda_s + 4 * c4]);
+            alignas(16) float dl[OL_KMAX];
+#pragma unroll
+            for (int q = 0; q < (K + 3) / 4; ++q)
+                *reinterpret_cast<float4 *>(&dl[4 * q]) = *reinterpret_cast<const float4 *>(&sD[i * OL_KMAX + 4 * q]);
 #pragma unroll
             for (int j = 0; j < OL_KMAX; ++j)
                 if (j < K) {
-                    const float dj = sD[i * OL_KMAX + j];
+                    const float dj = dl[j];
                     g[j].x += dj * x.x; g[j].y += dj * x.y; g[j].z += dj * x.z; g[j].w += dj * x.w;
                 }
         }
@@ -227,18 +261,32 @@ hipError_t launch_out_layer(OutLayerArgs a, hipStream_t stream, const LaunchEven
     a.R = out_layer_rows_for_batch(a.d, a.K, a.B);
     if (a.R == 0) return hipErrorInvalidValue;
     const size_t lds = lds_bytes(a.R, a.d, a.K);
-    static size_t granted = 0;
-    if (lds > granted) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(out_layer_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        granted = lds;
-    }
     const dim3 grid((unsigned)((a.B + a.R - 1) / a.R)), block(OL_NT);
-    if (ev.start)
-        hipExtLaunchKernelGGL(out_layer_kernel, grid, block, (unsigned)lds, stream, ev.start, ev.stop, 0, a);
-    else
-        hipLaunchKernelGGL(out_layer_kernel, grid, block, lds, stream, a);
+    static size_t granted[OL_KMAX + 1] = {};
+    hipError_t e = hipErrorInvalidValue;
+    switch (a.K) {
+#define HB_OL_CASE(KK)                                                                                   \
+    case KK:                                                                                             \
+        e = hipSuccess;                                                                                  \
+        if (lds > granted[KK]) {                                                                         \
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(out_layer_kernel<KK>),                \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);               \
+            if (e == hipSuccess) granted[KK] = lds;                                                      \
+        }                                                                                                \
+        if (e != hipSuccess) return e;                                                                   \
+        if (ev.start)                                                                                    \
+            hipExtLaunchKernelGGL(out_layer_kernel<KK>, grid, block, (unsigned)lds, stream, ev.start,    \
+                                  ev.stop, 0, a);                                                        \
+        else                                                                                             \
+            hipLaunchKernelGGL(out_layer_kernel<KK>, grid, block, lds, stream, a);                       \
+        break;
+        HB_OL_CASE(1) HB_OL_CASE(2) HB_OL_CASE(3) HB_OL_CASE(4) HB_OL_CASE(5) HB_OL_CASE(6) HB_OL_CASE(7)
+        HB_OL_CASE(8) HB_OL_CASE(9) HB_OL_CASE(10) HB_OL_CASE(11) HB_OL_CASE(12) HB_OL_CASE(13)
+        HB_OL_CASE(14) HB_OL_CASE(15) HB_OL_CASE(16)
+#undef HB_OL_CASE
+    default:
+        return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
