@@ -401,19 +401,20 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmArgs a)
 }
 
 // Backward of one hidden layer in ONE launch: the backward-data product D_{l-1} = (D_l W_l) f'
-// (64 x 64 x 32 tiles) and the weight-gradient product dW_l = D_l^T A_{l-1} (128 x 64 x 32
-// tiles x K-slices).  Both only read D_l, so they are
-// independent; sharing a launch lets the prologue / epilogue of one hide under the main loop
-// of the other and pays the per-launch latencies once.
+// (64 x 64 x 32 tiles) and the weight-gradient product dW_l = D_l^T A_{l-1} (DW_BM x 64 x 32
+// tiles x K-slices, DW_BM = 128 or 64).  Both only read D_l, so they are independent; sharing
+// a launch lets the prologue / epilogue of one hide under the main loop of the other and pays
+// the per-launch latencies once.
+template <int DW_BM>
 __global__ __launch_bounds__(NT) void gemm_f32_bwd_pair_kernel(GemmArgs da, GemmArgs dw, int n_dw)
 {
     constexpr int LDS_DA = lds_floats<64, 64, 32, true, false>();
-    constexpr int LDS_DW = lds_floats<128, 64, 32, false, false>();
+    constexpr int LDS_DW = lds_floats<DW_BM, 64, 32, false, false>();
     __shared__ __attribute__((aligned(16))) float smem[LDS_DA > LDS_DW ? LDS_DA : LDS_DW];
     const int b = blockIdx.x;
     if (b < n_dw) {  // the weight-gradient blocks are the longer ones: they are dispatched first
         const int tiles = dw.tiles_m * dw.tiles_n;
-        gemm_f32_tile<128, 64, 32, 2, false, false, GEMM_DW>(dw, smem, xcd_tile_order(b % tiles, tiles), b / tiles);
+        gemm_f32_tile<DW_BM, 64, 32, 2, false, false, GEMM_DW>(dw, smem, xcd_tile_order(b % tiles, tiles), b / tiles);
     } else {
         const int n_da = gridDim.x - n_dw;
         gemm_f32_tile<64, 64, 32, 2, true, false, GEMM_DA>(da, smem, xcd_tile_order(b - n_dw, n_da), 0);
@@ -789,18 +790,27 @@ hipError_t launch_gemm_f32_bwd_pair(GemmArgs da, GemmArgs dw, int max_splits, in
     da.tiles_n = (da.N + 63) / 64;
     da.splits = 1;
     da.k_chunk = (da.K + K_CHUNK_ALIGN - 1) / K_CHUNK_ALIGN * K_CHUNK_ALIGN;
-    dw.tiles_m = (dw.M + 127) / 128;
-    dw.tiles_n = (dw.N + 63) / 64;
     const long long n_da = (long long)da.tiles_m * da.tiles_n;
+    // While everything fits the device at once (four 64 x 64 workgroups per CU by LDS), the
+    // weight gradient takes 64 x 64 tiles too: 2 x pair_wgs blocks as long as the backward-data
+    // ones, so no compute unit ends on a lone long block (measured at B = 2048 and 4096:
+    // 45 instead of 47 us; with more backward-data blocks than that the 128-row tile wins).
+    static const int dw64_env = env_int("HB_PAIR_DW64", -1);  // tuning aid: 0 / 1 force
+    const bool dw64 = dw64_env >= 0 ? dw64_env != 0 : (n_da + 2 * pair_wgs <= 4 * 256);
+    dw.tiles_m = dw64 ? (dw.M + 63) / 64 : (dw.M + 127) / 128;
+    dw.tiles_n = (dw.N + 63) / 64;
     const long long t_dw = (long long)dw.tiles_m * dw.tiles_n;
     if (n_da > 0x3fffffffLL || t_dw > 0x3fffffffLL) return hipErrorInvalidValue;
-    const SplitPlan sp = plan_splits((int)t_dw, dw.K, max_splits, pair_wgs);
+    const SplitPlan sp = plan_splits((int)t_dw, dw.K, max_splits, dw64 ? 2 * pair_wgs : pair_wgs);
     dw.splits = sp.splits;
     dw.k_chunk = sp.chunk;
     if (splits_out) *splits_out = sp.splits;
     const long long blocks = n_da + t_dw * sp.splits;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    return launch_kernel(gemm_f32_bwd_pair_kernel, dim3((unsigned)blocks), dim3(NT), stream, ev, da, dw,
+    if (dw64)
+        return launch_kernel(gemm_f32_bwd_pair_kernel<64>, dim3((unsigned)blocks), dim3(NT), stream, ev, da, dw,
+                             (int)(t_dw * sp.splits));
+    return launch_kernel(gemm_f32_bwd_pair_kernel<128>, dim3((unsigned)blocks), dim3(NT), stream, ev, da, dw,
                          (int)(t_dw * sp.splits));
 }
 
