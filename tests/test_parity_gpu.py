@@ -108,6 +108,9 @@ SMALL = [
     ((70, 65, 129, 67, 2), hi.ACT_RELU, hi.LOSS_LOGISTIC, 321),
     ((100, 200, 100), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 77),    # K = 100 softmax (> 64 lanes)
     ((40, 72, 1000), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 50),     # K = 1000 softmax
+    ((20, 24, 16), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 100),   # widest output of the fused output layer
+    ((20, 24, 13), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 37),
+    ((90, 96, 3), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 1500),   # split-wavefront kernels, 3 batch slices
 ]
 
 
@@ -139,7 +142,7 @@ def test_config1_one_epoch_of_64_steps():
 
 
 # ---------------------------------------------------------------- config 2, batch ladder
-@pytest.mark.parametrize("B", [16, 48, 256, 1000, 4096, 4097])
+@pytest.mark.parametrize("B", [16, 48, 256, 1000, 1100, 1999, 2048, 4096, 4097])
 def test_config2_batch_sizes(B):
     cfg = hi.CONFIGS[2]
     X, y = hi.make_dense_dataset(2, 8192)
