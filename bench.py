@@ -95,7 +95,7 @@ def main():
     model = hb.Model(cfg.dims, cfg.activation, cfg.loss)
     model.configure(hb.HB_BF16_F32MASTER if dtype_name == "bf16" else hb.HB_F32, B, cfg.sparse)
     model.set_params(hi.make_params(args.config))
-    lr = 0.1 * B / 256 if args.config == 2 else cfg.lr
+    lr = 0.1 * B / 256 if args.config in (2, 6, 7) else cfg.lr  # Section 6.2: lr proportional to B
 
     n_batches = rows // B
     if cfg.sparse:

@@ -52,6 +52,14 @@ CONFIGS = {
               LOSS_LOGISTIC, DTYPE_F32, 72_000, 8192, 0.05, sparse=True),
     5: Config(5, "wide-2048-4096x3-1000-bf16", (2048, 4096, 4096, 4096, 1000), ACT_RELU,
               LOSS_SOFTMAX_CE, DTYPE_BF16_F32MASTER, 1_000_000, 16384, 0.05),
+    # The networks of the paper's own experiments (Section 7.1, Table 2), on synthetic data of
+    # their shapes: covtype with 6 hidden layers of 512 sigmoid units and 2 labels at the GPU
+    # batch size the paper names (8192, Section 7.2), and the delicious-shaped net with 8 hidden
+    # layers and a 983-way output.
+    6: Config(6, "paper-covtype-54-512x6-2", (54,) + (512,) * 6 + (2,), ACT_SIGMOID,
+              LOSS_SOFTMAX_CE, DTYPE_F32, 581_012, 8192, 0.1 * 8192 / 256),
+    7: Config(7, "paper-delicious-500-512x8-983", (500,) + (512,) * 8 + (983,), ACT_SIGMOID,
+              LOSS_SOFTMAX_CE, DTYPE_F32, 16_105, 2048, 0.1 * 2048 / 256),
 }
 
 
@@ -197,15 +205,15 @@ def csr_slice(row_ptr, col_idx, vals, start: int, stop: int):
 
 # --------------------------------------------------------------------------- per-config
 def make_dense_dataset(config: int, n: int | None = None):
-    """(X float32 [n x d0], y int32 [n]) for dense configs 1, 2, 3, 5 (n rows; the
+    """(X float32 [n x d0], y int32 [n]) for dense configs 1, 2, 3, 5, 6, 7 (n rows; the
     config's full size when n is None)."""
     cfg = CONFIGS[config]
     n = cfg.n_examples if n is None else int(n)
     d0, k = cfg.dims[0], cfg.dims[-1]
     data_rng, label_rng = rng_for(config, 0), rng_for(config, 1)
-    if config == 1 or config == 5:
+    if config in (1, 5, 7):
         return gaussian_features(n, d0, data_rng), uniform_labels(n, k, label_rng)
-    if config == 2:
+    if config in (2, 6):
         x = covtype_like_features(n, data_rng)
         return x, teacher_labels(x, k, label_rng)
     if config == 3:
