@@ -233,7 +233,11 @@ int64_t hb_sched_remaining(const hb_sched *s);                  /* examples left
  * lr = lr_per_example * b (learning rate proportional to the batch size, Section 6.2).
  * Every merge_every steps (and once at the end if any step is unmerged) the replica is merged
  * with host_model as hb_model_merge(m, host_model, merge_weight) does; merge_every = 0 or
- * host_model = NULL: never.
+ * host_model = NULL: never.  merge_weight = 1 (the push of Section 6.2) does not wait for the
+ * device: the replica is snapshot in stream order and travels to host_model on a third stream
+ * while the next steps run (directly if host_model is page-locked, else through a page-locked
+ * buffer and a host copy); every push has landed when the call returns.  While the call runs,
+ * host_model may be written at any time after a merge point.
  *   host_X  n_examples x d_0 row-major in HOST memory (fp32, or bfloat16 in the bf16 mode),
  *           page-locked memory makes the copies asynchronous;  host_y  n_examples int32.
  *   *updates (in/out, may be NULL -> starts at 0): the worker's update count u^E, carried

@@ -732,6 +732,8 @@ bool model_info(const hb_model *m, ModelInfo *out)
     return true;
 }
 
+const float *model_params_device(const hb_model *m) { return m->d_params; }
+
 void **model_worker_slot(hb_model *m, void (*deleter)(void *))
 {
     m->worker_state_free = deleter;

@@ -264,6 +264,8 @@ struct ModelInfo {
 };
 // false (and the thread's error text set) if m is null or not configured
 bool model_info(const hb_model *m, ModelInfo *out);
+// the replica's flat fp32 parameters on the device (dense models: always current)
+const float *model_params_device(const hb_model *m);
 // slot in the handle where the worker loop keeps its staging buffers between calls; the
 // deleter runs in hb_model_destroy
 void **model_worker_slot(hb_model *m, void (*deleter)(void *));

@@ -6,12 +6,16 @@
 //
 // gfx950 / HIP design of the loop: two device staging buffers and a copy stream; the rows of
 // batch k+1 travel over PCIe while batch k computes, ordered by events in both directions
-// (a buffer is refilled only after the step that read it has finished).  Everything stays at
-// the default stream priority.
+// (a buffer is refilled only after the step that read it has finished).  A push of the
+// replica (merge weight 1) is asynchronous as in Section 6.2: a device-to-device snapshot in
+// stream order, then device -> host on a third stream beside the following steps, straight
+// into the host model when that is page-locked.  Everything stays at the default stream
+// priority.
 #include "hb_internal.h"
 
 #include <cmath>
 #include <cstdarg>
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -143,8 +147,22 @@ struct Staging {
     hipStream_t copy = nullptr;
     hipEvent_t filled[2] = {nullptr, nullptr};    // the copy into buffer i has finished
     hipEvent_t consumed[2] = {nullptr, nullptr};  // the step reading buffer i has finished
+    // asynchronous push of the replica (merge weight 1): a device snapshot, a page-locked
+    // landing buffer for host models in pageable memory, a third stream
+    long long snap_elems = 0;
+    float *snap = nullptr;
+    float *snap_host = nullptr;
+    hipStream_t push = nullptr;
+    hipEvent_t snap_taken = nullptr;   // the snapshot is complete (model's stream)
+    hipEvent_t snap_landed = nullptr;  // the snapshot has reached host memory (push stream)
     ~Staging()
     {
+        if (push) (void)hipStreamSynchronize(push);
+        if (snap) (void)hipFree(snap);
+        if (snap_host) (void)hipHostFree(snap_host);
+        if (snap_taken) (void)hipEventDestroy(snap_taken);
+        if (snap_landed) (void)hipEventDestroy(snap_landed);
+        if (push) (void)hipStreamDestroy(push);
         if (copy) (void)hipStreamSynchronize(copy);
         for (int i = 0; i < 2; ++i) {
             if (x[i]) (void)hipFree(x[i]);
@@ -204,6 +222,45 @@ int acquire_staging(hb_model *m, const hb::ModelInfo &mi, int64_t cap, size_t ro
     return HB_OK;
 }
 
+// Resources of the asynchronous push, created at the first epoch that pushes.
+int acquire_push(Staging &st, long long P)
+{
+    if (st.snap_elems >= P && st.push) return HB_OK;
+    if (st.push) WK_HIP(hipStreamSynchronize(st.push));
+    if (st.snap) WK_HIP(hipFree(st.snap));
+    if (st.snap_host) WK_HIP(hipHostFree(st.snap_host));
+    st.snap = nullptr;
+    st.snap_host = nullptr;
+    st.snap_elems = 0;
+    WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.snap), sizeof(float) * (size_t)P));
+    WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&st.snap_host), sizeof(float) * (size_t)P, hipHostMallocDefault));
+    if (!st.push) WK_HIP(hipStreamCreateWithFlags(&st.push, hipStreamNonBlocking));  // default priority
+    if (!st.snap_taken) WK_HIP(hipEventCreateWithFlags(&st.snap_taken, hipEventDisableTiming));
+    if (!st.snap_landed) WK_HIP(hipEventCreateWithFlags(&st.snap_landed, hipEventDisableTiming));
+    st.snap_elems = P;
+    return HB_OK;
+}
+
+// One push in flight at most.  finish() waits for it and, when the host model is in pageable
+// memory, copies the landed snapshot into it; the destructor does the same on every way out
+// of the epoch, so nothing writes to the caller's memory after the call has returned.
+struct PushGuard {
+    Staging &st;
+    float *host_model;
+    size_t bytes;
+    bool direct;  // the host model is page-locked: the copy engine writes into it
+    bool in_flight = false;
+    int finish()
+    {
+        if (!in_flight) return HB_OK;
+        in_flight = false;
+        WK_HIP(hipEventSynchronize(st.snap_landed));
+        if (!direct) std::memcpy(host_model, st.snap_host, bytes);
+        return HB_OK;
+    }
+    ~PushGuard() { (void)finish(); }
+};
+
 }  // namespace
 
 extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X,
@@ -226,6 +283,10 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     if (merge_every < 0 || (merge_every > 0 && host_model && !(merge_weight >= 0.f && merge_weight <= 1.f)))
         return hb::set_error(HB_ERR_INVALID, "merge_every must be >= 0 and merge_weight in [0, 1]");
     const bool merging = merge_every > 0 && host_model != nullptr;
+    // weight 1 is the paper's push (global <- replica, Section 6.2): it leaves the replica as it
+    // is, so it can run beside the following steps; any other weight changes the replica and
+    // is done in stream order by hb_model_merge
+    const bool pushing = merging && merge_weight == 1.f;
 
     const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
     const size_t row_bytes = elem * (size_t)mi.d0;
@@ -236,6 +297,31 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
         if (rc_st != HB_OK) return rc_st;
     }
     Staging &st = *sp;
+    bool host_model_locked = false;
+    if (pushing) {
+        const int rc_p = acquire_push(st, mi.P);
+        if (rc_p != HB_OK) return rc_p;
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, host_model) == hipSuccess)
+            host_model_locked = (attr.type == hipMemoryTypeHost);
+        else
+            (void)hipGetLastError();  // ordinary pageable memory is unknown to the runtime
+    }
+    PushGuard push{st, host_model, sizeof(float) * (size_t)mi.P, host_model_locked};
+    // snapshot on the model's stream (the next step may change the replica at once), then
+    // device -> host on the push stream while the next steps run
+    auto push_async = [&]() -> int {
+        int rc_f = push.finish();  // the snapshot and landing buffers are free again
+        if (rc_f != HB_OK) return rc_f;
+        WK_HIP(hipMemcpyAsync(st.snap, hb::model_params_device(m), push.bytes, hipMemcpyDeviceToDevice, mi.stream));
+        WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
+        WK_HIP(hipStreamWaitEvent(st.push, st.snap_taken, 0));
+        WK_HIP(hipMemcpyAsync(push.direct ? host_model : st.snap_host, st.snap, push.bytes, hipMemcpyDeviceToHost,
+                              st.push));
+        WK_HIP(hipEventRecord(st.snap_landed, st.push));
+        push.in_flight = true;
+        return HB_OK;
+    };
 
     double u = updates ? *updates : 0.0;
     int64_t steps = 0;
@@ -287,7 +373,7 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
             if (rc != HB_OK) return rc;
         }
         if (merging && since_merge >= merge_every) {
-            rc = hb_model_merge(m, host_model, merge_weight);
+            rc = pushing ? push_async() : hb_model_merge(m, host_model, merge_weight);
             if (rc != HB_OK) return rc;
             since_merge = 0;
         }
@@ -297,9 +383,11 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     rc = flush_losses();
     if (rc != HB_OK) return rc;
     if (merging && since_merge > 0) {
-        rc = hb_model_merge(m, host_model, merge_weight);
+        rc = pushing ? push_async() : hb_model_merge(m, host_model, merge_weight);
         if (rc != HB_OK) return rc;
     }
+    rc = push.finish();
+    if (rc != HB_OK) return rc;
     WK_HIP(hipStreamSynchronize(st.copy));
     WK_HIP(hipStreamSynchronize(mi.stream));
     if (updates) *updates = u;

@@ -118,6 +118,47 @@ def test_adaptive_batch_sizes_pageable_memory_and_merging():
     assert _rel(H, ref_H) <= TOL
 
 
+@pytest.mark.parametrize("locked", [True, False])
+def test_asynchronous_push_of_the_replica(locked):
+    """merge_weight = 1 is the push of Section 6.2: the replica is snapshot in stream order and
+    travels to the host model beside the following steps, into page-locked memory directly and
+    into pageable memory through a landing buffer.  A push leaves the replica alone, so the
+    replica must equal plain sequential steps, and the host model must be the replica as it was
+    at the last merge point: with merge_every = 4 and 10 steps the pushes follow steps 4 and 8
+    and the closing one step 10.  A second epoch pushes after every step, so that each push
+    meets the one before it still in flight."""
+    import paper_2004_08771_amd as hb
+    import torch
+    dims, act, loss = (40, 96, 48, 5), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE
+    n = 10 * 96
+    X, y, params = _data(n, dims, 21)
+    lr_pe = 0.05 / 96
+    ref_p, ref_H, ref_u, ref_steps, ref_loss = _replay(AdaptiveSchedule(n, [96], [96], [96]), 0, 0, dims, act, loss,
+                                                       params, X, y, lr_pe, host_model=np.zeros_like(params),
+                                                       merge_every=4, w=1.0)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 96)
+    m.set_params(params)
+    s = hb.Sched(n, [96], [96], [96])
+    H = torch.zeros(params.size, dtype=torch.float32)
+    if locked:
+        H = H.pin_memory()
+    u, steps, loss_sum = m.worker_run_epoch(s, 0, X, y, lr_pe, host_model=H, merge_every=4, merge_weight=1.0)
+    got = np.empty_like(params)
+    m.get_params(got)
+    assert (u, steps) == (ref_u, ref_steps) == (10.0, 10)
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+    assert _rel(H.numpy(), ref_H) <= TOL
+    assert np.array_equal(H.numpy(), got)           # the closing push carried the final replica, bit for bit
+    # every push of a longer run lands in order: push after every step, host model = final replica
+    s.new_epoch()
+    H.zero_()
+    m.worker_run_epoch(s, 0, X, y, lr_pe, host_model=H, merge_every=1, merge_weight=1.0, updates=u)
+    m.get_params(got)
+    m.destroy()
+    assert np.array_equal(H.numpy(), got)
+
+
 def test_worker_argument_errors():
     import paper_2004_08771_amd as hb
     dims = (8, 4, 3)
