@@ -143,6 +143,12 @@ float hb_batch_grad_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_
 float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B);
 
 /*
+ * The same forward pass without host synchronisation: the mean loss of the B rows is written
+ * to *d_loss (DEVICE pointer, one float, may be NULL) in stream order.  Dense input.
+ */
+int hb_batch_loss_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float *d_loss);
+
+/*
  * Replica <-> global model exchange (Section 6.2: the replica is a deep copy of the
  * global model, pushed back to it after the update; a stale replica's contribution can be
  * damped).  With H = host_model (HOST pointer, P floats, flat layout; pinned memory makes
@@ -257,7 +263,8 @@ int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *ho
  * loss is computed at the end of an epoch, by a forward pass over all examples in sub-batches
  * that fit the device): rows [0, n_examples) are sent in pieces of at most `batch` rows
  * (<= max_B) through the same double-buffered transfer as the worker loop, hb_batch_loss's
- * forward pass runs on each, and *mean_loss receives the mean over all n_examples (the piece
+ * forward pass runs on each (asynchronously: the piece means are collected on the device and
+ * fetched 256 at a time), and *mean_loss receives the mean over all n_examples (the piece
  * means weighted by their sizes, accumulated in double).  The replica is not modified.
  */
 int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples, int64_t batch,

@@ -29,6 +29,7 @@ SIGNATURES = {
     "hb_batch_grad": (_f32, [_vp, _vp, _vp, _i64, _vp]),
     "hb_batch_grad_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "hb_batch_loss": (_f32, [_vp, _vp, _vp, _i64]),
+    "hb_batch_loss_async": (_int, [_vp, _vp, _vp, _i64, _vp]),
     "hb_model_merge": (_int, [_vp, _vp, _f32]),
     "hb_last_error": (ctypes.c_char_p, []),
     "hb_version": (ctypes.c_char_p, []),
@@ -177,6 +178,9 @@ class Model:
     def batch_loss(self, dX, dy, B) -> float:
         v = lib().hb_batch_loss(self._h, _ptr(dX), _ptr(dy), int(B))
         return _check_float(v)
+
+    def batch_loss_async(self, dX, dy, B, d_loss=None):
+        _check(lib().hb_batch_loss_async(self._h, _ptr(dX), _ptr(dy), int(B), _ptr(d_loss)))
 
     def model_merge(self, host_model, weight):
         _check(lib().hb_model_merge(self._h, _ptr(host_model), float(weight)))

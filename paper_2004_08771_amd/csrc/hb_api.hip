@@ -1075,14 +1075,19 @@ float hb_batch_grad(hb_model *m, const void *dX, const int32_t *dy, int64_t B, f
     return out;
 }
 
-float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B)
+int hb_batch_loss_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float *d_loss)
 {
-    if (validate_batch_call(m, dX, dy, B, false) != HB_OK)
-        return std::numeric_limits<float>::quiet_NaN();
+    int rc = validate_batch_call(m, dX, dy, B, false);
+    if (rc != HB_OK) return rc;
     Input in;
     in.X = static_cast<const float *>(dX);
-    if ((m->dtype == HB_BF16_F32MASTER ? run_step_bf16(m, dX, dy, B, 0.f, MODE_LOSS, nullptr, nullptr)
-                                       : run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, nullptr)) != HB_OK)
+    return m->dtype == HB_BF16_F32MASTER ? run_step_bf16(m, dX, dy, B, 0.f, MODE_LOSS, nullptr, d_loss)
+                                         : run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, d_loss);
+}
+
+float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B)
+{
+    if (hb_batch_loss_async(m, dX, dy, B, nullptr) != HB_OK)
         return std::numeric_limits<float>::quiet_NaN();
     float out;
     if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();

@@ -423,7 +423,19 @@ extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_
         return HB_OK;
     };
     for (int i = 0; i < 2; ++i) WK_HIP(hipEventRecord(st.consumed[i], mi.stream));
+    // the pieces' mean losses are collected on the device and fetched a window at a time, so
+    // that the host never waits for a single piece
     double sum = 0.0;
+    int64_t rows_in_window[LOSS_WINDOW];
+    int in_window = 0;
+    auto flush = [&]() -> int {
+        if (in_window == 0) return HB_OK;
+        WK_HIP(hipMemcpyAsync(st.loss_host, st.loss, sizeof(float) * in_window, hipMemcpyDeviceToHost, mi.stream));
+        WK_HIP(hipStreamSynchronize(mi.stream));
+        for (int i = 0; i < in_window; ++i) sum += (double)st.loss_host[i] * (double)rows_in_window[i];
+        in_window = 0;
+        return HB_OK;
+    };
     int buf = 0;
     int64_t begin = 0, count = n_examples < batch ? n_examples : batch;
     rc = send(0, begin, count);
@@ -436,14 +448,20 @@ extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_
             if (rc != HB_OK) return rc;
         }
         WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
-        const float l = hb_batch_loss(m, st.x[buf], st.y[buf], count);  // synchronises the model's stream
-        if (l != l) return hb_last_error_code();
+        rc = hb_batch_loss_async(m, st.x[buf], st.y[buf], count, st.loss + in_window);
+        if (rc != HB_OK) return rc;
         WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
-        sum += (double)l * (double)count;
+        rows_in_window[in_window] = count;
+        if (++in_window == LOSS_WINDOW) {
+            rc = flush();
+            if (rc != HB_OK) return rc;
+        }
         begin = nbegin;
         count = ncount;
         buf ^= 1;
     }
+    rc = flush();
+    if (rc != HB_OK) return rc;
     WK_HIP(hipStreamSynchronize(st.copy));
     *mean_loss = sum / (double)n_examples;
     return HB_OK;

@@ -211,6 +211,14 @@ def test_async_step_matches_sync_and_writes_device_loss():
     pa, pb = np.empty(params.size, np.float32), np.empty(params.size, np.float32)
     a.get_params(pa)
     b.get_params(pb)
+    # forward-only loss, asynchronous and synchronous: same kernels, same value, replica untouched
+    d_eval = torch.zeros(1, dtype=torch.float32, device="cuda")
+    a.batch_loss_async(dX, dy, 500, d_eval)
+    torch.cuda.synchronize()
+    assert float(d_eval.cpu()[0]) == b.batch_loss(dX, dy, 500)
+    pa2 = np.empty(params.size, np.float32)
+    a.get_params(pa2)
+    np.testing.assert_array_equal(pa2, pa)
     a.destroy()
     b.destroy()
     np.testing.assert_array_equal(d_loss.cpu().numpy(), np.array(sync_losses, dtype=np.float32))
