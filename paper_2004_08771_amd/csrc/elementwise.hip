@@ -53,6 +53,69 @@ __global__ __launch_bounds__(LOSS_NT) void loss_kernel(LossArgs a)
                     else static_cast<float *>(a.delta)[row * a.ldd] = d;
                 }
             }
+        } else if (G == 64 && a.vec4 && a.K <= 1024) {
+            // wide rows (up to 1024 outputs) with 16-byte aligned rows: the row is read once,
+            // four floats per lane and pass, and stays in registers for all three sweeps
+            const int c = (a.loss == 1) ? (yi + 1) / 2 : yi;
+            float4 v[4];
+            float mx = -INFINITY, zc = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k0 = 4 * (g + 64 * i);
+                v[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (k0 < a.K) {
+                    const float4 t = *reinterpret_cast<const float4 *>(z + k0);  // k0 + 3 < ldz: rows are padded to 4
+                    v[i].x = t.x;
+                    if (k0 + 1 < a.K) v[i].y = t.y;
+                    if (k0 + 2 < a.K) v[i].z = t.z;
+                    if (k0 + 3 < a.K) v[i].w = t.w;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k0 = 4 * (g + 64 * i);
+                mx = fmaxf(mx, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+                if (c >= k0 && c < k0 + 4) zc = (c == k0) ? v[i].x : (c == k0 + 1) ? v[i].y : (c == k0 + 2) ? v[i].z : v[i].w;
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+                zc += __shfl_xor(zc, o, 64);
+            }
+            float se = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)  // exp(-inf) = 0 for the masked tail
+                se += (__expf(v[i].x - mx) + __expf(v[i].y - mx)) + (__expf(v[i].z - mx) + __expf(v[i].w - mx));
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+            const float lse = mx + __logf(se);
+            if (g == 0) row_loss = lse - zc;
+            if (a.delta) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k0 = 4 * (g + 64 * i);
+                    if (k0 >= a.K) continue;
+                    float d[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) d[j] = (__expf(d[j] - lse) - (k0 + j == c ? 1.f : 0.f)) * invB;
+                    if (k0 + 4 <= a.K) {
+                        if (a.delta_bf16) {
+                            uint2 pk;
+                            pk.x = (unsigned)f32_to_bf16_rne(d[0]) | ((unsigned)f32_to_bf16_rne(d[1]) << 16);
+                            pk.y = (unsigned)f32_to_bf16_rne(d[2]) | ((unsigned)f32_to_bf16_rne(d[3]) << 16);
+                            *reinterpret_cast<uint2 *>(static_cast<unsigned short *>(a.delta) + row * a.ldd + k0) = pk;
+                        } else {
+                            *reinterpret_cast<float4 *>(static_cast<float *>(a.delta) + row * a.ldd + k0) =
+                                make_float4(d[0], d[1], d[2], d[3]);
+                        }
+                    } else {
+                        for (int j = 0; j < 4 && k0 + j < a.K; ++j) {
+                            if (a.delta_bf16) static_cast<unsigned short *>(a.delta)[row * a.ldd + k0 + j] = f32_to_bf16_rne(d[j]);
+                            else static_cast<float *>(a.delta)[row * a.ldd + k0 + j] = d[j];
+                        }
+                    }
+                }
+            }
         } else {
             const int c = (a.loss == 1) ? (yi + 1) / 2 : yi;
             float mx = -INFINITY, zc = 0.f;
@@ -239,8 +302,12 @@ int loss_grid_blocks(long long B, int K)
     return (int)((B + rows_per_block - 1) / rows_per_block);
 }
 
-hipError_t launch_loss(const LossArgs &a, hipStream_t stream, const LaunchEvents &ev)
+hipError_t launch_loss(const LossArgs &args, hipStream_t stream, const LaunchEvents &ev)
 {
+    LossArgs a = args;
+    a.vec4 = (a.ldz % 4 == 0) && ((reinterpret_cast<size_t>(a.Z) & 15) == 0) &&
+             (a.delta == nullptr ||
+              ((a.ldd % 4 == 0) && ((reinterpret_cast<size_t>(a.delta) & (a.delta_bf16 ? 7 : 15)) == 0)));
     const dim3 grid((unsigned)loss_grid_blocks(a.B, a.K)), block(LOSS_NT);
     switch (loss_group(a.K)) {
     case 1: return launch_kernel(loss_kernel<1>, grid, block, stream, ev, a);

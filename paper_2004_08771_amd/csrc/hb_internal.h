@@ -134,6 +134,7 @@ struct LossArgs {
     int ldd;
     int delta_bf16;
     float *block_partials;   // one loss sum per block (>= loss_grid_blocks entries)
+    int vec4;                // set by launch_loss: rows of Z and delta allow 16-byte / 8-byte accesses
 };
 // The mean loss is finished by the next consumer on the stream: sum of n block partials / B.
 struct LossFinalize {
