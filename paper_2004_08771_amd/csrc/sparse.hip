@@ -103,7 +103,18 @@ __global__ __launch_bounds__(CSC_NT) void csc_hist_kernel(const int32_t *__restr
     const long long r1 = min(B, r0 + rows_per_block);
     if (r0 < r1) {
         const int beg = row_ptr[r0], end = row_ptr[r1];
-        for (int p = beg + threadIdx.x; p < end; p += CSC_NT) atomicAdd(&s_hist[col_idx[p]], 1);
+        // eight column indices are requested before the first LDS atomic needs one
+        for (int p0 = beg + threadIdx.x; p0 < end; p0 += 8 * CSC_NT) {
+            int c[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * CSC_NT;
+                c[u] = (p < end) ? col_idx[p] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (c[u] >= 0) atomicAdd(&s_hist[c[u]], 1);
+        }
     }
     __syncthreads();
     int32_t *out = hist + (size_t)blockIdx.x * d0;
