@@ -239,11 +239,15 @@ int64_t hb_sched_remaining(const hb_sched *s);                  /* examples left
  * lr = lr_per_example * b (learning rate proportional to the batch size, Section 6.2).
  * Every merge_every steps (and once at the end if any step is unmerged) the replica is merged
  * with host_model as hb_model_merge(m, host_model, merge_weight) does; merge_every = 0 or
- * host_model = NULL: never.  merge_weight = 1 (the push of Section 6.2) does not wait for the
- * device: the replica is snapshot in stream order and travels to host_model on a third stream
- * while the next steps run (directly if host_model is page-locked, else through a page-locked
- * buffer and a host copy); every push has landed when the call returns.  While the call runs,
- * host_model may be written at any time after a merge point.
+ * host_model = NULL: never.  No merge waits for the device.  merge_weight = 1 (the push of
+ * Section 6.2): the replica is snapshot in stream order and travels to host_model on a third
+ * stream while the next steps run (directly if host_model is page-locked, else through a
+ * page-locked buffer and a host copy).  merge_weight < 1: host_model is first copied to the
+ * device on that stream (read at the merge point of the host's program order, which runs ahead
+ * of the device by at most one exchange), blended with the replica in stream order, and the
+ * blend travels back like a push (not for weight 0).  Every transfer has landed when the call
+ * returns.  While the call runs, host_model may be read and written at any time; what other
+ * workers write to it between the read and the landing of the blend is overwritten.
  *   host_X  n_examples x d_0 row-major in HOST memory (fp32, or bfloat16 in the bf16 mode),
  *           page-locked memory makes the copies asynchronous;  host_y  n_examples int32.
  *   *updates (in/out, may be NULL -> starts at 0): the worker's update count u^E, carried

@@ -734,6 +734,16 @@ bool model_info(const hb_model *m, ModelInfo *out)
 
 const float *model_params_device(const hb_model *m) { return m->d_params; }
 
+int model_blend_with_device(hb_model *m, float *d_global, float w)
+{
+    int rc = sync_flat_from_w1t(m);
+    if (rc != HB_OK) return rc;
+    HB_HIP(launch_merge(m->d_params, d_global, m->P, w, m->stream));
+    rc = sync_w1t_from_flat(m);
+    if (rc == HB_OK) rc = refresh_shadows(m);
+    return rc;
+}
+
 void **model_worker_slot(hb_model *m, void (*deleter)(void *))
 {
     m->worker_state_free = deleter;

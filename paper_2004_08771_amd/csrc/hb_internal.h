@@ -267,6 +267,9 @@ struct ModelInfo {
 bool model_info(const hb_model *m, ModelInfo *out);
 // the replica's flat fp32 parameters on the device (dense models: always current)
 const float *model_params_device(const hb_model *m);
+// M = (1 - w) G + w D in stream order, written to the replica D AND to d_global (P floats on
+// the device), followed by whatever keeps the replica's derived copies current (bf16 shadows)
+int model_blend_with_device(hb_model *m, float *d_global, float w);
 // slot in the handle where the worker loop keeps its staging buffers between calls; the
 // deleter runs in hb_model_destroy
 void **model_worker_slot(hb_model *m, void (*deleter)(void *));

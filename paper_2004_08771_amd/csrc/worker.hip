@@ -9,8 +9,9 @@
 // (a buffer is refilled only after the step that read it has finished).  A push of the
 // replica (merge weight 1) is asynchronous as in Section 6.2: a device-to-device snapshot in
 // stream order, then device -> host on a third stream beside the following steps, straight
-// into the host model when that is page-locked.  Everything stays at the default stream
-// priority.
+// into the host model when that is page-locked; a two-way exchange (weight < 1) first brings
+// the global model to the device on that stream and blends in stream order.  Everything stays
+// at the default stream priority.
 #include "hb_internal.h"
 
 #include <cmath>
@@ -155,6 +156,7 @@ struct Staging {
     hipStream_t push = nullptr;
     hipEvent_t snap_taken = nullptr;   // the snapshot is complete (model's stream)
     hipEvent_t snap_landed = nullptr;  // the snapshot has reached host memory (push stream)
+    hipEvent_t glob_here = nullptr;    // the global model has reached the device (push stream)
     ~Staging()
     {
         if (push) (void)hipStreamSynchronize(push);
@@ -162,6 +164,7 @@ struct Staging {
         if (snap_host) (void)hipHostFree(snap_host);
         if (snap_taken) (void)hipEventDestroy(snap_taken);
         if (snap_landed) (void)hipEventDestroy(snap_landed);
+        if (glob_here) (void)hipEventDestroy(glob_here);
         if (push) (void)hipStreamDestroy(push);
         if (copy) (void)hipStreamSynchronize(copy);
         for (int i = 0; i < 2; ++i) {
@@ -237,6 +240,7 @@ int acquire_push(Staging &st, long long P)
     if (!st.push) WK_HIP(hipStreamCreateWithFlags(&st.push, hipStreamNonBlocking));  // default priority
     if (!st.snap_taken) WK_HIP(hipEventCreateWithFlags(&st.snap_taken, hipEventDisableTiming));
     if (!st.snap_landed) WK_HIP(hipEventCreateWithFlags(&st.snap_landed, hipEventDisableTiming));
+    if (!st.glob_here) WK_HIP(hipEventCreateWithFlags(&st.glob_here, hipEventDisableTiming));
     st.snap_elems = P;
     return HB_OK;
 }
@@ -284,8 +288,8 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
         return hb::set_error(HB_ERR_INVALID, "merge_every must be >= 0 and merge_weight in [0, 1]");
     const bool merging = merge_every > 0 && host_model != nullptr;
     // weight 1 is the paper's push (global <- replica, Section 6.2): it leaves the replica as it
-    // is, so it can run beside the following steps; any other weight changes the replica and
-    // is done in stream order by hb_model_merge
+    // is; any other weight also brings the global model to the device and blends there.  Either
+    // way the transfers run on a third stream beside the steps.
     const bool pushing = merging && merge_weight == 1.f;
 
     const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
@@ -298,7 +302,7 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     }
     Staging &st = *sp;
     bool host_model_locked = false;
-    if (pushing) {
+    if (merging) {
         const int rc_p = acquire_push(st, mi.P);
         if (rc_p != HB_OK) return rc_p;
         hipPointerAttribute_t attr;
@@ -320,6 +324,35 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
                               st.push));
         WK_HIP(hipEventRecord(st.snap_landed, st.push));
         push.in_flight = true;
+        return HB_OK;
+    };
+
+    // Two-way exchange (0 <= weight < 1): the global model travels to the device while the
+    // current step still runs, the blend M = (1 - w) global + w replica follows that step in
+    // stream order (both the replica and the staging buffer then hold M), and M travels back
+    // like a push.  The global model is read when this is called, i.e. up to one exchange
+    // earlier than a synchronous hb_model_merge would read it: updates other workers make in
+    // between are overwritten by M, as Section 6.2 accepts for concurrent workers.
+    auto exchange_async = [&]() -> int {
+        int rc_f = push.finish();
+        if (rc_f != HB_OK) return rc_f;
+        WK_HIP(hipMemcpyAsync(st.snap, host_model, push.bytes, hipMemcpyHostToDevice, st.push));
+        WK_HIP(hipEventRecord(st.glob_here, st.push));
+        WK_HIP(hipStreamWaitEvent(mi.stream, st.glob_here, 0));
+        rc_f = hb::model_blend_with_device(m, st.snap, merge_weight);
+        if (rc_f != HB_OK) return rc_f;
+        if (merge_weight > 0.f) {  // weight 0 is the deep copy alone: the global model is unchanged
+            WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
+            WK_HIP(hipStreamWaitEvent(st.push, st.snap_taken, 0));
+            WK_HIP(hipMemcpyAsync(push.direct ? host_model : st.snap_host, st.snap, push.bytes,
+                                  hipMemcpyDeviceToHost, st.push));
+            WK_HIP(hipEventRecord(st.snap_landed, st.push));
+            push.in_flight = true;
+        } else {
+            // the staging buffer is free once the blend has read it: the next exchange waits for that
+            WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
+            WK_HIP(hipStreamWaitEvent(st.push, st.snap_taken, 0));
+        }
         return HB_OK;
     };
 
@@ -373,7 +406,7 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
             if (rc != HB_OK) return rc;
         }
         if (merging && since_merge >= merge_every) {
-            rc = pushing ? push_async() : hb_model_merge(m, host_model, merge_weight);
+            rc = pushing ? push_async() : exchange_async();
             if (rc != HB_OK) return rc;
             since_merge = 0;
         }
@@ -383,7 +416,7 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     rc = flush_losses();
     if (rc != HB_OK) return rc;
     if (merging && since_merge > 0) {
-        rc = pushing ? push_async() : hb_model_merge(m, host_model, merge_weight);
+        rc = pushing ? push_async() : exchange_async();
         if (rc != HB_OK) return rc;
     }
     rc = push.finish();
