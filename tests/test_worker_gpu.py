@@ -159,6 +159,33 @@ def test_asynchronous_push_of_the_replica(locked):
     assert np.array_equal(H.numpy(), got)
 
 
+def test_deep_copy_of_the_global_model_every_other_step():
+    """merge_weight = 0 is the deep copy of the ExecuteWork handler (Section 6.2): the replica is
+    overwritten by the global model, which stays as it is.  Every second step throws the
+    replica's progress away, so the epoch ends on the global model itself when the number of
+    steps is even, and one step away from it when it is odd."""
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (30, 40, 4), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    X, y, params = _data(7 * 50, dims, 33)
+    host0 = (params * 0.5).astype(np.float32)
+    lr_pe = 0.1 / 50
+    ref_p, ref_H, ref_u, ref_steps, ref_loss = _replay(AdaptiveSchedule(350, [50], [50], [50]), 0, 0, dims, act, loss,
+                                                       params, X, y, lr_pe, host_model=host0, merge_every=2, w=0.0)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 50)
+    m.set_params(params)
+    s = hb.Sched(350, [50], [50], [50])
+    H = host0.copy()
+    u, steps, loss_sum = m.worker_run_epoch(s, 0, X, y, lr_pe, host_model=H, merge_every=2, merge_weight=0.0)
+    got = np.empty_like(params)
+    m.get_params(got)
+    m.destroy()
+    assert steps == ref_steps == 7
+    assert np.array_equal(H, host0)                 # the global model is only read
+    assert np.array_equal(got, host0)               # 7 steps: the closing merge copies it once more
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+
+
 def test_worker_argument_errors():
     import paper_2004_08771_amd as hb
     dims = (8, 4, 3)
