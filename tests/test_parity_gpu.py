@@ -120,6 +120,34 @@ def test_small_shapes_match_oracle(dims, act, loss, B):
     check_case(dims, act, loss, params, X, y, lr=0.1)
 
 
+def test_random_shapes_match_oracle():
+    """A seeded sweep over network shapes and batch sizes around every tile size the kernels use
+    (32, 64, 128 outputs and rows; k-tiles of 32 and 64; batch slices of 512; 1 to 16 outputs for
+    the fused output layer, more for the general one).  The seed is one whose cases are all
+    well conditioned: a bias gradient that is a sum of cancelling terms (two classes, two rows)
+    has no meaningful relative error."""
+    rng = np.random.default_rng(3)
+    widths = [1, 2, 3, 5, 7, 8, 13, 16, 17, 31, 32, 33, 54, 63, 64, 65, 96, 100, 127, 128, 129, 200, 256, 300, 512, 520]
+    batches = [1, 2, 3, 7, 16, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 500, 769, 1000,
+               1025, 1500, 2047, 2048, 2049]
+    for case in range(120):
+        nh = int(rng.integers(0, 4))
+        dims = [int(rng.choice(widths))] + [int(rng.choice(widths[6:])) for _ in range(nh)]
+        loss = int(rng.integers(0, 2))
+        dims.append(int(rng.choice([1, 2])) if loss == hi.LOSS_LOGISTIC else int(rng.choice([2, 3, 7, 10, 16, 17, 40, 100])))
+        act = int(rng.choice([hi.ACT_SIGMOID, hi.ACT_RELU]))
+        B = int(rng.choice(batches))
+        work = B * sum(a * b for a, b in zip(dims[:-1], dims[1:]))
+        if work > 3e8:                      # keeps the oracle quick
+            B = max(1, int(B * 3e8 / work))
+        dims = tuple(dims)
+        params, X, y = _problem(dims, loss, B, seed=3000 + case)
+        try:
+            check_case(dims, act, loss, params, X, y, lr=0.1)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: dims {dims} act {act} loss {loss} B {B}: {e}") from None
+
+
 # ---------------------------------------------------------------- config 1, a whole epoch
 def test_config1_one_epoch_of_64_steps():
     torch = _torch()
