@@ -152,6 +152,18 @@ def main():
     value = args.steps * B / elapsed
     flops = step_flops(cfg.dims, B, mean_nnz)
 
+    # ---- the synchronous entry point (hb_batch_step: the host waits for every step's loss),
+    # reported beside the headline figure; dense configs only
+    sync_ms_per_step = None
+    if not cfg.sparse:
+        n_sync = max(1, min(args.steps, 50))
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(n_sync):
+            j = (args.warmup + args.steps + i) % n_batches
+            model.batch_step(x_ptr[j], y_ptr[j], B, lr)
+        sync_ms_per_step = 1e3 * (time.perf_counter() - t1) / n_sync
+
     # ---- second pass over the same steps with per-dispatch events -> per-kernel times
     roofline, kernels = None, []
     if not args.no_profile:
@@ -237,8 +249,13 @@ def main():
         else:
             n_steps, sample = 1, int(max(probe_rows, want))
         dt = sum(oracle_step(sample) for _ in range(n_steps))
+        # the same oracle on one core, on a small sample (its rate does not depend on B)
+        oracle.set_threads(1)
+        one_rows = min(B, 128)
+        one_core = one_rows / oracle_step(one_rows)
+        oracle.set_threads(cores)
         cpu_baseline = {"value": round(n_steps * sample / dt, 2), "unit": "examples/s", "cores": cores,
-                        "kind": "oracle",
+                        "kind": "oracle", "value_1_core": round(one_core, 2),
                         "sample": f"{n_steps} fp64 oracle step(s) (forward, backward, update) on the first "
                                   f"{sample} rows of the same dataset, {dt:.1f} s"}
 
@@ -260,6 +277,7 @@ def main():
         "step_tflops": round(flops / (elapsed / args.steps) / 1e12, 3),
         "step_frac_of_mfma_peak": round(flops / (elapsed / args.steps) / 1e12 / PEAK_TFLOPS[dtype_name], 4),
         "last_loss": last_loss,
+        "sync_ms_per_step": None if sync_ms_per_step is None else round(sync_ms_per_step, 5),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels": kernels,
