@@ -13,13 +13,11 @@ namespace {
 
 constexpr int LOSS_NT = 256;
 
+// round to nearest even through gfx950's v_cvt_pk_bf16_f32 (bit-identical to the integer
+// formula for every non-NaN input; NaN stays NaN)
 __device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
 {
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)(u >> 16);  // inf / nan
-    const unsigned int lsb = (u >> 16) & 1u;
-    u += 0x7fffu + lsb;
-    return (unsigned short)(u >> 16);
+    return __builtin_bit_cast(unsigned short, (__bf16)f);
 }
 
 // G lanes cooperate on one row (G = power of two <= 64).  Softmax cross-entropy:
