@@ -20,7 +20,9 @@
  *   y is a DEVICE pointer to B int32 labels: class index in [0, d_L) for
  *   HB_LOSS_SOFTMAX_CE; -1 / +1 for HB_LOSS_LOGISTIC (d_L = 1: loss on the margin
  *   y * z; d_L = 2: two-way softmax with class (y + 1) / 2).  Labels are not range-checked;
- *   an out-of-range label cannot cause an out-of-bounds access, only a wrong loss.
+ *   an out-of-range label cannot cause an out-of-bounds access, only a wrong loss.  With
+ *   HB_CHECK_LABELS=1 in the environment every batch call first counts them on the device
+ *   (one more pass over y and a synchronisation) and fails with HB_ERR_INVALID if there are any.
  *   The batch gradient is the MEAN over the batch of the per-example gradients; the
  *   loss a step returns is the mean batch loss at the weights before the update.
  *

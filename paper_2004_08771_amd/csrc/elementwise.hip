@@ -347,6 +347,29 @@ hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t st
     return hipGetLastError();
 }
 
+// Debug aid: number of labels outside their domain (class index in [0, K) for softmax
+// cross-entropy; +1 / -1 for the logistic loss), added to *bad.
+__global__ __launch_bounds__(256) void label_check_kernel(const int32_t *__restrict__ y, long long B, int K,
+                                                          int loss, unsigned int *bad)
+{
+    const long long step = (long long)gridDim.x * 256;
+    unsigned int n = 0;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < B; i += step) {
+        const int v = y[i];
+        n += (loss == 1) ? (v != 1 && v != -1) : (v < 0 || v >= K);
+    }
+    if (n) atomicAdd(bad, n);
+}
+
+hipError_t launch_label_check(const int32_t *y, long long B, int K, int loss, unsigned int *bad, hipStream_t stream)
+{
+    long long b = (B + 255) / 256;
+    if (b > 1024) b = 1024;
+    if (b < 1) b = 1;
+    label_check_kernel<<<(unsigned)b, 256, 0, stream>>>(y, B, K, loss, bad);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_u32(unsigned int *p, long long n, unsigned int v, hipStream_t stream)
 {
     long long b = (n + 255) / 256;

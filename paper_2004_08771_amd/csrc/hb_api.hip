@@ -689,6 +689,20 @@ int validate_batch_call(hb_model *m, const void *a, const int32_t *dy, int64_t B
     if (B < 1 || B > m->max_B)
         return fail(HB_ERR_INVALID, "B = %lld is outside [1, max_B = %lld]", (long long)B,
                     (long long)m->max_B);
+    // HB_CHECK_LABELS=1 (debug aid, costs a pass over y and a synchronisation per call): labels
+    // outside their domain are an error instead of a silently wrong loss
+    static const bool check_labels = getenv("HB_CHECK_LABELS") && atoi(getenv("HB_CHECK_LABELS")) != 0;
+    if (check_labels) {
+        unsigned int *d_bad = reinterpret_cast<unsigned int *>(m->d_loss + 3);
+        unsigned int bad = 0;
+        HB_HIP(launch_fill_u32(d_bad, 1, 0u, m->stream));
+        HB_HIP(launch_label_check(dy, B, m->dims[m->L], m->loss, d_bad, m->stream));
+        HB_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, m->stream));
+        HB_HIP(hipStreamSynchronize(m->stream));
+        if (bad)
+            return fail(HB_ERR_INVALID, "%u of the %lld labels are outside their domain (%s)", bad, (long long)B,
+                        m->loss == HB_LOSS_LOGISTIC ? "+1 / -1" : "class index in [0, d_L)");
+    }
     return HB_OK;
 }
 

@@ -200,6 +200,8 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t stream, const LaunchEv
 // D[i] = H[i] = (1-w) H[i] + w D[i]   (H is a device staging copy of the host model)
 hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t stream);
 hipError_t launch_fill_u32(unsigned int *p, long long n, unsigned int v, hipStream_t stream);
+// adds the number of out-of-domain labels to *bad (device counter); debug aid
+hipError_t launch_label_check(const int32_t *y, long long B, int K, int loss, unsigned int *bad, hipStream_t stream);
 
 
 // ---------------------------------------------------------------- CSR first layer

@@ -337,6 +337,45 @@ def test_gpu_argument_errors():
 
 
 # ---------------------------------------------------------------- CSR first layer
+def test_label_check_is_opt_in_and_catches_bad_labels():
+    """HB_CHECK_LABELS=1 is read when the library sees its first batch call, so the check runs
+    in a child process: good labels pass, a class index of d_L and a logistic label of 0 fail
+    with HB_ERR_INVALID, and without the variable the same calls go through."""
+    import os
+    import subprocess
+    import sys
+    code = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+import paper_2004_08771_amd as hb
+X = torch.zeros(8, 5, device="cuda")
+m = hb.Model((5, 4, 3), hb.HB_ACT_SIGMOID, hb.HB_LOSS_SOFTMAX_CE).configure(hb.HB_F32, 8)
+good = torch.tensor([0, 1, 2, 0, 1, 2, 0, 1], dtype=torch.int32, device="cuda")
+bad = good.clone(); bad[5] = 3
+out = []
+out.append(bool(np.isfinite(m.batch_loss(X, good, 8))))
+try:
+    m.batch_step(X, bad, 8, 0.1); out.append("no error")
+except hb.HbError as e:
+    out.append(e.code == hb.HB_ERR_INVALID)
+lg = hb.Model((5, 1), hb.HB_ACT_SIGMOID, hb.HB_LOSS_LOGISTIC).configure(hb.HB_F32, 8)
+pm = torch.tensor([1, -1, 1, -1, 1, -1, 1, -1], dtype=torch.int32, device="cuda")
+out.append(bool(np.isfinite(lg.batch_loss(X, pm, 8))))
+pm[0] = 0
+try:
+    lg.batch_loss(X, pm, 8); out.append("no error")
+except hb.HbError as e:
+    out.append(e.code == hb.HB_ERR_INVALID)
+print("RESULT", out)
+""" % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, HB_CHECK_LABELS="1")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert "RESULT [True, True, True, True]" in r.stdout, r.stdout + r.stderr
+    env.pop("HB_CHECK_LABELS")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert "RESULT [True, 'no error', True, 'no error']" in r.stdout, r.stdout + r.stderr
+
+
 def _csr_problem(dims, n_rows, seed, mean_nnz, max_nnz=256, bias_scale=0.2):
     rng = np.random.default_rng(seed)
     rp, ci, va = hi.zipf_csr(n_rows, dims[0], rng, mean_nnz=mean_nnz, max_nnz=max_nnz)
