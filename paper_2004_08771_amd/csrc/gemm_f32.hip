@@ -358,6 +358,32 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
     // ---- epilogue.  acc[i][j][v] is C(row, col) with
     //      row = 8 (v / 4) + 4 h + (v % 4), col = r   inside its 32 x 32 block.
     float *__restrict__ C = static_cast<float *>(a.C) + (size_t)split * a.c_split_stride;
+    if (KIND == GEMM_DA && a_in && b_in) {
+        // Interior tile of the backward-data product: the 16 activation values a lane needs for
+        // the derivative are requested together, without guards.  Behind a bounds check per
+        // element each load waited for the one before it (16 round trips to memory per block).
+        const float *__restrict__ aux = static_cast<const float *>(a.aux);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * WN + j * 32 + r;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int mb = m0 + wm * WM + i * 32 + 4 * h;
+                float o[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[v] = aux[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldaux + n];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float x = acc[i][j][0][v];
+                    if (CHAINS == 2) x += acc[i][j][CHAINS - 1][v];
+                    if (a.act == ACT_SIGMOID) x *= o[v] * (1.f - o[v]);
+                    else if (a.act == ACT_RELU) x = (o[v] > 0.f) ? x : 0.f;
+                    C[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldc + n] = x;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + wn * WN + j * 32 + r;
@@ -541,6 +567,12 @@ __device__ __forceinline__ void gemm_f32_small_tile(const GemmArgs &a, float *sm
     const bool n_ok = n < a.N;
     float bias = 0.f;
     if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+    float o4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (KIND == GEMM_DA && a_in && b_in) {  // the four activation values of the lane, requested together
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            o4[p] = static_cast<const float *>(a.aux)[(size_t)(m0 + 8 * wave + 2 * p + h) * a.ldaux + n];
+    }
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int row = 8 * wave + 2 * p + h;
@@ -553,7 +585,7 @@ __device__ __forceinline__ void gemm_f32_small_tile(const GemmArgs &a, float *sm
                 if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
                 else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
             } else if (KIND == GEMM_DA) {
-                const float o = static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
+                const float o = (a_in && b_in) ? o4[p] : static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
                 if (a.act == ACT_SIGMOID) x *= o * (1.f - o);
                 else if (a.act == ACT_RELU) x = (o > 0.f) ? x : 0.f;
             }
