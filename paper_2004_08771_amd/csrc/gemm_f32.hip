@@ -209,6 +209,14 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
     float colsum = 0.f;  // DW only: column sums of the A tile (bias gradient)
     const bool do_colsum = (KIND == GEMM_DW) && a.colsum != nullptr && tile_n == 0;
 
+    // forward: the lane's bias values are requested now, not after the main loop
+    float bias_pre[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + r;
+        bias_pre[j] = (KIND == GEMM_FWD && a.bias != nullptr && n < a.N) ? a.bias[n] : 0.f;
+    }
+
     // Software pipeline, three levels deep:
     //   global -> registers : the loads of tile kt+2 are issued at the top of iteration kt
     //   registers -> LDS    : just before that, tile kt+1 (loaded during iteration kt-1) is
@@ -358,29 +366,41 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
     // ---- epilogue.  acc[i][j][v] is C(row, col) with
     //      row = 8 (v / 4) + 4 h + (v % 4), col = r   inside its 32 x 32 block.
     float *__restrict__ C = static_cast<float *>(a.C) + (size_t)split * a.c_split_stride;
-    if (KIND == GEMM_DA && a_in && b_in) {
-        // Interior tile of the backward-data product: the 16 activation values a lane needs for
-        // the derivative are requested together, without guards.  Behind a bounds check per
-        // element each load waited for the one before it (16 round trips to memory per block).
+    if (a_in && b_in) {
+        // Interior tile: no guards.  The backward-data product requests the 16 activation
+        // values a lane needs for the derivative together; behind a bounds check per element
+        // each load waited for the one before it (16 round trips to memory per block).
         const float *__restrict__ aux = static_cast<const float *>(a.aux);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int n = n0 + wn * WN + j * 32 + r;
+            const float bias = bias_pre[j];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int mb = m0 + wm * WM + i * 32 + 4 * h;
                 float o[16];
+                if (KIND == GEMM_DA) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[v] = aux[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldaux + n];
+                    for (int v = 0; v < 16; ++v) o[v] = aux[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldaux + n];
+                }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     float x = acc[i][j][0][v];
                     if (CHAINS == 2) x += acc[i][j][CHAINS - 1][v];
-                    if (a.act == ACT_SIGMOID) x *= o[v] * (1.f - o[v]);
-                    else if (a.act == ACT_RELU) x = (o[v] > 0.f) ? x : 0.f;
+                    if (KIND == GEMM_FWD) {
+                        x += bias;
+                        if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
+                        else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
+                    } else if (KIND == GEMM_DA) {
+                        if (a.act == ACT_SIGMOID) x *= o[v] * (1.f - o[v]);
+                        else if (a.act == ACT_RELU) x = (o[v] > 0.f) ? x : 0.f;
+                    }
                     C[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldc + n] = x;
                 }
             }
+        }
+        if (KIND == GEMM_DW) {
+            if (do_colsum && tid < BM) a.colsum[(size_t)split * a.M + m0 + tid] = colsum;
         }
         return;
     }
@@ -388,8 +408,7 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + wn * WN + j * 32 + r;
         const bool n_ok = n < a.N;
-        float bias = 0.f;
-        if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+        const float bias = bias_pre[j];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
