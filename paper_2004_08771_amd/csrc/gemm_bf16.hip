@@ -421,15 +421,23 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            // weight gradient: the 16 fp32 master weights of this 32 x 32 block that the lane
+            // updates are requested together.  Fetched four at a time between the stores of
+            // the previous four (which the compiler must assume to alias), every group of four
+            // was a round trip to memory of its own: 64 per lane and tile.
+            float wm[4][4];
+            if (KIND == GEMM_DW) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float w[4];  // weight gradient: the fp32 master weights of the four rows
-                if (KIND == GEMM_DW) {
+                for (int q = 0; q < 4; ++q)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        w[e] = *reinterpret_cast<const float *>(
+                        wm[q][e] = *reinterpret_cast<const float *>(
                             cf0 + ((size_t)(mw + i * 32 + 8 * q + e) * a.ldc + nb) * 4 + lo_cf);
-                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float (&w)[4] = wm[q];
                 float x[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
