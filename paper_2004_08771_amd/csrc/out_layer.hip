@@ -164,9 +164,17 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
     }
     if (!a.backward) return;
 
+    // P4 and P5 only read LDS and are independent.  When the weight-gradient partial needs no
+    // more than a quarter of the block (d <= 512), its wavefronts run it while the others do
+    // the backward-data part: side by side instead of one after the other.
+    const int w_wave_threads = ((d4 + 63) / 64) * 64;            // whole wavefronts that cover d4
+    const bool split = a.Dprev != nullptr && w_wave_threads * 4 <= OL_NT;
+    const int p4_first = split ? w_wave_threads : 0;             // first thread of the P4 group
+    const int p4_threads = OL_NT - p4_first;
+
     // ---- P4: D_{L-1}[i][k] = (sum_j D_L[i][j] W[j][k]) * f'(A[i][k]), 16-byte stores along k
-    if (a.Dprev) {
-        for (int idx = tid; idx < R * d4; idx += OL_NT) {
+    if (a.Dprev && tid >= p4_first) {
+        for (int idx = tid - p4_first; idx < R * d4; idx += p4_threads) {
             const int i = idx / d4, c4 = idx - i * d4;
             if (r0 + i >= a.B) continue;
             float4 s = {0.f, 0.f, 0.f, 0.f};
@@ -196,6 +204,7 @@ __global__ __launch_bounds__(OL_NT) void out_layer_kernel(OutLayerArgs a)
     // ---- P5: dW_L partial of this block, dW[j][k] = sum_i D_L[i][j] A[i][k]: one thread per
     // float4 of k, all R rows (R is small: the grid is sized to one block per CU)
     float *out = a.dW_partial + (size_t)blockIdx.x * K * d;
+    if (split && tid >= p4_first) return;   // the backward-data wavefronts are done
     for (int c4 = tid; c4 < d4; c4 += OL_NT) {
         float4 g[OL_KMAX];
 #pragma unroll
