@@ -19,6 +19,8 @@ namespace {
 constexpr int SP_NT = 128;    // threads per row / per chunk: one float4 each for d_1 = 512
 constexpr int CHUNK = 128;    // non-zeros per gradient chunk
 
+constexpr int SPMM_CAP = 512;  // entries of a row staged in LDS at a time (forward product)
+
 __device__ __forceinline__ float act_apply(float z, int act)
 {
     if (act == ACT_SIGMOID) return 1.0f / (1.0f + __expf(-z));
@@ -32,7 +34,57 @@ __global__ __launch_bounds__(SP_NT) void spmm_fwd_kernel(SpmmArgs a)
     const long long i = blockIdx.x;
     const int beg = a.row_ptr[i], end = a.row_ptr[i + 1];
     float *__restrict__ out = a.out + i * a.ldo;
-    if (a.vec) {
+    const int n4v = a.d1 >> 2;
+    if (a.vec && n4v <= SP_NT) {
+        // Outputs of up to 4 x SP_NT floats (one float4 per thread): the row's column indices
+        // and values are brought into LDS once, coalesced, SPMM_CAP entries at a time, so that
+        // the gathers do not each wait for a scalar load of their index first, and sixteen
+        // weight-row gathers are in flight per thread.
+        __shared__ int s_col[SPMM_CAP];
+        __shared__ float s_val[SPMM_CAP];
+        const int q = threadIdx.x;
+        const bool live = q < n4v;
+        float4 acc = live ? reinterpret_cast<const float4 *>(a.bias)[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int base = beg; base < end; base += SPMM_CAP) {
+            const int n = min(SPMM_CAP, end - base);
+            if (base != beg) __syncthreads();  // the previous chunk has been consumed
+            for (int t = threadIdx.x; t < n; t += SP_NT) {
+                s_col[t] = a.col_idx[base + t];
+                s_val[t] = a.vals[base + t];
+            }
+            __syncthreads();
+            if (live) {
+                int p = 0;
+                for (; p + 16 <= n; p += 16) {
+                    float4 w[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        w[u] = reinterpret_cast<const float4 *>(a.W1t + (size_t)s_col[p + u] * a.ldw)[q];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {  // added in index order
+                        const float v = s_val[p + u];
+                        acc.x += v * w[u].x; acc.y += v * w[u].y; acc.z += v * w[u].z; acc.w += v * w[u].w;
+                    }
+                }
+                if (p < n) {  // the tail: indices past the end are clamped, their values zero
+                    float4 w[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        w[u] = reinterpret_cast<const float4 *>(a.W1t + (size_t)s_col[min(p + u, n - 1)] * a.ldw)[q];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const float v = (p + u < n) ? s_val[p + u] : 0.f;
+                        acc.x += v * w[u].x; acc.y += v * w[u].y; acc.z += v * w[u].z; acc.w += v * w[u].w;
+                    }
+                }
+            }
+        }
+        if (live) {
+            acc.x = act_apply(acc.x, a.act); acc.y = act_apply(acc.y, a.act);
+            acc.z = act_apply(acc.z, a.act); acc.w = act_apply(acc.w, a.act);
+            reinterpret_cast<float4 *>(out)[q] = acc;
+        }
+    } else if (a.vec) {
         const int n4 = a.d1 >> 2;
         for (int q = threadIdx.x; q < n4; q += SP_NT) {
             float4 acc = reinterpret_cast<const float4 *>(a.bias)[q];
