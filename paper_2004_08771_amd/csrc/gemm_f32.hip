@@ -717,7 +717,7 @@ SplitPlan plan_splits(int tiles, int K, int max_splits, int wgs = 0)
 // (0 switches the small kernels off).
 int small_tiles_max()
 {
-    static const int v = env_int("HB_GEMM_SMALL_TILES", 256);
+    static const int v = env_int("HB_GEMM_SMALL_TILES", 160);  // measured crossover: B = 1280 for 512-wide layers
     return v;
 }
 int small_k_max()
@@ -735,11 +735,10 @@ bool small_dw(int K)
     static const int forced = env_int("HB_GEMM_TILE", 0);
     return forced == 0 && K >= 64 && K < small_k_max();
 }
-// K-slices of the small weight-gradient kernel: one up to K = 768, then about 512 long
-// (multiples of its k-tile)
+// K-slices of the small weight-gradient kernel: at most 512 long (multiples of its k-tile)
 SplitPlan plan_small_splits(int K, int max_splits)
 {
-    int s = (K <= 768) ? 1 : (K + 511) / 512;
+    int s = (K + 511) / 512;
     if (s > max_splits) s = max_splits;
     if (s < 1) s = 1;
     const int chunk = ((K + s - 1) / s + SMALL_BK - 1) / SMALL_BK * SMALL_BK;
