@@ -510,6 +510,8 @@ __device__ __forceinline__ void gemm_f32_small_tile(const GemmArgs &a, float *sm
     const bool a_in = (m0 + 32 <= a.M), b_in = (n0 + 32 <= a.N);
     float colsum = 0.f;
     const bool do_colsum = (KIND == GEMM_DW) && a.colsum != nullptr && tile_n == 0;
+    // forward: the lane's bias is requested now, not after the reduction
+    const float bias_pre = (KIND == GEMM_FWD && a.bias != nullptr && n0 + r < a.N) ? a.bias[n0 + r] : 0.f;
 
     v4f ra[TA::VPT], rb[TB::VPT];
     auto load_tile = [&](int t) {
@@ -584,8 +586,7 @@ __device__ __forceinline__ void gemm_f32_small_tile(const GemmArgs &a, float *sm
     float *__restrict__ C = static_cast<float *>(a.C) + (size_t)split * a.c_split_stride;
     const int n = n0 + r;
     const bool n_ok = n < a.N;
-    float bias = 0.f;
-    if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
+    const float bias = bias_pre;
     float o4[4] = {0.f, 0.f, 0.f, 0.f};
     if (KIND == GEMM_DA && a_in && b_in) {  // the four activation values of the lane, requested together
 #pragma unroll
