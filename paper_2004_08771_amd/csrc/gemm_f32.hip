@@ -261,8 +261,9 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
     // group 0, the global loads of tile kt+2 in group 1.  The explicit lgkmcnt(0) at the head
     // of a group tells the compiler that the reads of the previous group have arrived; left
     // to itself it places the reads next to their first use and waits for them there.
-    const bool fast = (G == 4) && a_in && b_in && a.a_vec != 0 && a.b_vec != 0 && nk > 0 &&
-                      ((kend - kbeg) % BK == 0) && !a.no_fast_loop;
+    // (a last, partial k-tile is loaded through the guarded path, which pads it with zeros)
+    const bool fast = (G == 4) && a_in && b_in && a.a_vec != 0 && a.b_vec != 0 && nk > 0 && !a.no_fast_loop;
+    const int nk_full = (kend - kbeg) / BK;  // tiles [0, nk_full) are whole
     if (fast) {
         auto group = [&](int slot, int chain, auto &&extra) {
             bool first = true;
@@ -282,14 +283,19 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                         }
                     }
         };
-        TA::load_fast(ra, A, a.lda, m0, kbeg, true, tid);
-        TB::load_fast(rb, Bm, a.ldb, n0, kbeg, true, tid);
+        auto load_any = [&](int t) {
+            if (t < nk_full) {
+                TA::load_fast(ra, A, a.lda, m0, kbeg + t * BK, true, tid);
+                TB::load_fast(rb, Bm, a.ldb, n0, kbeg + t * BK, true, tid);
+            } else {
+                TA::load(ra, A, a.lda, m0, a.M, kbeg + t * BK, kend, true, tid);
+                TB::load(rb, Bm, a.ldb, n0, a.N, kbeg + t * BK, kend, true, tid);
+            }
+        };
+        load_any(0);
         TA::store(smem, ra, tid);
         TB::store(smem + TA::FLOATS, rb, tid);
-        if (nk > 1) {
-            TA::load_fast(ra, A, a.lda, m0, kbeg + BK, true, tid);
-            TB::load_fast(rb, Bm, a.ldb, n0, kbeg + BK, true, tid);
-        }
+        if (nk > 1) load_any(1);
         __syncthreads();
         read_frags(0, smem, smem + TA::FLOATS, 0);
         for (int kt = 0; kt < nk; ++kt) {
@@ -314,10 +320,7 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
             __builtin_amdgcn_s_waitcnt(0xc07f);
             group(1, 1, [&]() {
                 read_frags(0, As, Bs, 2);
-                if (next2) {
-                    TA::load_fast(ra, A, a.lda, m0, kbeg + (kt + 2) * BK, true, tid);
-                    TB::load_fast(rb, Bm, a.ldb, n0, kbeg + (kt + 2) * BK, true, tid);
-                }
+                if (next2) load_any(kt + 2);
             });
             __builtin_amdgcn_s_waitcnt(0xc07f);
             group(0, 2, [&]() { read_frags(1, As, Bs, 3); });
