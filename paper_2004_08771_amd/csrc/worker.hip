@@ -5,8 +5,10 @@
 // after updating).  Host code only: the step itself is hb_batch_step_async.
 //
 // gfx950 / HIP design of the loop: two device staging buffers and a copy stream; the rows of
-// batch k+1 travel over PCIe while batch k computes, ordered by events in both directions
-// (a buffer is refilled only after the step that read it has finished).  A push of the
+// batch k+1 travel over PCIe while batch k computes.  The step waits for its buffer's copy
+// through an event on the model's stream; the copy into a buffer waits for the step that last
+// read it on the HOST (the host is at most one step ahead of the device at that point, and the
+// device always has the current step queued).  A push of the
 // replica (merge weight 1) is asynchronous as in Section 6.2: a device-to-device snapshot in
 // stream order, then device -> host on a third stream beside the following steps, straight
 // into the host model when that is page-locked; a two-way exchange (weight < 1) first brings
@@ -312,18 +314,36 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
             (void)hipGetLastError();  // ordinary pageable memory is unknown to the runtime
     }
     PushGuard push{st, host_model, sizeof(float) * (size_t)mi.P, host_model_locked};
-    // snapshot on the model's stream (the next step may change the replica at once), then
-    // device -> host on the push stream while the next steps run
-    auto push_async = [&]() -> int {
-        int rc_f = push.finish();  // the snapshot and landing buffers are free again
-        if (rc_f != HB_OK) return rc_f;
-        WK_HIP(hipMemcpyAsync(st.snap, hb::model_params_device(m), push.bytes, hipMemcpyDeviceToDevice, mi.stream));
-        WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
-        WK_HIP(hipStreamWaitEvent(st.push, st.snap_taken, 0));
+    // A snapshot (or a blend) is produced in stream order on the model's stream; its journey to
+    // the host is ISSUED later, by issue_d2h(), once the next step has been enqueued: the host
+    // waits there for the snapshot event, so that the copy call needs no cross-stream wait (an
+    // asynchronous copy behind a hipStreamWaitEvent blocks inside the runtime, see fetch()),
+    // and the device has work queued while the host waits.
+    bool snap_pending = false;  // st.snap is being written / read on the model's stream (snap_taken covers it)
+    bool d2h_wanted = false;    // ... and has to travel to the host afterwards
+    auto issue_d2h = [&]() -> int {
+        if (!snap_pending) return HB_OK;
+        snap_pending = false;
+        WK_HIP(hipEventSynchronize(st.snap_taken));
+        if (!d2h_wanted) return HB_OK;
+        d2h_wanted = false;
         WK_HIP(hipMemcpyAsync(push.direct ? host_model : st.snap_host, st.snap, push.bytes, hipMemcpyDeviceToHost,
                               st.push));
         WK_HIP(hipEventRecord(st.snap_landed, st.push));
         push.in_flight = true;
+        return HB_OK;
+    };
+    // everything of the previous exchange is over: st.snap and the landing buffer are free
+    auto settle = [&]() -> int {
+        int rc_f = issue_d2h();
+        return rc_f != HB_OK ? rc_f : push.finish();
+    };
+    auto push_async = [&]() -> int {
+        int rc_f = settle();
+        if (rc_f != HB_OK) return rc_f;
+        WK_HIP(hipMemcpyAsync(st.snap, hb::model_params_device(m), push.bytes, hipMemcpyDeviceToDevice, mi.stream));
+        WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
+        snap_pending = d2h_wanted = true;
         return HB_OK;
     };
 
@@ -334,25 +354,16 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     // earlier than a synchronous hb_model_merge would read it: updates other workers make in
     // between are overwritten by M, as Section 6.2 accepts for concurrent workers.
     auto exchange_async = [&]() -> int {
-        int rc_f = push.finish();
+        int rc_f = settle();
         if (rc_f != HB_OK) return rc_f;
         WK_HIP(hipMemcpyAsync(st.snap, host_model, push.bytes, hipMemcpyHostToDevice, st.push));
         WK_HIP(hipEventRecord(st.glob_here, st.push));
-        WK_HIP(hipStreamWaitEvent(mi.stream, st.glob_here, 0));
+        WK_HIP(hipStreamWaitEvent(mi.stream, st.glob_here, 0));  // followed by kernel launches only
         rc_f = hb::model_blend_with_device(m, st.snap, merge_weight);
         if (rc_f != HB_OK) return rc_f;
-        if (merge_weight > 0.f) {  // weight 0 is the deep copy alone: the global model is unchanged
-            WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
-            WK_HIP(hipStreamWaitEvent(st.push, st.snap_taken, 0));
-            WK_HIP(hipMemcpyAsync(push.direct ? host_model : st.snap_host, st.snap, push.bytes,
-                                  hipMemcpyDeviceToHost, st.push));
-            WK_HIP(hipEventRecord(st.snap_landed, st.push));
-            push.in_flight = true;
-        } else {
-            // the staging buffer is free once the blend has read it: the next exchange waits for that
-            WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
-            WK_HIP(hipStreamWaitEvent(st.push, st.snap_taken, 0));
-        }
+        WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
+        snap_pending = true;
+        d2h_wanted = merge_weight > 0.f;  // weight 0 is the deep copy alone: the global model is unchanged
         return HB_OK;
     };
 
@@ -375,8 +386,11 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
         int rc = hb_sched_request(s, worker, u_report, &begin, count);
         if (rc != HB_OK || *count == 0) return rc;
         if (*count > cap) return hb::set_error(HB_ERR_STATE, "scheduler handed out %lld rows, more than max_b", (long long)*count);
-        // the buffer's previous reader must be done before it is overwritten
-        WK_HIP(hipStreamWaitEvent(st.copy, st.consumed[buf], 0));
+        // The buffer's previous reader must be done before it is overwritten.  The HOST waits
+        // for it: a hipStreamWaitEvent on the copy stream makes the asynchronous copy call that
+        // follows block inside the runtime for far longer (probe with a 150 us kernel per
+        // iteration: 215-490 us per iteration against 148 with this host-side wait).
+        WK_HIP(hipEventSynchronize(st.consumed[buf]));
         WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
                               row_bytes * (size_t)*count, hipMemcpyHostToDevice, st.copy));
         WK_HIP(hipMemcpyAsync(st.y[buf], host_y + begin, sizeof(int32_t) * (size_t)*count, hipMemcpyHostToDevice,
@@ -391,13 +405,18 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     if (rc != HB_OK) return rc;
     int buf = 0;
     while (cur > 0) {
-        // batch k+1 is requested now, with the update count batch k will have produced
-        rc = fetch(buf ^ 1, u + 1.0, &nxt);
-        if (rc != HB_OK) return rc;
         WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
         rc = hb_batch_step_async(m, st.x[buf], st.y[buf], cur, lr_per_example * (float)cur, st.loss + in_window);
         if (rc != HB_OK) return rc;
         WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
+        rc = issue_d2h();  // the snapshot taken after step k-1 leaves now that step k is queued
+        if (rc != HB_OK) return rc;
+        // Batch k+1 is requested while batch k computes, with the update count batch k will
+        // have produced.  The request comes AFTER step k has been enqueued: it waits on the
+        // host until the other buffer's last reader (step k-1) has finished, and the device
+        // must have step k queued by then or it idles meanwhile.
+        rc = fetch(buf ^ 1, u + 1.0, &nxt);
+        if (rc != HB_OK) return rc;
         u += 1.0;
         ++steps;
         ++since_merge;
@@ -419,7 +438,7 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
         rc = pushing ? push_async() : exchange_async();
         if (rc != HB_OK) return rc;
     }
-    rc = push.finish();
+    rc = settle();
     if (rc != HB_OK) return rc;
     WK_HIP(hipStreamSynchronize(st.copy));
     WK_HIP(hipStreamSynchronize(mi.stream));
@@ -447,7 +466,7 @@ extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_
     if (rc != HB_OK) return rc;
     Staging &st = *sp;
     auto send = [&](int buf, int64_t begin, int64_t count) -> int {
-        WK_HIP(hipStreamWaitEvent(st.copy, st.consumed[buf], 0));
+        WK_HIP(hipEventSynchronize(st.consumed[buf]));  // host-side, see the worker loop
         WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
                               row_bytes * (size_t)count, hipMemcpyHostToDevice, st.copy));
         WK_HIP(hipMemcpyAsync(st.y[buf], host_y + begin, sizeof(int32_t) * (size_t)count, hipMemcpyHostToDevice,
@@ -476,14 +495,14 @@ extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_
     while (count > 0) {
         const int64_t nbegin = begin + count;
         const int64_t ncount = (n_examples - nbegin) < batch ? (n_examples - nbegin) : batch;
-        if (ncount > 0) {  // the next piece travels while this one is evaluated
-            rc = send(buf ^ 1, nbegin, ncount);
-            if (rc != HB_OK) return rc;
-        }
         WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
         rc = hb_batch_loss_async(m, st.x[buf], st.y[buf], count, st.loss + in_window);
         if (rc != HB_OK) return rc;
         WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
+        if (ncount > 0) {  // the next piece travels while this one is evaluated (enqueued first, see the worker loop)
+            rc = send(buf ^ 1, nbegin, ncount);
+            if (rc != HB_OK) return rc;
+        }
         rows_in_window[in_window] = count;
         if (++in_window == LOSS_WINDOW) {
             rc = flush();
