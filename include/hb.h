@@ -243,8 +243,8 @@ int64_t hb_sched_remaining(const hb_sched *s);                  /* examples left
  * with host_model as hb_model_merge(m, host_model, merge_weight) does; merge_every = 0 or
  * host_model = NULL: never.  No merge waits for the device.  merge_weight = 1 (the push of
  * Section 6.2): the replica is snapshot in stream order and travels to host_model on a third
- * stream while the next steps run (directly if host_model is page-locked, else through a
- * page-locked buffer and a host copy).  merge_weight < 1: host_model is first copied to the
+ * stream while the next steps run (the copy is issued once the next step has been enqueued;
+ * directly if host_model is page-locked, else through a page-locked buffer and a host copy).  merge_weight < 1: host_model is first copied to the
  * device on that stream (read at the merge point of the host's program order, which runs ahead
  * of the device by at most one exchange), blended with the replica in stream order, and the
  * blend travels back like a push (not for weight 0).  Every transfer has landed when the call
