@@ -10,7 +10,10 @@
 // identically for both operands, which leaves the contraction unchanged); M-major
 // operands are read one float per lane with the 32 rows of a block on consecutive
 // addresses.  Epilogues fuse bias + activation (forward), the activation derivative
-// (backward-data) and the bias-gradient column sums (weight gradient).
+// (backward-data) and the bias-gradient column sums (weight gradient); interior tiles take
+// a form without guards that requests everything it reads in one batch.  Products with few
+// output tiles (small batches) run a second kernel family further down: 32 x 32 tiles with
+// the contraction split over the four wavefronts of a workgroup.
 #include "hb_internal.h"
 
 #include <stdlib.h>
