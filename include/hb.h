@@ -256,13 +256,32 @@ int64_t hb_sched_remaining(const hb_sched *s);                  /* examples left
  *   from epoch to epoch;  *steps_out, *loss_sum_out (may be NULL): steps taken in this call and
  *   the sum of their pre-update mean losses.
  * The request for batch k+1 is made while batch k computes, with the update count batch k
- * will have produced.  Dense input only (HB_ERR_UNSUPPORTED for a CSR model); the scheduler's
- * max_b of this worker must not exceed the model's max_B.  Synchronises the model's stream
- * before returning.
+ * will have produced.  Dense input only (HB_ERR_UNSUPPORTED for a CSR model, which
+ * hb_worker_run_epoch_csr serves); the scheduler's max_b of this worker must not exceed the
+ * model's max_B.  Synchronises the model's stream before returning.
  */
 int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X, const int32_t *host_y,
                         float lr_per_example, float *host_model, int32_t merge_every, float merge_weight,
                         double *updates, int64_t *steps_out, double *loss_sum_out);
+
+/*
+ * The same loop for a model configured with sparse_first_layer, over HOST-resident CSR training
+ * data (sparse input is the future work of Section 8; the loop is that of Section 5.1 / 6.2
+ * unchanged): host_row_ptr has n_examples + 1 non-decreasing int64 entries, host_col_idx /
+ * host_vals the stored entries (column indices in [0, d_0), trusted as in hb_batch_step_csr).
+ * For each batch the slice of the row pointer is rebased to start at 0 on the host (into a
+ * page-locked array of the handle) and travels with the batch's column indices, values and
+ * labels on the copy stream while the previous batch computes; the step is
+ * hb_batch_step_csr_async.  The device buffers for indices and values grow on demand (with a
+ * stream synchronisation when they do).  A batch with more than 2^31 - 1 stored entries, or a
+ * row pointer that decreases, is HB_ERR_INVALID (the steps taken until then stay applied).
+ * Merging, update counts and outputs are those of hb_worker_run_epoch; HB_ERR_UNSUPPORTED for a
+ * dense model.
+ */
+int hb_worker_run_epoch_csr(hb_model *m, hb_sched *s, int32_t worker, const int64_t *host_row_ptr,
+                            const int32_t *host_col_idx, const float *host_vals, const int32_t *host_y,
+                            float lr_per_example, float *host_model, int32_t merge_every, float merge_weight,
+                            double *updates, int64_t *steps_out, double *loss_sum_out);
 
 /*
  * Loss of the replica over a HOST-resident dataset (the evaluation stage of Section 5.2: the

@@ -59,6 +59,8 @@ SIGNATURES["hb_sched_new_epoch"] = (_int, [_vp])
 SIGNATURES["hb_sched_batch_size"] = (_i64, [_vp, _i32])
 SIGNATURES["hb_sched_remaining"] = (_i64, [_vp])
 SIGNATURES["hb_worker_run_epoch"] = (_int, [_vp, _vp, _i32, _vp, _vp, _f32, _vp, _i32, _f32, _f64p, _i64p, _f64p])
+SIGNATURES["hb_worker_run_epoch_csr"] = (_int, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _f32, _f64p, _i64p,
+                                                _f64p])
 SIGNATURES["hb_worker_eval_loss"] = (_int, [_vp, _vp, _vp, _i64, _i64, _f64p])
 SIGNATURES["hb_cpu_worker_run_epoch"] = (_int, [_vp, _i32, _i32p, _i32, _int, _int, _vp, _vp, _vp, _f32, _i32, _f64,
                                                 _f64p, _i64p, _f64p])
@@ -205,6 +207,18 @@ class Model:
                                          float(lr_per_example), _ptr(host_model), int(merge_every),
                                          float(merge_weight), ctypes.byref(u), ctypes.byref(steps),
                                          ctypes.byref(loss_sum)))
+        return u.value, steps.value, loss_sum.value
+
+    def worker_run_epoch_csr(self, sched, worker, host_row_ptr, host_col_idx, host_vals, host_y, lr_per_example,
+                             host_model=None, merge_every=0, merge_weight=1.0, updates=0.0):
+        """hb_worker_run_epoch_csr (host_row_ptr: int64).  Returns (updates, steps, loss_sum)."""
+        u = ctypes.c_double(float(updates))
+        steps = ctypes.c_int64(0)
+        loss_sum = ctypes.c_double(0.0)
+        _check(lib().hb_worker_run_epoch_csr(self._h, sched._h, int(worker), _ptr(host_row_ptr), _ptr(host_col_idx),
+                                             _ptr(host_vals), _ptr(host_y), float(lr_per_example), _ptr(host_model),
+                                             int(merge_every), float(merge_weight), ctypes.byref(u),
+                                             ctypes.byref(steps), ctypes.byref(loss_sum)))
         return u.value, steps.value, loss_sum.value
 
     def worker_eval_loss(self, host_X, host_y, n_examples, batch) -> float:

@@ -748,6 +748,8 @@ bool model_info(const hb_model *m, ModelInfo *out)
 
 const float *model_params_device(const hb_model *m) { return m->d_params; }
 
+int model_flat_refresh(hb_model *m) { return sync_flat_from_w1t(m); }
+
 int model_blend_with_device(hb_model *m, float *d_global, float w)
 {
     int rc = sync_flat_from_w1t(m);

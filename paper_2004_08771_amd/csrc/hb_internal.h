@@ -269,6 +269,9 @@ struct ModelInfo {
 bool model_info(const hb_model *m, ModelInfo *out);
 // the replica's flat fp32 parameters on the device (dense models: always current)
 const float *model_params_device(const hb_model *m);
+// brings the flat buffer up to date in stream order (a sparse first layer's weights live
+// transposed beside it); nothing to do for dense models
+int model_flat_refresh(hb_model *m);
 // M = (1 - w) G + w D in stream order, written to the replica D AND to d_global (P floats on
 // the device), followed by whatever keeps the replica's derived copies current (bf16 shadows)
 int model_blend_with_device(hb_model *m, float *d_global, float w);

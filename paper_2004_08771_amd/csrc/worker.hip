@@ -159,6 +159,24 @@ struct Staging {
     hipEvent_t snap_taken = nullptr;   // the snapshot is complete (model's stream)
     hipEvent_t snap_landed = nullptr;  // the snapshot has reached host memory (push stream)
     hipEvent_t glob_here = nullptr;    // the global model has reached the device (push stream)
+    // CSR batches: the slice of the row pointer is rebased to start at 0 in a page-locked array,
+    // column indices and values travel as they are
+    int64_t nnz_cap = 0;
+    int64_t nnz[2] = {0, 0};  // stored entries of the batch in buffer i
+    int32_t *rp[2] = {nullptr, nullptr};
+    int32_t *rp_host[2] = {nullptr, nullptr};
+    int32_t *ci[2] = {nullptr, nullptr};
+    float *va[2] = {nullptr, nullptr};
+    void release_csr_values()
+    {
+        for (int i = 0; i < 2; ++i) {
+            if (ci[i]) (void)hipFree(ci[i]);
+            if (va[i]) (void)hipFree(va[i]);
+            ci[i] = nullptr;
+            va[i] = nullptr;
+        }
+        nnz_cap = 0;
+    }
     ~Staging()
     {
         if (push) (void)hipStreamSynchronize(push);
@@ -174,6 +192,11 @@ struct Staging {
             if (y[i]) (void)hipFree(y[i]);
             if (filled[i]) (void)hipEventDestroy(filled[i]);
             if (consumed[i]) (void)hipEventDestroy(consumed[i]);
+        }
+        release_csr_values();
+        for (int i = 0; i < 2; ++i) {
+            if (rp[i]) (void)hipFree(rp[i]);
+            if (rp_host[i]) (void)hipHostFree(rp_host[i]);
         }
         if (loss) (void)hipFree(loss);
         if (loss_host) (void)hipHostFree(loss_host);
@@ -209,7 +232,7 @@ int acquire_staging(hb_model *m, const hb::ModelInfo &mi, int64_t cap, size_t ro
         sp->cap = 0;
         sp->row_bytes = row_bytes;
         for (int i = 0; i < 2; ++i) {
-            WK_HIP(hipMalloc(&sp->x[i], row_bytes * (size_t)cap));
+            if (row_bytes) WK_HIP(hipMalloc(&sp->x[i], row_bytes * (size_t)cap));  // no dense rows for CSR input
             WK_HIP(hipMalloc(reinterpret_cast<void **>(&sp->y[i]), sizeof(int32_t) * (size_t)cap));
             WK_HIP(hipEventCreateWithFlags(&sp->filled[i], hipEventDisableTiming));
             // "consumed" only orders the copy engine behind a step that READ the buffer: no data
@@ -247,6 +270,28 @@ int acquire_push(Staging &st, long long P)
     return HB_OK;
 }
 
+// Row-pointer staging for the staging buffers' row capacity (kept for the life of the staging buffers) and room for
+// batches of `nnz` stored entries, grown with headroom when a batch needs more.  The caller
+// makes sure that nothing reads the old buffers any more before they are replaced.
+int acquire_csr(Staging &st, int64_t nnz)
+{
+    for (int i = 0; i < 2; ++i) {
+        if (!st.rp[i]) WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.rp[i]), sizeof(int32_t) * (size_t)(st.cap + 1)));
+        if (!st.rp_host[i])
+            WK_HIP(hipHostMalloc(reinterpret_cast<void **>(&st.rp_host[i]), sizeof(int32_t) * (size_t)(st.cap + 1),
+                                 hipHostMallocDefault));
+    }
+    if (nnz <= st.nnz_cap) return HB_OK;
+    st.release_csr_values();
+    const int64_t want = nnz + nnz / 4 + 1024;
+    for (int i = 0; i < 2; ++i) {
+        WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.ci[i]), sizeof(int32_t) * (size_t)want));
+        WK_HIP(hipMalloc(reinterpret_cast<void **>(&st.va[i]), sizeof(float) * (size_t)want));
+    }
+    st.nnz_cap = want;
+    return HB_OK;
+}
+
 // One push in flight at most.  finish() waits for it and, when the host model is in pageable
 // memory, copies the landed snapshot into it; the destructor does the same on every way out
 // of the epoch, so nothing writes to the caller's memory after the call has returned.
@@ -267,20 +312,31 @@ struct PushGuard {
     ~PushGuard() { (void)finish(); }
 };
 
+// Host-resident CSR training data: row pointer of n_examples + 1 entries over col_idx / vals.
+struct CsrHost {
+    const int64_t *row_ptr;
+    const int32_t *col_idx;
+    const float *vals;
+};
+
 }  // namespace
 
-extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X,
-                                   const int32_t *host_y, float lr_per_example, float *host_model,
-                                   int32_t merge_every, float merge_weight, double *updates, int64_t *steps_out,
-                                   double *loss_sum_out)
+// The worker's loop for dense rows (csr == nullptr) or CSR rows (host_X == nullptr).
+static int run_epoch(const char *who, hb_model *m, hb_sched *s, int32_t worker, const void *host_X,
+                     const CsrHost *csr, const int32_t *host_y, float lr_per_example, float *host_model,
+                     int32_t merge_every, float merge_weight, double *updates, int64_t *steps_out,
+                     double *loss_sum_out)
 {
     hb::ModelInfo mi;
     if (!hb::model_info(m, &mi)) return hb_last_error_code();
-    if (!s || !host_X || !host_y) return hb::set_error(HB_ERR_INVALID, "hb_worker_run_epoch: NULL argument");
+    if (!s || !host_y || (!csr && !host_X) || (csr && (!csr->row_ptr || !csr->col_idx || !csr->vals)))
+        return hb::set_error(HB_ERR_INVALID, "%s: NULL argument", who);
     if (worker < 0 || worker >= (int32_t)s->b.size())
-        return hb::set_error(HB_ERR_INVALID, "hb_worker_run_epoch: worker %d is outside [0, %d)", (int)worker,
-                             (int)s->b.size());
-    if (mi.sparse) return hb::set_error(HB_ERR_UNSUPPORTED, "hb_worker_run_epoch: dense input only");
+        return hb::set_error(HB_ERR_INVALID, "%s: worker %d is outside [0, %d)", who, (int)worker, (int)s->b.size());
+    if ((mi.sparse != 0) != (csr != nullptr))
+        return hb::set_error(HB_ERR_UNSUPPORTED, csr ? "%s: the model is not configured with sparse_first_layer"
+                                                     : "%s: dense input only (hb_worker_run_epoch_csr takes CSR data)",
+                             who);
     if (s->max_b[worker] > mi.max_B)
         return hb::set_error(HB_ERR_INVALID, "the scheduler's max_b (%lld) of this worker exceeds the model's max_B (%lld)",
                              (long long)s->max_b[worker], (long long)mi.max_B);
@@ -295,7 +351,7 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     const bool pushing = merging && merge_weight == 1.f;
 
     const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
-    const size_t row_bytes = elem * (size_t)mi.d0;
+    const size_t row_bytes = csr ? 0 : elem * (size_t)mi.d0;
     const int64_t cap = s->max_b[worker];
     Staging *sp = nullptr;
     {
@@ -303,6 +359,10 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
         if (rc_st != HB_OK) return rc_st;
     }
     Staging &st = *sp;
+    if (csr) {
+        const int rc_c = acquire_csr(st, 0);
+        if (rc_c != HB_OK) return rc_c;
+    }
     bool host_model_locked = false;
     if (merging) {
         const int rc_p = acquire_push(st, mi.P);
@@ -340,6 +400,8 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     };
     auto push_async = [&]() -> int {
         int rc_f = settle();
+        if (rc_f != HB_OK) return rc_f;
+        rc_f = hb::model_flat_refresh(m);  // a sparse first layer is kept transposed beside the flat buffer
         if (rc_f != HB_OK) return rc_f;
         WK_HIP(hipMemcpyAsync(st.snap, hb::model_params_device(m), push.bytes, hipMemcpyDeviceToDevice, mi.stream));
         WK_HIP(hipEventRecord(st.snap_taken, mi.stream));
@@ -391,8 +453,42 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
         // follows block inside the runtime for far longer (probe with a 150 us kernel per
         // iteration: 215-490 us per iteration against 148 with this host-side wait).
         WK_HIP(hipEventSynchronize(st.consumed[buf]));
-        WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
-                              row_bytes * (size_t)*count, hipMemcpyHostToDevice, st.copy));
+        if (csr) {
+            const int64_t base = csr->row_ptr[begin];
+            const int64_t nnz = csr->row_ptr[begin + *count] - base;
+            if (nnz < 0 || nnz > INT32_MAX)
+                return hb::set_error(HB_ERR_INVALID, "%s: rows [%lld, %lld) hold %lld stored entries", who,
+                                     (long long)begin, (long long)(begin + *count), (long long)nnz);
+            if (nnz > st.nnz_cap) {
+                // both value buffers are replaced: the step still reading the other one has to finish
+                WK_HIP(hipStreamSynchronize(st.copy));
+                WK_HIP(hipStreamSynchronize(mi.stream));
+                const int rc_c = acquire_csr(st, nnz);
+                if (rc_c != HB_OK) return rc_c;
+            }
+            // rp_host[buf] was last read by the copy that filled this buffer two requests ago,
+            // which the step waited for that has just been seen to finish
+            int32_t *rp = st.rp_host[buf];
+            for (int64_t i = 0; i <= *count; ++i) {
+                const int64_t off = csr->row_ptr[begin + i] - base;
+                if (off < 0 || off > nnz || (i > 0 && off < rp[i - 1]))
+                    return hb::set_error(HB_ERR_INVALID, "%s: host_row_ptr is not non-decreasing at row %lld", who,
+                                         (long long)(begin + i));
+                rp[i] = (int32_t)off;
+            }
+            st.nnz[buf] = nnz;
+            WK_HIP(hipMemcpyAsync(st.rp[buf], rp, sizeof(int32_t) * (size_t)(*count + 1), hipMemcpyHostToDevice,
+                                  st.copy));
+            if (nnz > 0) {
+                WK_HIP(hipMemcpyAsync(st.ci[buf], csr->col_idx + base, sizeof(int32_t) * (size_t)nnz,
+                                      hipMemcpyHostToDevice, st.copy));
+                WK_HIP(hipMemcpyAsync(st.va[buf], csr->vals + base, sizeof(float) * (size_t)nnz,
+                                      hipMemcpyHostToDevice, st.copy));
+            }
+        } else {
+            WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
+                                  row_bytes * (size_t)*count, hipMemcpyHostToDevice, st.copy));
+        }
         WK_HIP(hipMemcpyAsync(st.y[buf], host_y + begin, sizeof(int32_t) * (size_t)*count, hipMemcpyHostToDevice,
                               st.copy));
         WK_HIP(hipEventRecord(st.filled[buf], st.copy));
@@ -406,7 +502,10 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     int buf = 0;
     while (cur > 0) {
         WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
-        rc = hb_batch_step_async(m, st.x[buf], st.y[buf], cur, lr_per_example * (float)cur, st.loss + in_window);
+        rc = csr ? hb_batch_step_csr_async(m, st.rp[buf], st.ci[buf], st.va[buf], st.nnz[buf], st.y[buf], cur,
+                                           lr_per_example * (float)cur, st.loss + in_window)
+                 : hb_batch_step_async(m, st.x[buf], st.y[buf], cur, lr_per_example * (float)cur,
+                                       st.loss + in_window);
         if (rc != HB_OK) return rc;
         WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
         rc = issue_d2h();  // the snapshot taken after step k-1 leaves now that step k is queued
@@ -446,6 +545,27 @@ extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, con
     if (steps_out) *steps_out = steps;
     if (loss_sum_out) *loss_sum_out = loss_sum;
     return HB_OK;
+}
+
+extern "C" int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *host_X,
+                                   const int32_t *host_y, float lr_per_example, float *host_model,
+                                   int32_t merge_every, float merge_weight, double *updates, int64_t *steps_out,
+                                   double *loss_sum_out)
+{
+    if (!host_X) return hb::set_error(HB_ERR_INVALID, "hb_worker_run_epoch: NULL argument");
+    return run_epoch("hb_worker_run_epoch", m, s, worker, host_X, nullptr, host_y, lr_per_example, host_model,
+                     merge_every, merge_weight, updates, steps_out, loss_sum_out);
+}
+
+extern "C" int hb_worker_run_epoch_csr(hb_model *m, hb_sched *s, int32_t worker, const int64_t *host_row_ptr,
+                                       const int32_t *host_col_idx, const float *host_vals, const int32_t *host_y,
+                                       float lr_per_example, float *host_model, int32_t merge_every,
+                                       float merge_weight, double *updates, int64_t *steps_out,
+                                       double *loss_sum_out)
+{
+    const CsrHost csr{host_row_ptr, host_col_idx, host_vals};
+    return run_epoch("hb_worker_run_epoch_csr", m, s, worker, nullptr, &csr, host_y, lr_per_example, host_model,
+                     merge_every, merge_weight, updates, steps_out, loss_sum_out);
 }
 
 extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples,

@@ -2,7 +2,7 @@
 scheduler hands out is replayed with oracle.batch_step (lr proportional to the batch size,
 Section 6.2) and, where merging is on, oracle.model_merge.  The loop prefetches: the request
 for batch k+1 is made while batch k computes, reporting the update count batch k will have
-produced."""
+produced.  hb_worker_run_epoch_csr is replayed the same way with oracle.batch_step_csr."""
 import numpy as np
 import pytest
 
@@ -184,6 +184,132 @@ def test_deep_copy_of_the_global_model_every_other_step():
     assert np.array_equal(got, host0)               # 7 steps: the closing merge copies it once more
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
     assert _rel(got, ref_p) <= TOL
+
+
+def _replay_csr(sched, worker, dims, act, loss, params, rp, ci, va, y, lr_pe, host_model=None, merge_every=0, w=1.0):
+    """The CSR loop, step by step, on the oracle (same order of requests as _replay)."""
+    p = params.astype(np.float64)
+    H = None if host_model is None else host_model.astype(np.float64)
+    u, steps, loss_sum, since = 0.0, 0, 0.0, 0
+    begin, count = sched.request(worker, u)
+    while count > 0:
+        nb, nc = sched.request(worker, u + 1.0)
+        brp, bci, bva = hi.csr_slice(rp, ci, va, begin, begin + count)
+        l, p = oracle.batch_step_csr(dims, act, loss, p, brp, bci, bva, y[begin:begin + count],
+                                     float(np.float32(lr_pe) * np.float32(count)))
+        loss_sum += l
+        u += 1.0
+        steps += 1
+        since += 1
+        if H is not None and merge_every > 0 and since >= merge_every:
+            p, H = oracle.model_merge(p, H, w)
+            since = 0
+        begin, count = nb, nc
+    if H is not None and merge_every > 0 and since > 0:
+        p, H = oracle.model_merge(p, H, w)
+    return p, H, u, steps, loss_sum
+
+
+def _csr_data(n, dims, seed, mean_nnz):
+    rng = np.random.default_rng(seed)
+    rp, ci, va = hi.zipf_csr(n, dims[0], rng, mean_nnz=mean_nnz, max_nnz=64)
+    y = hi.csr_pm1_labels(rp, ci, va, dims[0], rng)
+    params = hi.xavier_uniform_params(dims, rng, bias_scale=0.1)
+    return rp.astype(np.int64), ci, va, y, params
+
+
+@pytest.mark.parametrize("merge", [None, (1, 1.0), (2, 0.5)])
+def test_csr_worker_epoch_matches_sequential_oracle_steps(merge):
+    """hb_worker_run_epoch_csr: the batches' row-pointer slices are rebased on the host, index and
+    value buffers grow on demand (the second epoch's batches are larger than the first's), with
+    no merge, a push after every step and a blend every other step."""
+    import paper_2004_08771_amd as hb
+    import torch
+    dims, act, loss = (500, 48, 24, 1), hi.ACT_SIGMOID, hi.LOSS_LOGISTIC
+    n = 2000
+    rp, ci, va, y, params = _csr_data(n, dims, 21, mean_nnz=12)
+    lr_pe = 0.2 / 128
+    kw = {} if merge is None else dict(merge_every=merge[0], w=merge[1])
+    host0 = None
+    if merge is not None:
+        host0 = (params + np.random.default_rng(5).standard_normal(params.size).astype(np.float32) * 0.01).astype(np.float32)
+    mk = lambda make: make(n, [1, 16], [8, 300], [1, 300], 1.5)
+
+    def cpu_share(s):                 # the other worker took 20 batches and reports many updates
+        uc = 0.0
+        for _ in range(20):
+            s.request(0, uc)
+            uc += 8.0
+
+    so = mk(AdaptiveSchedule)
+    cpu_share(so)
+    ref_p, ref_H, ref_u, ref_steps, ref_loss = _replay_csr(so, 1, dims, act, loss, params, rp, ci, va, y, lr_pe,
+                                                           host_model=host0, **kw)
+    assert ref_steps > 8
+
+    sl = mk(hb.Sched)
+    cpu_share(sl)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 300, sparse_first_layer=True)
+    m.set_params(params)
+    H = None if host0 is None else host0.copy()
+    h_ci, h_va = torch.from_numpy(ci).pin_memory(), torch.from_numpy(va).pin_memory()
+    gkw = {} if merge is None else dict(host_model=H, merge_every=merge[0], merge_weight=merge[1])
+    u, steps, loss_sum = m.worker_run_epoch_csr(sl, 1, rp, h_ci, h_va, y, lr_pe, **gkw)
+    got = np.empty_like(params)
+    m.get_params(got)
+    assert (u, steps) == (ref_u, ref_steps)
+    assert sl.remaining() == so.remaining()
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+    if H is not None:
+        assert _rel(H, ref_H) <= TOL
+    m.destroy()
+
+
+def test_csr_worker_buffers_grow_and_errors():
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (300, 16, 1), hi.ACT_SIGMOID, hi.LOSS_LOGISTIC
+    n = 1024
+    rp, ci, va, y, params = _csr_data(n, dims, 22, mean_nnz=6)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 256, sparse_first_layer=True)
+    m.set_params(params)
+    # first epoch: small batches size the value buffers; second epoch: 8 times the rows per batch
+    s1 = hb.Sched(n, [32], [32], [32])
+    u, steps, _ = m.worker_run_epoch_csr(s1, 0, rp, ci, va, y, 1e-3)
+    assert steps == 32
+    s2 = hb.Sched(n, [256], [256], [256])
+    u, steps, loss_sum = m.worker_run_epoch_csr(s2, 0, rp, ci, va, y, 1e-3, updates=u)
+    assert (u, steps) == (36.0, 4)
+    got = np.empty_like(params)
+    m.get_params(got)
+    p = params.astype(np.float64)
+    ref_loss = 0.0
+    for b, cnt, reps in ((32, 32, False), (256, 4, True)):
+        for k in range(cnt):
+            brp, bci, bva = hi.csr_slice(rp, ci, va, k * b, (k + 1) * b)
+            l, p = oracle.batch_step_csr(dims, act, loss, p, brp, bci, bva, y[k * b:(k + 1) * b],
+                                         float(np.float32(1e-3) * np.float32(b)))
+            ref_loss += l if reps else 0.0
+    assert _rel(got, p) <= TOL
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    # a row pointer that decreases is refused before anything is copied
+    bad = rp.copy()
+    bad[10] = bad[9] - 1
+    s3 = hb.Sched(n, [32], [32], [32])
+    with pytest.raises(hb.HbError):
+        m.worker_run_epoch_csr(s3, 0, bad, ci, va, y, 1e-3)
+    with pytest.raises(hb.HbError):
+        m.worker_run_epoch_csr(hb.Sched(n, [32], [32], [32]), 0, None, ci, va, y, 1e-3)
+    # dense and CSR loops are not interchangeable
+    X = np.zeros((n, dims[0]), dtype=np.float32)
+    with pytest.raises(hb.HbError):
+        m.worker_run_epoch(hb.Sched(n, [32], [32], [32]), 0, X, y, 1e-3)
+    m.destroy()
+    d = hb.Model(dims, act, loss).configure(hb.HB_F32, 256)
+    d.set_params(params)
+    with pytest.raises(hb.HbError):
+        d.worker_run_epoch_csr(hb.Sched(n, [32], [32], [32]), 0, rp, ci, va, y, 1e-3)
+    d.destroy()
 
 
 def test_worker_argument_errors():
