@@ -150,6 +150,14 @@ float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B);
  */
 int hb_batch_loss_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float *d_loss);
 
+/* Forward pass and mean loss of a CSR batch (arguments as hb_batch_step_csr), with and without
+ * host synchronisation. */
+float hb_batch_loss_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                        const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B);
+int hb_batch_loss_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                            const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,
+                            float *d_loss);
+
 /*
  * Replica <-> global model exchange (Section 6.2: the replica is a deep copy of the
  * global model, pushed back to it after the update; a stale replica's contribution can be
@@ -294,6 +302,11 @@ int hb_worker_run_epoch_csr(hb_model *m, hb_sched *s, int32_t worker, const int6
  */
 int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples, int64_t batch,
                         double *mean_loss);
+/* The same evaluation over HOST-resident CSR data (arrays as for hb_worker_run_epoch_csr) for a
+ * model configured with sparse_first_layer; the pieces run through hb_batch_loss_csr_async. */
+int hb_worker_eval_loss_csr(hb_model *m, const int64_t *host_row_ptr, const int32_t *host_col_idx,
+                            const float *host_vals, const int32_t *host_y, int64_t n_examples, int64_t batch,
+                            double *mean_loss);
 
 /*
  * The CPU worker's share of one epoch (Algorithm 2, CPU worker; Sections 6.1-6.3), host code

@@ -30,6 +30,8 @@ SIGNATURES = {
     "hb_batch_grad_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "hb_batch_loss": (_f32, [_vp, _vp, _vp, _i64]),
     "hb_batch_loss_async": (_int, [_vp, _vp, _vp, _i64, _vp]),
+    "hb_batch_loss_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64]),
+    "hb_batch_loss_csr_async": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "hb_model_merge": (_int, [_vp, _vp, _f32]),
     "hb_last_error": (ctypes.c_char_p, []),
     "hb_version": (ctypes.c_char_p, []),
@@ -62,6 +64,7 @@ SIGNATURES["hb_worker_run_epoch"] = (_int, [_vp, _vp, _i32, _vp, _vp, _f32, _vp,
 SIGNATURES["hb_worker_run_epoch_csr"] = (_int, [_vp, _vp, _i32, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _f32, _f64p, _i64p,
                                                 _f64p])
 SIGNATURES["hb_worker_eval_loss"] = (_int, [_vp, _vp, _vp, _i64, _i64, _f64p])
+SIGNATURES["hb_worker_eval_loss_csr"] = (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _f64p])
 SIGNATURES["hb_cpu_worker_run_epoch"] = (_int, [_vp, _i32, _i32p, _i32, _int, _int, _vp, _vp, _vp, _f32, _i32, _f64,
                                                 _f64p, _i64p, _f64p])
 
@@ -184,6 +187,15 @@ class Model:
     def batch_loss_async(self, dX, dy, B, d_loss=None):
         _check(lib().hb_batch_loss_async(self._h, _ptr(dX), _ptr(dy), int(B), _ptr(d_loss)))
 
+    def batch_loss_csr(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B) -> float:
+        v = lib().hb_batch_loss_csr(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals), int(nnz), _ptr(dy),
+                                    int(B))
+        return _check_float(v)
+
+    def batch_loss_csr_async(self, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, d_loss=None):
+        _check(lib().hb_batch_loss_csr_async(self._h, _ptr(d_row_ptr), _ptr(d_col_idx), _ptr(d_vals), int(nnz),
+                                             _ptr(dy), int(B), _ptr(d_loss)))
+
     def model_merge(self, host_model, weight):
         _check(lib().hb_model_merge(self._h, _ptr(host_model), float(weight)))
 
@@ -225,6 +237,12 @@ class Model:
         out = ctypes.c_double(0.0)
         _check(lib().hb_worker_eval_loss(self._h, _ptr(host_X), _ptr(host_y), int(n_examples), int(batch),
                                          ctypes.byref(out)))
+        return out.value
+
+    def worker_eval_loss_csr(self, host_row_ptr, host_col_idx, host_vals, host_y, n_examples, batch) -> float:
+        out = ctypes.c_double(0.0)
+        _check(lib().hb_worker_eval_loss_csr(self._h, _ptr(host_row_ptr), _ptr(host_col_idx), _ptr(host_vals),
+                                             _ptr(host_y), int(n_examples), int(batch), ctypes.byref(out)))
         return out.value
 
 

@@ -1133,6 +1133,25 @@ int hb_batch_step_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t
     return run_step(m, in, dy, B, lr, MODE_STEP, nullptr, d_loss);
 }
 
+int hb_batch_loss_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
+                            const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B, float *d_loss)
+{
+    Input in;
+    int rc = validate_csr_call(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, &in);
+    if (rc != HB_OK) return rc;
+    return run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, d_loss);
+}
+
+float hb_batch_loss_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx, const float *d_vals,
+                        int64_t nnz, const int32_t *dy, int64_t B)
+{
+    if (hb_batch_loss_csr_async(m, d_row_ptr, d_col_idx, d_vals, nnz, dy, B, nullptr) != HB_OK)
+        return std::numeric_limits<float>::quiet_NaN();
+    float out;
+    if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
+    return out;
+}
+
 float hb_batch_step_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
                         const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B, float lr)
 {

@@ -319,6 +319,45 @@ struct CsrHost {
     const float *vals;
 };
 
+// Sends rows [begin, begin + count) of host-resident CSR data into staging buffer `buf` on the
+// copy stream: the row-pointer slice rebased to 0, column indices and values as they are.  The
+// caller has seen buffer buf's last reader finish.
+int send_csr_rows(const char *who, Staging &st, hipStream_t model_stream, const CsrHost &csr, int buf, int64_t begin,
+                  int64_t count)
+{
+    const int64_t base = csr.row_ptr[begin];
+    const int64_t nnz = csr.row_ptr[begin + count] - base;
+    if (nnz < 0 || nnz > INT32_MAX)
+        return hb::set_error(HB_ERR_INVALID, "%s: rows [%lld, %lld) hold %lld stored entries", who, (long long)begin,
+                             (long long)(begin + count), (long long)nnz);
+    if (nnz > st.nnz_cap) {
+        // both value buffers are replaced: the kernels still reading the other one have to finish
+        WK_HIP(hipStreamSynchronize(st.copy));
+        WK_HIP(hipStreamSynchronize(model_stream));
+        const int rc_c = acquire_csr(st, nnz);
+        if (rc_c != HB_OK) return rc_c;
+    }
+    // rp_host[buf] was last read by the copy that filled this buffer two batches ago; the
+    // kernels that waited for that copy have been seen to finish
+    int32_t *rp = st.rp_host[buf];
+    for (int64_t i = 0; i <= count; ++i) {
+        const int64_t off = csr.row_ptr[begin + i] - base;
+        if (off < 0 || off > nnz || (i > 0 && off < rp[i - 1]))
+            return hb::set_error(HB_ERR_INVALID, "%s: host_row_ptr is not non-decreasing at row %lld", who,
+                                 (long long)(begin + i));
+        rp[i] = (int32_t)off;
+    }
+    st.nnz[buf] = nnz;
+    WK_HIP(hipMemcpyAsync(st.rp[buf], rp, sizeof(int32_t) * (size_t)(count + 1), hipMemcpyHostToDevice, st.copy));
+    if (nnz > 0) {
+        WK_HIP(hipMemcpyAsync(st.ci[buf], csr.col_idx + base, sizeof(int32_t) * (size_t)nnz, hipMemcpyHostToDevice,
+                              st.copy));
+        WK_HIP(hipMemcpyAsync(st.va[buf], csr.vals + base, sizeof(float) * (size_t)nnz, hipMemcpyHostToDevice,
+                              st.copy));
+    }
+    return HB_OK;
+}
+
 }  // namespace
 
 // The worker's loop for dense rows (csr == nullptr) or CSR rows (host_X == nullptr).
@@ -454,37 +493,8 @@ static int run_epoch(const char *who, hb_model *m, hb_sched *s, int32_t worker, 
         // iteration: 215-490 us per iteration against 148 with this host-side wait).
         WK_HIP(hipEventSynchronize(st.consumed[buf]));
         if (csr) {
-            const int64_t base = csr->row_ptr[begin];
-            const int64_t nnz = csr->row_ptr[begin + *count] - base;
-            if (nnz < 0 || nnz > INT32_MAX)
-                return hb::set_error(HB_ERR_INVALID, "%s: rows [%lld, %lld) hold %lld stored entries", who,
-                                     (long long)begin, (long long)(begin + *count), (long long)nnz);
-            if (nnz > st.nnz_cap) {
-                // both value buffers are replaced: the step still reading the other one has to finish
-                WK_HIP(hipStreamSynchronize(st.copy));
-                WK_HIP(hipStreamSynchronize(mi.stream));
-                const int rc_c = acquire_csr(st, nnz);
-                if (rc_c != HB_OK) return rc_c;
-            }
-            // rp_host[buf] was last read by the copy that filled this buffer two requests ago,
-            // which the step waited for that has just been seen to finish
-            int32_t *rp = st.rp_host[buf];
-            for (int64_t i = 0; i <= *count; ++i) {
-                const int64_t off = csr->row_ptr[begin + i] - base;
-                if (off < 0 || off > nnz || (i > 0 && off < rp[i - 1]))
-                    return hb::set_error(HB_ERR_INVALID, "%s: host_row_ptr is not non-decreasing at row %lld", who,
-                                         (long long)(begin + i));
-                rp[i] = (int32_t)off;
-            }
-            st.nnz[buf] = nnz;
-            WK_HIP(hipMemcpyAsync(st.rp[buf], rp, sizeof(int32_t) * (size_t)(*count + 1), hipMemcpyHostToDevice,
-                                  st.copy));
-            if (nnz > 0) {
-                WK_HIP(hipMemcpyAsync(st.ci[buf], csr->col_idx + base, sizeof(int32_t) * (size_t)nnz,
-                                      hipMemcpyHostToDevice, st.copy));
-                WK_HIP(hipMemcpyAsync(st.va[buf], csr->vals + base, sizeof(float) * (size_t)nnz,
-                                      hipMemcpyHostToDevice, st.copy));
-            }
+            const int rc_s = send_csr_rows(who, st, mi.stream, *csr, buf, begin, *count);
+            if (rc_s != HB_OK) return rc_s;
         } else {
             WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
                                   row_bytes * (size_t)*count, hipMemcpyHostToDevice, st.copy));
@@ -568,27 +578,41 @@ extern "C" int hb_worker_run_epoch_csr(hb_model *m, hb_sched *s, int32_t worker,
                      merge_every, merge_weight, updates, steps_out, loss_sum_out);
 }
 
-extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples,
-                                   int64_t batch, double *mean_loss)
+// The evaluation loop for dense rows (csr == nullptr) or CSR rows (host_X == nullptr).
+static int eval_loss(const char *who, hb_model *m, const void *host_X, const CsrHost *csr, const int32_t *host_y,
+                     int64_t n_examples, int64_t batch, double *mean_loss)
 {
     hb::ModelInfo mi;
     if (!hb::model_info(m, &mi)) return hb_last_error_code();
-    if (!host_X || !host_y || !mean_loss) return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: NULL argument");
-    if (mi.sparse) return hb::set_error(HB_ERR_UNSUPPORTED, "hb_worker_eval_loss: dense input only");
-    if (n_examples < 1) return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: n_examples must be >= 1");
+    if (!host_y || !mean_loss || (!csr && !host_X) || (csr && (!csr->row_ptr || !csr->col_idx || !csr->vals)))
+        return hb::set_error(HB_ERR_INVALID, "%s: NULL argument", who);
+    if ((mi.sparse != 0) != (csr != nullptr))
+        return hb::set_error(HB_ERR_UNSUPPORTED, csr ? "%s: the model is not configured with sparse_first_layer"
+                                                     : "%s: dense input only (hb_worker_eval_loss_csr takes CSR data)",
+                             who);
+    if (n_examples < 1) return hb::set_error(HB_ERR_INVALID, "%s: n_examples must be >= 1", who);
     if (batch < 1 || batch > mi.max_B)
-        return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: batch = %lld is outside [1, max_B = %lld]",
-                             (long long)batch, (long long)mi.max_B);
+        return hb::set_error(HB_ERR_INVALID, "%s: batch = %lld is outside [1, max_B = %lld]", who, (long long)batch,
+                             (long long)mi.max_B);
     const size_t elem = (mi.dtype == HB_BF16_F32MASTER) ? 2 : 4;
-    const size_t row_bytes = elem * (size_t)mi.d0;
+    const size_t row_bytes = csr ? 0 : elem * (size_t)mi.d0;
     Staging *sp = nullptr;
     int rc = acquire_staging(m, mi, batch, row_bytes, &sp);
     if (rc != HB_OK) return rc;
     Staging &st = *sp;
+    if (csr) {
+        rc = acquire_csr(st, 0);
+        if (rc != HB_OK) return rc;
+    }
     auto send = [&](int buf, int64_t begin, int64_t count) -> int {
         WK_HIP(hipEventSynchronize(st.consumed[buf]));  // host-side, see the worker loop
-        WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
-                              row_bytes * (size_t)count, hipMemcpyHostToDevice, st.copy));
+        if (csr) {
+            const int rc_s = send_csr_rows(who, st, mi.stream, *csr, buf, begin, count);
+            if (rc_s != HB_OK) return rc_s;
+        } else {
+            WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
+                                  row_bytes * (size_t)count, hipMemcpyHostToDevice, st.copy));
+        }
         WK_HIP(hipMemcpyAsync(st.y[buf], host_y + begin, sizeof(int32_t) * (size_t)count, hipMemcpyHostToDevice,
                               st.copy));
         WK_HIP(hipEventRecord(st.filled[buf], st.copy));
@@ -616,7 +640,9 @@ extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_
         const int64_t nbegin = begin + count;
         const int64_t ncount = (n_examples - nbegin) < batch ? (n_examples - nbegin) : batch;
         WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
-        rc = hb_batch_loss_async(m, st.x[buf], st.y[buf], count, st.loss + in_window);
+        rc = csr ? hb_batch_loss_csr_async(m, st.rp[buf], st.ci[buf], st.va[buf], st.nnz[buf], st.y[buf], count,
+                                           st.loss + in_window)
+                 : hb_batch_loss_async(m, st.x[buf], st.y[buf], count, st.loss + in_window);
         if (rc != HB_OK) return rc;
         WK_HIP(hipEventRecord(st.consumed[buf], mi.stream));
         if (ncount > 0) {  // the next piece travels while this one is evaluated (enqueued first, see the worker loop)
@@ -637,4 +663,19 @@ extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_
     WK_HIP(hipStreamSynchronize(st.copy));
     *mean_loss = sum / (double)n_examples;
     return HB_OK;
+}
+
+extern "C" int hb_worker_eval_loss(hb_model *m, const void *host_X, const int32_t *host_y, int64_t n_examples,
+                                   int64_t batch, double *mean_loss)
+{
+    if (!host_X) return hb::set_error(HB_ERR_INVALID, "hb_worker_eval_loss: NULL argument");
+    return eval_loss("hb_worker_eval_loss", m, host_X, nullptr, host_y, n_examples, batch, mean_loss);
+}
+
+extern "C" int hb_worker_eval_loss_csr(hb_model *m, const int64_t *host_row_ptr, const int32_t *host_col_idx,
+                                       const float *host_vals, const int32_t *host_y, int64_t n_examples,
+                                       int64_t batch, double *mean_loss)
+{
+    const CsrHost csr{host_row_ptr, host_col_idx, host_vals};
+    return eval_loss("hb_worker_eval_loss_csr", m, nullptr, &csr, host_y, n_examples, batch, mean_loss);
 }

@@ -402,6 +402,10 @@ def check_csr_case(dims, act, loss, params, rp, ci, va, y, lr, tol=TOL_F32):
     d_va, d_y = torch.from_numpy(va).cuda(), torch.from_numpy(y).cuda()
     d_g = torch.full((params.size,), float("nan"), dtype=torch.float32, device="cuda")
     lg = m.batch_grad_csr(d_rp, d_ci, d_va, ci.size, d_y, B, d_g)
+    ll = m.batch_loss_csr(d_rp, d_ci, d_va, ci.size, d_y, B)
+    d_l = torch.zeros(1, device="cuda")
+    m.batch_loss_csr_async(d_rp, d_ci, d_va, ci.size, d_y, B, d_l)
+    assert float(d_l.cpu()[0]) == ll
     m.get_params(back)
     np.testing.assert_array_equal(back, params)
     ls = m.batch_step_csr(d_rp, d_ci, d_va, ci.size, d_y, B, lr)
@@ -409,7 +413,7 @@ def check_csr_case(dims, act, loss, params, rp, ci, va, y, lr, tol=TOL_F32):
     m.get_params(after)
     m.destroy()
 
-    for name, v in (("batch_grad_csr", lg), ("batch_step_csr", ls)):
+    for name, v in (("batch_grad_csr", lg), ("batch_loss_csr", ll), ("batch_step_csr", ls)):
         assert abs(v - l_ref) <= tol * abs(l_ref), f"{name} loss {v} vs {l_ref}"
     assert_close_per_tensor(dims, d_g.cpu().numpy(), g_ref, tol, "gradient", abs_floor=1e-7)
     assert_close_per_tensor(dims, after, p_ref, tol, "parameters after one step")

@@ -359,6 +359,26 @@ def test_epoch_loss_evaluation_matches_oracle_mean_loss():
     assert abs(gotb - refb) <= 2e-2 * abs(refb)
 
 
+def test_csr_epoch_loss_evaluation_matches_oracle_mean_loss():
+    """The evaluation stage over CSR data: the oracle's dense forward pass over the expanded rows
+    is the reference; pieces of 300 rows with a ragged last one, then pieces of 7."""
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (400, 40, 1), hi.ACT_RELU, hi.LOSS_LOGISTIC
+    n = 1000
+    rp, ci, va, y, params = _csr_data(n, dims, 23, mean_nnz=9)
+    ref = oracle.batch_loss(dims, act, loss, params.astype(np.float64), hi.csr_to_dense(rp, ci, va, dims[0]), y)
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 300, sparse_first_layer=True)
+    m.set_params(params)
+    got = m.worker_eval_loss_csr(rp, ci, va, y, n, 300)
+    assert abs(got - ref) <= TOL * abs(ref)
+    assert abs(m.worker_eval_loss_csr(rp, ci, va, y, n, 7) - ref) <= TOL * abs(ref)
+    after = np.empty_like(params); m.get_params(after)
+    np.testing.assert_array_equal(after, params)
+    with pytest.raises(hb.HbError):
+        m.worker_eval_loss(np.zeros((n, dims[0]), dtype=np.float32), y, n, 300)   # dense rows for a CSR model
+    m.destroy()
+
+
 def test_cpu_and_gpu_workers_share_an_epoch():
     """CPU+GPU Adaptive Hogbatch end to end on synthetic data: one scheduler, one shared host
     model, a CPU worker (Hogwild threads) and the GPU worker running concurrently, the GPU
