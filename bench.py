@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
+    ap.add_argument("--no-from-host", action="store_true",
+                    help="skip the worker-loop leg (same steps with the dataset in page-locked host memory)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (reference for HBM byte counters)")
     return ap.parse_args()
@@ -218,6 +220,41 @@ def main():
         for k in kernels:
             for key in ("_total_ms", "_flops", "_bytes"):
                 k.pop(key)
+    # ---- the GPU worker's loop over the same dataset in page-locked HOST memory (per-batch
+    # transfer on a copy stream beside the steps): the PCIe-inclusive rate, reported beside
+    # `value`, never as it.  Skipped for datasets above 1 GiB.
+    from_host = None
+    host_bytes = (data["col_idx"].nbytes + data["vals"].nbytes) if cfg.sparse else \
+        rows * cfg.dims[0] * (2 if dtype_name == "bf16" else 4)
+    if not args.no_from_host and host_bytes <= (1 << 30) and n_batches >= 2:
+        sched = hb.Sched(rows, [B], [B], [B])
+        pin = lambda a: torch.from_numpy(np.ascontiguousarray(a)).pin_memory()
+        h_y = pin(data["y"])
+        if cfg.sparse:
+            h_rp = data["row_ptr"].astype(np.int64)
+            h_ci, h_va = pin(data["col_idx"]), pin(data["vals"])
+            epoch = lambda u: model.worker_run_epoch_csr(sched, 0, h_rp, h_ci, h_va, h_y, lr / B, updates=u)
+        else:
+            h_X = torch.from_numpy(X)
+            h_X = (h_X.to(torch.bfloat16) if dtype_name == "bf16" else h_X).pin_memory()
+            epoch = lambda u: model.worker_run_epoch(sched, 0, h_X, h_y, lr / B, updates=u)
+        u = 0.0
+        n_warm = max(1, min(4, (args.warmup + n_batches - 1) // n_batches + 1))
+        for _ in range(n_warm):               # untimed: staging buffers, the runtime's copy paths
+            u, _, _ = epoch(u)
+            sched.new_epoch()
+        n_epochs = max(1, min(8, args.steps // n_batches))
+        t2 = time.perf_counter()
+        h_steps = 0
+        for _ in range(n_epochs):
+            u, st_e, _ = epoch(u)
+            sched.new_epoch()
+            h_steps += st_e
+        dt2 = time.perf_counter() - t2
+        from_host = {"value": round(h_steps * B / dt2, 1), "unit": "examples/s",
+                     "ms_per_step": round(1e3 * dt2 / h_steps, 5), "steps": h_steps,
+                     "what": "hb_worker_run_epoch%s: Adaptive Hogbatch scheduler with one worker, dataset in "
+                             "page-locked host memory, no merging" % ("_csr" if cfg.sparse else "")}
     model.destroy()
 
     # ---- the oracle as it stands, on the host cores, on a bounded sample of the same workload
@@ -278,6 +315,7 @@ def main():
         "step_frac_of_mfma_peak": round(flops / (elapsed / args.steps) / 1e12 / PEAK_TFLOPS[dtype_name], 4),
         "last_loss": last_loss,
         "sync_ms_per_step": None if sync_ms_per_step is None else round(sync_ms_per_step, 5),
+        "from_host": from_host,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels": kernels,

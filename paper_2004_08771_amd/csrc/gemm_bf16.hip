@@ -16,6 +16,7 @@
 // and refreshes both bf16 copies of W_l in the same pass.
 #include "hb_internal.h"
 
+#include <mutex>
 #include <stdlib.h>
 
 namespace hb {
@@ -897,12 +898,16 @@ hipError_t launch_shape_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, 
     void (*k)(GemmBf16Args) = kind == GEMM_FWD  ? gemm_bf16_nt_kernel<BM, BN, BK, GEMM_FWD>
                               : kind == GEMM_DA ? gemm_bf16_nt_kernel<BM, BN, BK, GEMM_DA>
                                                 : gemm_bf16_nt_kernel<BM, BN, BK, GEMM_DW>;
+    static std::mutex attr_mu;  // handles on different host threads launch concurrently
     static bool attr_set[3] = {false, false, false};  // per instantiation (BM, BN, BK) and kind
-    if (LDS > 48 * 1024 && !attr_set[kind]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
-        if (e != hipSuccess) return e;
-        attr_set[kind] = true;
+    if (LDS > 48 * 1024) {
+        std::lock_guard<std::mutex> lk(attr_mu);
+        if (!attr_set[kind]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+            if (e != hipSuccess) return e;
+            attr_set[kind] = true;
+        }
     }
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (a.N + BN - 1) / BN;
@@ -928,12 +933,16 @@ hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, co
     void (*k)(GemmBf16Args) = kind == GEMM_FWD  ? gemm_bf16_dma_kernel<GEMM_FWD>
                               : kind == GEMM_DA ? gemm_bf16_dma_kernel<GEMM_DA>
                                                 : gemm_bf16_dma_kernel<GEMM_DW>;
+    static std::mutex attr_mu;
     static bool attr_set[3] = {false, false, false};
-    if (!attr_set[kind]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)DMA_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set[kind] = true;
+    {
+        std::lock_guard<std::mutex> lk(attr_mu);
+        if (!attr_set[kind]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)DMA_LDS_BYTES);
+            if (e != hipSuccess) return e;
+            attr_set[kind] = true;
+        }
     }
     a.tiles_m = (a.M + DMA_BM - 1) / DMA_BM;
     a.tiles_n = (a.N + DMA_BN - 1) / DMA_BN;

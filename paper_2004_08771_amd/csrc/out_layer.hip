@@ -12,6 +12,7 @@
 // has about one block per CU (R = 16 at B = 4096).  512 threads per block.
 #include "hb_internal.h"
 
+#include <mutex>
 #include <stdlib.h>
 
 namespace hb {
@@ -271,16 +272,20 @@ hipError_t launch_out_layer(OutLayerArgs a, hipStream_t stream, const LaunchEven
     if (a.R == 0) return hipErrorInvalidValue;
     const size_t lds = lds_bytes(a.R, a.d, a.K);
     const dim3 grid((unsigned)((a.B + a.R - 1) / a.R)), block(OL_NT);
+    static std::mutex granted_mu;  // handles on different host threads launch concurrently
     static size_t granted[OL_KMAX + 1] = {};
     hipError_t e = hipErrorInvalidValue;
     switch (a.K) {
 #define HB_OL_CASE(KK)                                                                                   \
     case KK:                                                                                             \
         e = hipSuccess;                                                                                  \
-        if (lds > granted[KK]) {                                                                         \
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(out_layer_kernel<KK>),                \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);               \
-            if (e == hipSuccess) granted[KK] = lds;                                                      \
+        {                                                                                                \
+            std::lock_guard<std::mutex> lk(granted_mu);                                                  \
+            if (lds > granted[KK]) {                                                                     \
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(out_layer_kernel<KK>),            \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
+                if (e == hipSuccess) granted[KK] = lds;                                                  \
+            }                                                                                            \
         }                                                                                                \
         if (e != hipSuccess) return e;                                                                   \
         if (ev.start)                                                                                    \

@@ -13,6 +13,8 @@
 // of their chunk sums.  Everything is HBM/L2-bandwidth work; no MFMA.
 #include "hb_internal.h"
 
+#include <mutex>
+
 namespace hb {
 namespace {
 
@@ -505,15 +507,19 @@ hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, cons
     const int rows_per_block = (int)((B + nb - 1) / nb);
     const size_t lds = ((size_t)d0 + (size_t)rows_per_block + 1) * sizeof(int32_t);
     // more than 64 KB of dynamic LDS has to be requested per kernel
+    static std::mutex lds_mu;  // handles on different host threads launch concurrently
     static size_t lds_granted = 0;
-    if (lds > 32 * 1024 && lds > lds_granted) {
-        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_hist_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (ea == hipSuccess)
-            ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_place_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (ea != hipSuccess) return ea;
-        lds_granted = lds;
+    if (lds > 32 * 1024) {
+        std::lock_guard<std::mutex> lk(lds_mu);
+        if (lds > lds_granted) {
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_hist_kernel),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (ea == hipSuccess)
+                ea = hipFuncSetAttribute(reinterpret_cast<const void *>(csc_place_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (ea != hipSuccess) return ea;
+            lds_granted = lds;
+        }
     }
     if (ev_hist.start)
         hipExtLaunchKernelGGL(csc_hist_kernel, dim3(nb), dim3(CSC_NT), (unsigned)lds, stream, ev_hist.start,

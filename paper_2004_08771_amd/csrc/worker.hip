@@ -312,6 +312,20 @@ struct PushGuard {
     ~PushGuard() { (void)finish(); }
 };
 
+// On every way out of a loop, the failing ones included, nothing is still reading the caller's
+// host arrays or writing the staging buffers: all streams are drained (a no-op after the
+// loops' own final synchronisation).
+struct DrainGuard {
+    Staging &st;
+    hipStream_t model;
+    ~DrainGuard()
+    {
+        (void)hipStreamSynchronize(st.copy);
+        if (st.push) (void)hipStreamSynchronize(st.push);
+        (void)hipStreamSynchronize(model);
+    }
+};
+
 // Host-resident CSR training data: row pointer of n_examples + 1 entries over col_idx / vals.
 struct CsrHost {
     const int64_t *row_ptr;
@@ -402,6 +416,7 @@ static int run_epoch(const char *who, hb_model *m, hb_sched *s, int32_t worker, 
         const int rc_c = acquire_csr(st, 0);
         if (rc_c != HB_OK) return rc_c;
     }
+    DrainGuard drain{st, mi.stream};
     bool host_model_locked = false;
     if (merging) {
         const int rc_p = acquire_push(st, mi.P);
@@ -604,6 +619,7 @@ static int eval_loss(const char *who, hb_model *m, const void *host_X, const Csr
         rc = acquire_csr(st, 0);
         if (rc != HB_OK) return rc;
     }
+    DrainGuard drain{st, mi.stream};
     auto send = [&](int buf, int64_t begin, int64_t count) -> int {
         WK_HIP(hipEventSynchronize(st.consumed[buf]));  // host-side, see the worker loop
         if (csr) {

@@ -422,3 +422,64 @@ def test_cpu_and_gpu_workers_share_an_epoch():
     assert np.all(np.isfinite(H))
     after = oracle.batch_loss(dims, act, loss, H, X, y)
     assert after < before
+
+
+def test_two_gpu_workers_on_their_own_streams_share_an_epoch():
+    """Two GPU workers (Section 6.2 lets any number of workers share the global model): two
+    replicas on the one device, each handle on a stream of its own (default priority), driven by
+    two host threads against one scheduler and one host model, each replica blended into the host
+    model after every step.  As with the CPU+GPU pair the interleaving is free; what is checked is
+    what the algorithm fixes.  Afterwards each handle alone still matches the oracle on its own
+    stream: concurrent use has not disturbed it."""
+    import threading
+    import torch
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (32, 64, 32, 6), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    n = 30000
+    rng = np.random.default_rng(14)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    teacher = rng.standard_normal((dims[0], dims[-1]))
+    y = np.argmax(X @ teacher, axis=1).astype(np.int32)
+    params = hi.xavier_uniform_params(dims, rng)
+    before = oracle.batch_loss(dims, act, loss, params, X, y)
+    H = params.copy()
+    s = hb.Sched(n, [64, 64], [512, 256], [512, 256], 2.0)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ms = [hb.Model(dims, act, loss).configure(hb.HB_F32, 512, stream=st.cuda_stream) for st in streams]
+    for m in ms:
+        m.set_params(params)
+    out = {}
+
+    def work(w):
+        try:
+            out[w] = ms[w].worker_run_epoch(s, w, X, y, 0.02 / 64, host_model=H, merge_every=1, merge_weight=0.5)
+        except Exception as e:          # reported by the assertion below
+            out[w] = e
+
+    th = [threading.Thread(target=work, args=(w,)) for w in range(2)]
+    for x in th:
+        x.start()
+    for x in th:
+        x.join(timeout=100)
+    assert all(isinstance(out.get(w), tuple) for w in range(2)), out
+    (u0, st0, _), (u1, st1, _) = out[0], out[1]
+    assert st0 >= 1 and st1 >= 1 and u0 == st0 and u1 == st1
+    assert s.remaining() < 64
+    assert 64 <= s.batch_size(0) <= 512 and 64 <= s.batch_size(1) <= 256
+    assert np.all(np.isfinite(H))
+    assert oracle.batch_loss(dims, act, loss, H, X, y) < before
+    # one more step on each handle, alone, against the oracle
+    for w, m in enumerate(ms):
+        p0 = np.empty_like(params)
+        m.get_params(p0)
+        B = 200 + 56 * w
+        l_ref, p_ref = oracle.batch_step(dims, act, loss, p0.astype(np.float64), X[:B], y[:B], 0.05)
+        with torch.cuda.stream(streams[w]):
+            dX, dy = torch.from_numpy(X[:B]).cuda(), torch.from_numpy(y[:B]).cuda()
+        streams[w].synchronize()
+        l = m.batch_step(dX, dy, B, 0.05)
+        p1 = np.empty_like(params)
+        m.get_params(p1)
+        assert abs(l - l_ref) <= TOL * abs(l_ref)
+        assert _rel(p1, p_ref) <= TOL
+        m.destroy()
