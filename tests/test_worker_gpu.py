@@ -312,6 +312,38 @@ def test_csr_worker_buffers_grow_and_errors():
     d.destroy()
 
 
+def test_bf16_worker_epoch_follows_the_oracle_with_rounded_operands():
+    """The loop in bf16 mode (host rows are bfloat16, 2 bytes each through the staging buffers):
+    every step is replayed on the oracle with the weights and the rows rounded to bf16 and fp64
+    master weights, to the bf16 tolerance."""
+    import paper_2004_08771_amd as hb
+    import torch
+    dims, act, loss = (64, 128, 64, 10), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    n, b = 2048 + 100, 256
+    X, y, params = _data(n, dims, 31)
+    lr_pe = 0.1 / 256
+    Xr = oracle.bf16_round(X)
+    p = params.astype(np.float64)
+    ref_loss = 0.0
+    for k in range(n // b):
+        l, g = oracle.batch_grad(dims, act, loss, oracle.round_weights_bf16(dims, p.astype(np.float32)),
+                                 Xr[k * b:(k + 1) * b], y[k * b:(k + 1) * b])
+        p = p - float(np.float32(lr_pe) * np.float32(b)) * g
+        ref_loss += l
+    m = hb.Model(dims, act, loss).configure(hb.HB_BF16_F32MASTER, b)
+    m.set_params(params)
+    hX = torch.from_numpy(X).to(torch.bfloat16).pin_memory()
+    s = hb.Sched(n, [b], [b], [b])
+    u, steps, loss_sum = m.worker_run_epoch(s, 0, hX, y, lr_pe)
+    got = np.empty_like(params)
+    m.get_params(got)
+    m.destroy()
+    assert (u, steps) == (8.0, 8) and s.remaining() == 100
+    assert abs(loss_sum - ref_loss) <= 2e-2 * abs(ref_loss)
+    assert _rel(got, p) <= 2e-2
+    assert _rel(got - params, p - params) <= 5e-2      # the updates themselves, not only the weights they barely move
+
+
 def test_worker_argument_errors():
     import paper_2004_08771_amd as hb
     dims = (8, 4, 3)
