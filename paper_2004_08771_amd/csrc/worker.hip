@@ -13,7 +13,9 @@
 // stream order, then device -> host on a third stream beside the following steps, straight
 // into the host model when that is page-locked; a two-way exchange (weight < 1) first brings
 // the global model to the device on that stream and blends in stream order.  Everything stays
-// at the default stream priority.
+// at the default stream priority.  The training and the evaluation loop each exist once, for
+// dense rows and for CSR rows (sparse first layer): a CSR batch travels as the rebased slice of
+// the row pointer plus its column indices and values.
 #include "hb_internal.h"
 
 #include <cmath>
