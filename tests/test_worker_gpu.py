@@ -78,6 +78,37 @@ def test_single_worker_epoch_matches_sequential_oracle_steps():
     m.destroy()
 
 
+def test_worker_epoch_at_the_benchmark_shape():
+    """Config 2 (54-512x4-7) at the batch size the benchmark times: two steps of 4096 rows from
+    page-locked host memory with a push after every step, replayed on the oracle."""
+    import paper_2004_08771_amd as hb
+    import torch
+    cfg = hi.CONFIGS[2]
+    B = 4096
+    n = 2 * B + 40
+    X, y = hi.make_dense_dataset(2, n)
+    params = hi.make_params(2, bias_scale=0.1)
+    lr_pe = 0.1 / 256
+    host0 = np.zeros_like(params)
+    ref_p, ref_H, ref_u, ref_steps, ref_loss = _replay(AdaptiveSchedule(n, [B], [B], [B]), 0, 0, cfg.dims,
+                                                       cfg.activation, cfg.loss, params, X, y, lr_pe,
+                                                       host_model=host0, merge_every=1, w=1.0)
+    m = hb.Model(cfg.dims, cfg.activation, cfg.loss).configure(hb.HB_F32, B)
+    m.set_params(params)
+    s = hb.Sched(n, [B], [B], [B])
+    H = torch.zeros(params.size).pin_memory()
+    u, steps, loss_sum = m.worker_run_epoch(s, 0, torch.from_numpy(X).pin_memory(), torch.from_numpy(y).pin_memory(),
+                                            lr_pe, host_model=H, merge_every=1, merge_weight=1.0)
+    got = np.empty_like(params)
+    m.get_params(got)
+    m.destroy()
+    assert (u, steps) == (ref_u, ref_steps) == (2.0, 2) and s.remaining() == 40
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+    assert _rel(got - params, ref_p - params) <= 1e-3   # the two updates themselves
+    assert np.array_equal(H.numpy(), got)               # the last push carried the final replica
+
+
 def test_adaptive_batch_sizes_pageable_memory_and_merging():
     """Two workers at the coordinator; the other (CPU) worker has taken its share and reported
     many updates, so the GPU worker's batch shrinks from request to request (alpha = 1.5, ragged
@@ -264,6 +295,32 @@ def test_csr_worker_epoch_matches_sequential_oracle_steps(merge):
     if H is not None:
         assert _rel(H, ref_H) <= TOL
     m.destroy()
+
+
+def test_csr_worker_epoch_at_the_benchmark_shape():
+    """Config 4 (20958-512x3-2, CSR rows of the real-sim shape) at the batch size the benchmark
+    times: two steps of 8192 rows from host memory, replayed on the oracle."""
+    import paper_2004_08771_amd as hb
+    cfg = hi.CONFIGS[4]
+    B = 8192
+    n = 2 * B + 50
+    rp, ci, va, y = hi.make_csr_dataset(4, n)
+    rp = rp.astype(np.int64)
+    params = hi.make_params(4, bias_scale=0.1)
+    lr_pe = cfg.lr / B
+    ref_p, _, ref_u, ref_steps, ref_loss = _replay_csr(AdaptiveSchedule(n, [B], [B], [B]), 0, cfg.dims, cfg.activation,
+                                                       cfg.loss, params, rp, ci, va, y, lr_pe)
+    m = hb.Model(cfg.dims, cfg.activation, cfg.loss).configure(hb.HB_F32, B, sparse_first_layer=True)
+    m.set_params(params)
+    s = hb.Sched(n, [B], [B], [B])
+    u, steps, loss_sum = m.worker_run_epoch_csr(s, 0, rp, ci, va, y, lr_pe)
+    got = np.empty_like(params)
+    m.get_params(got)
+    m.destroy()
+    assert (u, steps) == (ref_u, ref_steps) == (2.0, 2) and s.remaining() == 50
+    assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
+    assert _rel(got, ref_p) <= TOL
+    assert _rel(got - params, ref_p - params) <= 1e-3   # the two updates themselves
 
 
 def test_csr_worker_buffers_grow_and_errors():
