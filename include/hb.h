@@ -264,7 +264,9 @@ int64_t hb_sched_remaining(const hb_sched *s);                  /* examples left
  *   from epoch to epoch;  *steps_out, *loss_sum_out (may be NULL): steps taken in this call and
  *   the sum of their pre-update mean losses.
  * The request for batch k+1 is made while batch k computes, with the update count batch k
- * will have produced.  Dense input only (HB_ERR_UNSUPPORTED for a CSR model, which
+ * will have produced.  The host waits for a batch's copy to land before it enqueues the step
+ * (it runs one step ahead of the device); HB_WORKER_STREAMWAIT=1 in the environment makes the
+ * device wait instead.  Dense input only (HB_ERR_UNSUPPORTED for a CSR model, which
  * hb_worker_run_epoch_csr serves); the scheduler's max_b of this worker must not exceed the
  * model's max_B.  Synchronises the model's stream before returning.
  */

@@ -5,10 +5,11 @@
 // after updating).  Host code only: the step itself is hb_batch_step_async.
 //
 // gfx950 / HIP design of the loop: two device staging buffers and a copy stream; the rows of
-// batch k+1 travel over PCIe while batch k computes.  The step waits for its buffer's copy
-// through an event on the model's stream; the copy into a buffer waits for the step that last
-// read it on the HOST (the host is at most one step ahead of the device at that point, and the
-// device always has the current step queued).  A push of the
+// batch k+1 travel over PCIe while batch k computes.  Both hand-overs are waited for on the
+// HOST, which runs one step ahead of the device: the copy into a buffer is issued once the step
+// that last read it has finished (the device has the current step queued meanwhile), and a
+// step is enqueued once its buffer's copy has landed (issued a whole step earlier), so that
+// neither stream ever waits for the other on the device.  A push of the
 // replica (merge weight 1) is asynchronous as in Section 6.2: a device-to-device snapshot in
 // stream order, then device -> host on a third stream beside the following steps, straight
 // into the host model when that is page-locked; a two-way exchange (weight < 1) first brings
@@ -20,6 +21,7 @@
 
 #include <cmath>
 #include <cstdarg>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -269,6 +271,21 @@ int acquire_push(Staging &st, long long P)
     if (!st.snap_landed) WK_HIP(hipEventCreateWithFlags(&st.snap_landed, hipEventDisableTiming));
     if (!st.glob_here) WK_HIP(hipEventCreateWithFlags(&st.glob_here, hipEventDisableTiming));
     st.snap_elems = P;
+    return HB_OK;
+}
+
+// The kernels of a batch must not start before its copy has landed.  The HOST waits for the copy
+// (it runs one step ahead of the device, so the copy, issued a whole step earlier, has normally
+// finished) and the kernels are then enqueued without any cross-stream dependency: a
+// hipStreamWaitEvent on the model's stream costs 4-8 us of idle device time between two steps
+// (config 2, B = 4096: 244 -> 240 us per step; B = 512: 104.5 -> 100.5).  When the transfer takes
+// longer than the step the device-side wait would start the step a launch latency earlier:
+// HB_WORKER_STREAMWAIT=1 selects it (tuning aid).
+int wait_filled(Staging &st, int buf, hipStream_t model_stream)
+{
+    static const bool stream_wait = getenv("HB_WORKER_STREAMWAIT") && atoi(getenv("HB_WORKER_STREAMWAIT")) != 0;
+    if (stream_wait) WK_HIP(hipStreamWaitEvent(model_stream, st.filled[buf], 0));
+    else WK_HIP(hipEventSynchronize(st.filled[buf]));
     return HB_OK;
 }
 
@@ -528,7 +545,8 @@ static int run_epoch(const char *who, hb_model *m, hb_sched *s, int32_t worker, 
     if (rc != HB_OK) return rc;
     int buf = 0;
     while (cur > 0) {
-        WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
+        rc = wait_filled(st, buf, mi.stream);
+        if (rc != HB_OK) return rc;
         rc = csr ? hb_batch_step_csr_async(m, st.rp[buf], st.ci[buf], st.va[buf], st.nnz[buf], st.y[buf], cur,
                                            lr_per_example * (float)cur, st.loss + in_window)
                  : hb_batch_step_async(m, st.x[buf], st.y[buf], cur, lr_per_example * (float)cur,
@@ -657,7 +675,8 @@ static int eval_loss(const char *who, hb_model *m, const void *host_X, const Csr
     while (count > 0) {
         const int64_t nbegin = begin + count;
         const int64_t ncount = (n_examples - nbegin) < batch ? (n_examples - nbegin) : batch;
-        WK_HIP(hipStreamWaitEvent(mi.stream, st.filled[buf], 0));
+        rc = wait_filled(st, buf, mi.stream);
+        if (rc != HB_OK) return rc;
         rc = csr ? hb_batch_loss_csr_async(m, st.rp[buf], st.ci[buf], st.va[buf], st.nnz[buf], st.y[buf], count,
                                            st.loss + in_window)
                  : hb_batch_loss_async(m, st.x[buf], st.y[buf], count, st.loss + in_window);
