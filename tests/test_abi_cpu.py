@@ -48,10 +48,21 @@ def test_calls_before_configure_fail_with_state_error():
     for call in (lambda: m.set_params(buf), lambda: m.get_params(buf), lambda: m.model_merge(buf, 0.5),
                  lambda: m.batch_step(1, 1, 4, 0.1), lambda: m.batch_grad(1, 1, 4, 1),
                  lambda: m.batch_loss(1, 1, 4), lambda: m.batch_step_async(1, 1, 4, 0.1),
-                 lambda: m.batch_step_csr(1, 1, 1, 4, 1, 4, 0.1), lambda: m.profile_enable(True)):
+                 lambda: m.batch_step_csr(1, 1, 1, 4, 1, 4, 0.1), lambda: m.profile_enable(True),
+                 lambda: m.batch_loss_async(1, 1, 4), lambda: m.batch_loss_csr(1, 1, 1, 4, 1, 4),
+                 lambda: m.batch_loss_csr_async(1, 1, 1, 4, 1, 4),
+                 lambda: m.worker_eval_loss(buf, buf, 4, 4), lambda: m.worker_eval_loss_csr(buf, buf, buf, buf, 4, 4)):
         with pytest.raises(hb.HbError) as e:
             call()
         assert e.value.code == hb.HB_ERR_STATE
+    # the worker loops check the handle before anything else, too
+    s = hb.Sched(64, [4], [16], [16])
+    for call in (lambda: m.worker_run_epoch(s, 0, buf, buf, 0.01),
+                 lambda: m.worker_run_epoch_csr(s, 0, buf, buf, buf, buf, 0.01)):
+        with pytest.raises(hb.HbError) as e:
+            call()
+        assert e.value.code == hb.HB_ERR_STATE
+    assert s.remaining() == 64          # nothing was requested from the scheduler
     m.destroy()
 
 
