@@ -328,6 +328,31 @@ int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_t *layer_di
                             float lr_per_example, int32_t threads, double beta, double *updates,
                             int64_t *batches_out, double *loss_sum_out);
 
+/*
+ * One epoch of CPU+GPU Hogbatch / Adaptive Hogbatch (Sections 6.2-6.3, Algorithm 2) with one CPU
+ * worker and one GPU worker: hb_cpu_worker_run_epoch runs as worker `cpu_worker` of the
+ * scheduler on a thread started for it, hb_worker_run_epoch as worker `gpu_worker` on the
+ * calling thread, both over the same fp32 rows host_X / host_y and the same host_model (the
+ * global model, P floats): the CPU threads update it in place without locks, the GPU replica
+ * `gpu` (HB_F32, dense; its network is also the CPU worker's) is merged with it every
+ * merge_every (>= 1) steps with merge_weight as in hb_worker_run_epoch.  Fixed batch sizes
+ * (min_b = max_b in the scheduler) give CPU+GPU Hogbatch, a range gives Adaptive Hogbatch.
+ * The call returns when neither worker is sent anything more.  *gpu_updates / *cpu_updates
+ * (in/out, may be NULL -> start at 0) carry the workers' update counts from epoch to epoch;
+ * *stats (may be NULL) receives the steps / batches taken and the sums of their pre-update mean
+ * losses.  The replica should hold the global model when the first epoch starts
+ * (hb_model_set_params or hb_model_merge with weight 0).  If a worker fails, the other one still
+ * finishes the epoch and the first error (the GPU worker's, if both) is returned.
+ */
+typedef struct hb_epoch_stats {
+    int64_t gpu_steps, cpu_batches;
+    double gpu_loss_sum, cpu_loss_sum;
+} hb_epoch_stats;
+int hb_hogbatch_run_epoch(hb_sched *s, hb_model *gpu, int32_t gpu_worker, int32_t cpu_worker, const float *host_X,
+                          const int32_t *host_y, float *host_model, float lr_per_example, int32_t cpu_threads,
+                          double beta, int32_t merge_every, float merge_weight, double *gpu_updates,
+                          double *cpu_updates, hb_epoch_stats *stats);
+
 #ifdef __cplusplus
 }
 #endif

@@ -68,6 +68,9 @@ SIGNATURES["hb_worker_eval_loss_csr"] = (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _
 SIGNATURES["hb_cpu_worker_run_epoch"] = (_int, [_vp, _i32, _i32p, _i32, _int, _int, _vp, _vp, _vp, _f32, _i32, _f64,
                                                 _f64p, _i64p, _f64p])
 
+SIGNATURES["hb_hogbatch_run_epoch"] = (_int, [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _f32, _i32, _f64, _i32, _f32, _f64p,
+                                              _f64p, _vp])
+
 _lib = None
 
 
@@ -281,6 +284,23 @@ class Sched:
 
     def remaining(self) -> int:
         return int(lib().hb_sched_remaining(self._h))
+
+
+class EpochStats(ctypes.Structure):
+    _fields_ = [("gpu_steps", ctypes.c_int64), ("cpu_batches", ctypes.c_int64),
+                ("gpu_loss_sum", ctypes.c_double), ("cpu_loss_sum", ctypes.c_double)]
+
+
+def hogbatch_run_epoch(sched, gpu_model, gpu_worker, cpu_worker, host_X, host_y, host_model, lr_per_example,
+                       cpu_threads=1, beta=1.0, merge_every=1, merge_weight=0.5, gpu_updates=0.0, cpu_updates=0.0):
+    """hb_hogbatch_run_epoch.  Returns (gpu_updates, cpu_updates, stats dict)."""
+    gu, cu = ctypes.c_double(float(gpu_updates)), ctypes.c_double(float(cpu_updates))
+    st = EpochStats()
+    _check(lib().hb_hogbatch_run_epoch(sched._h, gpu_model._h, int(gpu_worker), int(cpu_worker), _ptr(host_X),
+                                       _ptr(host_y), _ptr(host_model), float(lr_per_example), int(cpu_threads),
+                                       float(beta), int(merge_every), float(merge_weight), ctypes.byref(gu),
+                                       ctypes.byref(cu), ctypes.byref(st)))
+    return gu.value, cu.value, {f: getattr(st, f) for f, _ in EpochStats._fields_}
 
 
 def cpu_worker_run_epoch(sched, worker, layer_dims, activation, loss, host_X, host_y, host_model, lr_per_example,

@@ -746,6 +746,16 @@ bool model_info(const hb_model *m, ModelInfo *out)
     return true;
 }
 
+bool model_arch(const hb_model *m, const int **dims, int *n, int *act, int *loss)
+{
+    if (check_handle(m, false) != HB_OK) return false;
+    *dims = m->dims.data();
+    *n = (int)m->dims.size();
+    *act = m->act;
+    *loss = m->loss;
+    return true;
+}
+
 const float *model_params_device(const hb_model *m) { return m->d_params; }
 
 int model_flat_refresh(hb_model *m) { return sync_flat_from_w1t(m); }

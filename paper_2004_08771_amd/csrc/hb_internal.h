@@ -269,6 +269,8 @@ struct ModelInfo {
 bool model_info(const hb_model *m, ModelInfo *out);
 // the replica's flat fp32 parameters on the device (dense models: always current)
 const float *model_params_device(const hb_model *m);
+// the network behind a handle: layer widths d_0 .. d_L (n entries), activation, loss
+bool model_arch(const hb_model *m, const int **dims, int *n, int *act, int *loss);
 // brings the flat buffer up to date in stream order (a sparse first layer's weights live
 // transposed beside it); nothing to do for dense models
 int model_flat_refresh(hb_model *m);

@@ -23,7 +23,10 @@
 #include <cstdarg>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <mutex>
+#include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/hb.h"
@@ -611,6 +614,68 @@ extern "C" int hb_worker_run_epoch_csr(hb_model *m, hb_sched *s, int32_t worker,
     const CsrHost csr{host_row_ptr, host_col_idx, host_vals};
     return run_epoch("hb_worker_run_epoch_csr", m, s, worker, nullptr, &csr, host_y, lr_per_example, host_model,
                      merge_every, merge_weight, updates, steps_out, loss_sum_out);
+}
+
+// One epoch of the heterogeneous algorithms: the CPU worker on a thread of its own, the GPU
+// worker on the calling thread, both against the same scheduler and host model.
+extern "C" int hb_hogbatch_run_epoch(hb_sched *s, hb_model *gpu, int32_t gpu_worker, int32_t cpu_worker,
+                                     const float *host_X, const int32_t *host_y, float *host_model,
+                                     float lr_per_example, int32_t cpu_threads, double beta, int32_t merge_every,
+                                     float merge_weight, double *gpu_updates, double *cpu_updates,
+                                     hb_epoch_stats *stats)
+{
+    hb::ModelInfo mi;
+    if (!hb::model_info(gpu, &mi)) return hb_last_error_code();
+    if (!s || !host_X || !host_y || !host_model)
+        return hb::set_error(HB_ERR_INVALID, "hb_hogbatch_run_epoch: NULL argument");
+    if (mi.sparse || mi.dtype != HB_F32)
+        return hb::set_error(HB_ERR_UNSUPPORTED,
+                             "hb_hogbatch_run_epoch: both workers read the same fp32 dense rows (HB_F32, no sparse first layer)");
+    const int32_t n_workers = (int32_t)s->b.size();
+    if (gpu_worker < 0 || gpu_worker >= n_workers || cpu_worker < 0 || cpu_worker >= n_workers || gpu_worker == cpu_worker)
+        return hb::set_error(HB_ERR_INVALID, "hb_hogbatch_run_epoch: workers %d and %d must be two different workers in [0, %d)",
+                             (int)gpu_worker, (int)cpu_worker, (int)n_workers);
+    if (merge_every < 1)
+        return hb::set_error(HB_ERR_INVALID,
+                             "hb_hogbatch_run_epoch: merge_every must be >= 1 (the replica's updates reach the global model by merging only)");
+    const int *dims = nullptr;
+    int n_dims = 0, act = 0, loss = 0;
+    if (!hb::model_arch(gpu, &dims, &n_dims, &act, &loss)) return hb_last_error_code();
+    const std::vector<int32_t> dims32(dims, dims + n_dims);
+
+    struct {
+        int rc = HB_OK;
+        std::string err;
+        int64_t batches = 0;
+        double loss_sum = 0.0;
+    } cpu;
+    double cu = cpu_updates ? *cpu_updates : 0.0;
+    std::thread cpu_thread;
+    try {
+        cpu_thread = std::thread([&] {
+            cpu.rc = hb_cpu_worker_run_epoch(s, cpu_worker, dims32.data(), n_dims, act, loss, host_X, host_y, host_model,
+                                             lr_per_example, cpu_threads, beta, &cu, &cpu.batches, &cpu.loss_sum);
+            if (cpu.rc != HB_OK) cpu.err = hb_last_error();  // the error text is per thread
+        });
+    } catch (const std::exception &e) {
+        return hb::set_error(HB_ERR_ALLOC, "hb_hogbatch_run_epoch: cannot start the CPU worker's thread: %s", e.what());
+    }
+    int64_t gpu_steps = 0;
+    double gpu_loss = 0.0;
+    const int grc = hb_worker_run_epoch(gpu, s, gpu_worker, host_X, host_y, lr_per_example, host_model, merge_every,
+                                        merge_weight, gpu_updates, &gpu_steps, &gpu_loss);
+    const std::string gerr = (grc != HB_OK) ? hb_last_error() : "";
+    cpu_thread.join();  // whatever happened to the GPU worker, the CPU worker finishes what is left of the epoch
+    if (cpu_updates) *cpu_updates = cu;
+    if (stats) {
+        stats->gpu_steps = gpu_steps;
+        stats->cpu_batches = cpu.batches;
+        stats->gpu_loss_sum = gpu_loss;
+        stats->cpu_loss_sum = cpu.loss_sum;
+    }
+    if (grc != HB_OK) return hb::set_error(grc, "GPU worker: %s", gerr.c_str());
+    if (cpu.rc != HB_OK) return hb::set_error(cpu.rc, "CPU worker: %s", cpu.err.c_str());
+    return HB_OK;
 }
 
 // The evaluation loop for dense rows (csr == nullptr) or CSR rows (host_X == nullptr).

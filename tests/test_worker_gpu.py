@@ -553,7 +553,8 @@ def test_two_gpu_workers_on_their_own_streams_share_an_epoch():
     assert all(isinstance(out.get(w), tuple) for w in range(2)), out
     (u0, st0, _), (u1, st1, _) = out[0], out[1]
     assert st0 >= 1 and st1 >= 1 and u0 == st0 and u1 == st1
-    assert s.remaining() < 64
+    # each worker stops at the first request that cannot be served with its batch size
+    assert s.remaining() < min(s.batch_size(0), s.batch_size(1))
     assert 64 <= s.batch_size(0) <= 512 and 64 <= s.batch_size(1) <= 256
     assert np.all(np.isfinite(H))
     assert oracle.batch_loss(dims, act, loss, H, X, y) < before
@@ -572,3 +573,47 @@ def test_two_gpu_workers_on_their_own_streams_share_an_epoch():
         assert abs(l - l_ref) <= TOL * abs(l_ref)
         assert _rel(p1, p_ref) <= TOL
         m.destroy()
+
+
+def test_one_call_runs_a_cpu_gpu_epoch():
+    """hb_hogbatch_run_epoch: the CPU worker on its own thread, the GPU worker on the caller's,
+    one scheduler, one host model, for three epochs with the update counts carried over.  The
+    interleaving is free; what the algorithm fixes is checked."""
+    import paper_2004_08771_amd as hb
+    dims, act, loss = (32, 64, 32, 6), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
+    n = 20000
+    rng = np.random.default_rng(15)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    teacher = rng.standard_normal((dims[0], dims[-1]))
+    y = np.argmax(X @ teacher, axis=1).astype(np.int32)
+    params = hi.xavier_uniform_params(dims, rng)
+    H = params.copy()
+    t = 4
+    s = hb.Sched(n, [t, 64], [8 * t, 1024], [t, 1024], 2.0)      # worker 0: CPU, worker 1: GPU
+    m = hb.Model(dims, act, loss).configure(hb.HB_F32, 1024)
+    m.set_params(params)
+    losses = [oracle.batch_loss(dims, act, loss, H, X, y)]
+    gu = cu = 0.0
+    for epoch in range(3):
+        gu0, cu0 = gu, cu
+        gu, cu, st = hb.hogbatch_run_epoch(s, m, 1, 0, X, y, H, 0.02 / 64, cpu_threads=t, beta=1.0, merge_every=1,
+                                           merge_weight=0.5, gpu_updates=gu, cpu_updates=cu)
+        assert st["gpu_steps"] >= 1 and st["cpu_batches"] >= 1
+        assert gu - gu0 == st["gpu_steps"] and cu - cu0 == st["cpu_batches"] * t
+        assert s.remaining() < 64
+        assert t <= s.batch_size(0) <= 8 * t and 64 <= s.batch_size(1) <= 1024
+        assert np.all(np.isfinite(H))
+        losses.append(oracle.batch_loss(dims, act, loss, H, X, y))
+        s.new_epoch()
+    assert losses[1] < losses[0] and losses[-1] < losses[0]
+    # argument errors: same worker twice, no merging, a model that is not fp32 dense
+    with pytest.raises(hb.HbError):
+        hb.hogbatch_run_epoch(s, m, 1, 1, X, y, H, 0.01)
+    with pytest.raises(hb.HbError):
+        hb.hogbatch_run_epoch(s, m, 1, 0, X, y, H, 0.01, merge_every=0)
+    assert s.remaining() == n                                    # nothing was handed out by the failing calls
+    m.destroy()
+    mb = hb.Model(dims, act, loss).configure(hb.HB_BF16_F32MASTER, 1024)
+    with pytest.raises(hb.HbError):
+        hb.hogbatch_run_epoch(s, mb, 1, 0, X, y, H, 0.01)
+    mb.destroy()
