@@ -49,6 +49,30 @@ def test_one_thread_is_sequential_minibatch_sgd(dims, act, loss):
     assert np.linalg.norm(H - p) <= 1e-4 * np.linalg.norm(p)
 
 
+@pytest.mark.parametrize("dims,act,loss", [
+    ((12, 9, 5), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE),
+    ((10, 8, 6, 2), hi.ACT_RELU, hi.LOSS_LOGISTIC),
+    ((7, 5, 1), hi.ACT_SIGMOID, hi.LOSS_LOGISTIC),
+])
+def test_one_thread_with_batches_of_one_example_is_plain_sgd(dims, act, loss):
+    """A sub-batch of one example takes the path that applies the update while the gradient is
+    formed (Hogwild's case); with one thread it is plain SGD, one oracle step per example."""
+    import paper_2004_08771_amd as hb
+    n, lr_pe = 60, 0.05
+    X, y, params = _data(n, dims, loss, 6)
+    p = params.astype(np.float64)
+    ref_loss = 0.0
+    for i in range(n):
+        l, p = oracle.batch_step(dims, act, loss, p, X[i:i + 1], y[i:i + 1], float(np.float32(lr_pe)))
+        ref_loss += l
+    H = params.copy()
+    s = hb.Sched(n, [1], [1], [1])
+    u, batches, loss_sum = hb.cpu_worker_run_epoch(s, 0, dims, act, loss, X, y, H, lr_pe, threads=1, beta=1.0)
+    assert batches == n and u == float(n) and s.remaining() == 0
+    assert abs(loss_sum - ref_loss) <= 1e-4 * abs(ref_loss)
+    assert np.linalg.norm(H - p) <= 1e-4 * np.linalg.norm(p)
+
+
 def test_hogwild_threads_consume_the_epoch_and_reduce_the_loss():
     import paper_2004_08771_amd as hb
     dims, act, loss = (20, 16, 4), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
