@@ -524,7 +524,7 @@ def test_two_gpu_workers_on_their_own_streams_share_an_epoch():
     import torch
     import paper_2004_08771_amd as hb
     dims, act, loss = (32, 64, 32, 6), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE
-    n = 30000
+    n = 60000
     rng = np.random.default_rng(14)
     X = rng.standard_normal((n, dims[0])).astype(np.float32)
     teacher = rng.standard_normal((dims[0], dims[-1]))
@@ -537,6 +537,9 @@ def test_two_gpu_workers_on_their_own_streams_share_an_epoch():
     ms = [hb.Model(dims, act, loss).configure(hb.HB_F32, 512, stream=st.cuda_stream) for st in streams]
     for m in ms:
         m.set_params(params)
+        # staging buffers and streams are created by a handle's first epoch (milliseconds): do that
+        # before the race, with a learning rate of zero, so that both workers get a share of it
+        m.worker_run_epoch(hb.Sched(1024, [512], [512], [512]), 0, X, y, 0.0)
     out = {}
 
     def work(w):
