@@ -105,7 +105,11 @@ float hb_batch_step(hb_model *m, const void *dX, const int32_t *dy, int64_t B, f
 
 /*
  * Same step without any host synchronisation: the mean loss is written to *d_loss (DEVICE
- * pointer, one float, may be NULL) when the stream reaches that point.
+ * pointer, one float, may be NULL) when the stream reaches that point.  For dense input the
+ * call enqueues kernels only (no memset or copy, no allocation), so it may be recorded by a
+ * stream capture on the handle's stream once one ordinary call has been made; a replay does
+ * what the call did (same pointers, B and lr).  Replay is no faster than calling: the host
+ * already runs ahead of the device.
  */
 int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float lr,
                         float *d_loss);

@@ -618,3 +618,54 @@ def test_config5_bf16_full_batch_equals_mean_of_sub_batches():
     assert abs(l_full - np.log(1000.0)) < 0.5          # random labels, small weights
     assert_close_per_tensor(cfg.dims, g_full.cpu().numpy(), (g_sum / parts).cpu().numpy(), 2e-3,
                             "full-batch gradient vs mean of quarter-batch gradients", abs_floor=1e-9)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_step_can_be_captured_in_a_graph_and_replays_like_eager_steps(bf16):
+    """hb_batch_step_async records kernels only (no memset or copy nodes, no allocation, no
+    synchronisation), so a caller may capture it.  A captured step is replayed five times, with
+    eager work and synchronisations of the caller's own in between; after every replay the
+    replica equals, bit for bit, that of a second handle taking the same steps eagerly."""
+    import paper_2004_08771_amd as hb
+    torch = _torch()
+    dims, act, loss, B = (40, 96, 64, 5), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 200
+    rng = np.random.default_rng(77)
+    X = rng.standard_normal((B, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[-1], size=B).astype(np.int32)
+    params = hi.xavier_uniform_params(dims, rng, bias_scale=0.1)
+    dtype = hb.HB_BF16_F32MASTER if bf16 else hb.HB_F32
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        dX = torch.from_numpy(X).cuda()
+        if bf16:
+            dX = dX.to(torch.bfloat16)
+        dy = torch.from_numpy(y).cuda()
+        dl_g, dl_e = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+        other = torch.ones(1 << 16, device="cuda")
+    st.synchronize()
+    eager = hb.Model(dims, act, loss).configure(dtype, B, stream=st.cuda_stream)
+    graphed = hb.Model(dims, act, loss).configure(dtype, B, stream=st.cuda_stream)
+    eager.set_params(params)
+    graphed.set_params(params)
+    graphed.batch_step_async(dX, dy, B, 0.0, dl_g)       # lr = 0: anything created lazily exists before the capture
+    st.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        graphed.batch_step_async(dX, dy, B, 0.2, dl_g)
+    pe, pg = np.empty_like(params), np.empty_like(params)
+    graphed.get_params(pg)
+    np.testing.assert_array_equal(pg, params)            # capturing ran nothing
+    for k in range(5):
+        g.replay()
+        eager.batch_step_async(dX, dy, B, 0.2, dl_e)
+        with torch.cuda.stream(st):
+            other.mul_(1.0001)                           # the caller's own eager work between replays
+        torch.cuda.synchronize()
+        eager.get_params(pe)
+        graphed.get_params(pg)
+        np.testing.assert_array_equal(pg, pe, err_msg=f"replay {k}")
+        assert float(dl_g.cpu()[0]) == float(dl_e.cpu()[0])
+    assert not np.array_equal(pe, params)
+    eager.destroy()
+    graphed.destroy()
+
