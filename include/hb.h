@@ -122,6 +122,9 @@ int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t 
  * pointers).  nnz must equal d_row_ptr[B]; it is passed so that no device read is needed
  * to size the launch.  Column indices are trusted: an index outside [0, d_0) is an
  * out-of-bounds access.  Only the weight columns that occur in the batch are touched.
+ * The CSR arrays are also read by a stream the handle owns (the per-batch column sort runs
+ * beside the forward pass); that work is joined into the handle's stream before the step ends
+ * there, so "until the stream reaches the end of the step" still bounds every read.
  */
 float hb_batch_step_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
                         const float *d_vals, int64_t nnz, const int32_t *dy, int64_t B,

@@ -112,6 +112,10 @@ struct hb_model {
     int4 *d_chunk_desc = nullptr;        // descriptor of each gradient chunk (capacity follows the CSC arrays)
     float *d_csc_val = nullptr;
     int64_t csc_cap = 0;
+    // the per-batch CSC build depends on the batch only: it runs on a stream of its own beside
+    // the forward pass and is joined before the sparse weight gradient
+    hipStream_t csc_stream = nullptr;
+    hipEvent_t csc_fork = nullptr, csc_join = nullptr;
     int b1_splits = 1;
     std::vector<void *> owned;           // every device allocation, for destroy
 
@@ -150,6 +154,14 @@ void release_device(hb_model *m)
     m->prof.clear();
     for (hipEvent_t e : m->free_events) (void)hipEventDestroy(e);
     m->free_events.clear();
+    if (m->csc_stream) {
+        (void)hipStreamSynchronize(m->csc_stream);
+        (void)hipStreamDestroy(m->csc_stream);
+    }
+    if (m->csc_fork) (void)hipEventDestroy(m->csc_fork);
+    if (m->csc_join) (void)hipEventDestroy(m->csc_join);
+    m->csc_stream = nullptr;
+    m->csc_fork = m->csc_join = nullptr;
     if (m->d_csc_row) (void)hipFree(m->d_csc_row);
     if (m->d_csc_val) (void)hipFree(m->d_csc_val);
     if (m->d_chunk_desc) (void)hipFree(m->d_chunk_desc);
@@ -229,6 +241,7 @@ int ensure_csc_capacity(hb_model *m, int64_t nnz)
 {
     if (nnz <= m->csc_cap) return HB_OK;
     HB_HIP(hipStreamSynchronize(m->stream));
+    if (m->csc_stream) HB_HIP(hipStreamSynchronize(m->csc_stream));
     int64_t cap = m->csc_cap > 0 ? m->csc_cap : 1024;
     while (cap < nnz) cap *= 2;
     if (m->d_csc_row) (void)hipFree(m->d_csc_row);
@@ -262,6 +275,31 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
     // D_{L-1} and the dW_L / db_L partials from a single read of A_{L-1}
     const bool fused_out = m->out_rows > 0 && aligned16(m->d_params + m->w_off[L]);
     const int L_gemm = fused_out ? L - 1 : L;
+
+    // ---- sparse first layer: the batch's CSC arrays (needed by the weight gradient only) are
+    // built beside the forward pass.  The fork event also orders the build behind the previous
+    // step's weight gradient, which read the same arrays.
+    auto csc_build = [&](hipStream_t s) -> int {
+        HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_cursor,
+                                m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_chunk_desc,
+                                m->d_csc_row, m->d_csc_val, s,
+                                prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
+                                prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0,
+                                           8.0 * (double)csc_hist_elems(B, m->dims[0])),
+                                prof_begin(m, HB_K_OTHER, 4, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
+                                prof_begin(m, HB_K_OTHER, 5, 0, 0, 0, 0.0, 16.0 * in.nnz)));
+        return HB_OK;
+    };
+    const bool csc_beside = m->sparse && mode != MODE_LOSS && m->csc_stream != nullptr;
+    if (csc_beside) {
+        // forked at the start of the step: later fork points (behind the first or second forward
+        // product) measured the same
+        HB_HIP(hipEventRecord(m->csc_fork, st));
+        HB_HIP(hipStreamWaitEvent(m->csc_stream, m->csc_fork, 0));
+        const int rc_b = csc_build(m->csc_stream);
+        if (rc_b != HB_OK) return rc_b;
+        HB_HIP(hipEventRecord(m->csc_join, m->csc_stream));
+    }
 
     // ---- forward, Eq. (1): A_l = f(A_{l-1} W_l^T + b_l); the last layer keeps raw scores
     for (int l = 1; l <= L_gemm; ++l) {
@@ -452,14 +490,12 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sb.count = m->dims[1];
             sb.stride = m->dims[1];
             sb.splits = m->b1_splits;
-            HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_cursor,
-                                    m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_chunk_desc,
-                                    m->d_csc_row, m->d_csc_val, sw_stream,
-                                    prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
-                                    prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0,
-                                               8.0 * (double)csc_hist_elems(B, m->dims[0])),
-                                    prof_begin(m, HB_K_OTHER, 4, 0, 0, 0, 0.0, 16.0 * m->dims[0]),
-                                    prof_begin(m, HB_K_OTHER, 5, 0, 0, 0, 0.0, 16.0 * in.nnz)));
+            if (csc_beside) {
+                HB_HIP(hipStreamWaitEvent(sw_stream, m->csc_join, 0));
+            } else {
+                const int rc_b = csc_build(sw_stream);
+                if (rc_b != HB_OK) return rc_b;
+            }
             SparseDwArgs sd = {};
             sd.col_start = m->d_col_start;
             sd.chunk_start = m->d_chunk_start;
@@ -1003,6 +1039,15 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_start, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 1);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, csc_hist_elems(max_B, m->dims[0]));
+        // HB_CSC_INLINE=1 (tuning aid) keeps the CSC build on the handle's stream, before the weight gradient
+        static const bool csc_inline = getenv("HB_CSC_INLINE") && atoi(getenv("HB_CSC_INLINE")) != 0;
+        if (rc == HB_OK && !csc_inline) {
+            if (hipStreamCreateWithFlags(&m->csc_stream, hipStreamNonBlocking) != hipSuccess ||  // default priority
+                hipEventCreateWithFlags(&m->csc_fork, hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&m->csc_join, hipEventDisableTiming) != hipSuccess)
+                rc = fail(HB_ERR_DEVICE, "cannot create the stream and events of the CSC build: %s",
+                          hipGetErrorString(hipGetLastError()));
+        }
     }
     {
         // one loss partial per block of whichever kernel computes the loss
