@@ -34,7 +34,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=2, help="workload (hb_inputs.CONFIGS index)")
     ap.add_argument("--batch", type=int, default=4096, help="rows per step (the metric is quoted at 4096)")
-    ap.add_argument("--rows", type=int, default=0, help="dataset rows kept on the device (0: the config's size)")
+    ap.add_argument("--rows", type=int, default=0,
+                    help="dataset rows kept on the device (0: the config's size, at most 2 GiB of fp32 rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
@@ -65,6 +66,11 @@ def step_flops(dims, B, first_layer_nnz_per_row=None):
     return B * (6.0 * pw - 2.0 * first)
 
 
+def note(msg):
+    """Progress on stderr (stdout carries the one JSON line): long silent phases look like hangs."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -88,10 +94,15 @@ def main():
     cfg = hi.CONFIGS[args.config]
     B = args.batch
     rows = args.rows or cfg.n_examples
+    if not args.rows and not cfg.sparse:
+        # by default no more than 2 GiB of fp32 rows are generated (config 5: 262,144 of its 1,000,000);
+        # the step time does not depend on how many batches the steps cycle through
+        rows = min(rows, (2 << 30) // (4 * cfg.dims[0]))
     rows = max(rows, B)
     t_gen = time.perf_counter()
     data = make_device_dataset(hi, torch, args.config, rows)
     t_gen = time.perf_counter() - t_gen
+    note(f"dataset of {rows} rows generated in {t_gen:.1f} s")
     dtype_name = "bf16" if cfg.dtype == hi.DTYPE_BF16_F32MASTER else "f32"
 
     model = hb.Model(cfg.dims, cfg.activation, cfg.loss)
@@ -149,6 +160,7 @@ def main():
         one_step(args.warmup + i, d_loss)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    note(f"{args.steps} timed steps: {1e3 * elapsed / args.steps:.4f} ms per step")
     last_loss = float(d_loss.item())
     ms_per_step = 1e3 * elapsed / args.steps
     value = args.steps * B / elapsed
@@ -256,6 +268,7 @@ def main():
                      "what": "hb_worker_run_epoch%s: Adaptive Hogbatch scheduler with one worker, dataset in "
                              "page-locked host memory, no merging" % ("_csr" if cfg.sparse else "")}
     model.destroy()
+    note("device legs done" + ("" if from_host is None else f"; from host memory {from_host['ms_per_step']:.4f} ms per step"))
 
     # ---- the oracle as it stands, on the host cores, on a bounded sample of the same workload
     cpu_baseline = None
@@ -285,12 +298,17 @@ def main():
             n_steps, sample = int(min(8, want // B)), B
         else:
             n_steps, sample = 1, int(max(probe_rows, want))
-        dt = sum(oracle_step(sample) for _ in range(n_steps))
-        # the same oracle on one core, on a small sample (its rate does not depend on B)
+        note(f"oracle on {cores} threads: {rate:.0f} examples/s on a probe of {probe_rows} rows; timing {n_steps} step(s) of {sample} rows")
+        dt = 0.0
+        for i in range(n_steps):
+            dt += oracle_step(sample)
+            note(f"oracle step {i + 1} of {n_steps} done")
+        # the same oracle on one core, on a small sample (its rate does not depend on B): about 4 s
         oracle.set_threads(1)
-        one_rows = min(B, 128)
+        one_rows = int(max(8, min(B, 128, 4.0 * rate / max(cores, 1))))
         one_core = one_rows / oracle_step(one_rows)
         oracle.set_threads(cores)
+        note(f"oracle on one thread: {one_core:.1f} examples/s on {one_rows} rows")
         cpu_baseline = {"value": round(n_steps * sample / dt, 2), "unit": "examples/s", "cores": cores,
                         "kind": "oracle", "value_1_core": round(one_core, 2),
                         "sample": f"{n_steps} fp64 oracle step(s) (forward, backward, update) on the first "
