@@ -441,8 +441,20 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ d
     const long long r0 = (long long)blockIdx.y * rows_per_split;
     const long long r1 = min(B, r0 + rows_per_split);
     float s = 0.f;
-    if (col < d)
-        for (long long i = r0 + rg; i < r1; i += 4) s += delta[i * ldd + col];
+    if (col < d) {
+        // eight rows requested before the first is added: the slice is a chain of loads otherwise
+        long long i = r0 + rg;
+        float s1 = 0.f;
+        for (; i + 28 < r1; i += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = delta[(i + 4 * u) * ldd + col];
+            s += (v[0] + v[1]) + (v[2] + v[3]);
+            s1 += (v[4] + v[5]) + (v[6] + v[7]);
+        }
+        for (; i < r1; i += 4) s += delta[i * ldd + col];
+        s += s1;
+    }
     red[rg][threadIdx.x & 63] = s;
     __syncthreads();
     if (rg == 0 && col < d)
