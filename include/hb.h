@@ -157,6 +157,29 @@ float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B);
  */
 int hb_batch_loss_async(hb_model *m, const void *dX, const int32_t *dy, int64_t B, float *d_loss);
 
+/*
+ * hb_batch_loss_async for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  No handle is needed: the
+ * network is described as for hb_mlp_create (HOST pointer layer_dims), d_params is the flat
+ * fp32 parameter vector on the DEVICE (P floats, 16-byte aligned, only read), dX is B x d_0 fp32
+ * row-major and dy B int32 labels (DEVICE pointers), d_loss (DEVICE pointer, one float, required)
+ * receives the mean loss of the B rows in stream order on hip_stream (a hipStream_t, NULL = the
+ * default stream).  Dense fp32 input only.  The call allocates and frees nothing on the device
+ * and does not synchronise: the activations and the per-block loss sums live in a workspace of
+ * HB_STATIC_SCRATCH_BYTES that is part of the library's device image (every device the library
+ * is loaded on holds one copy until the process ends).  A batch whose activations
+ * (sum over l >= 1 of B x d_l floats, rows padded to 4 floats) and loss sums do not fit is
+ * HB_ERR_UNSUPPORTED; nothing has been launched then.  Every call on a device shares that
+ * device's workspace, which keeps the previous call's contents (each call overwrites all it
+ * reads): calls on one device whose execution may overlap -- different streams, or host threads
+ * whose streams are not ordered -- race; calls on one stream are safe.  The result is the one
+ * hb_batch_loss_async gives for a replica holding d_params (the same kernels run).
+ */
+#define HB_STATIC_SCRATCH_BYTES (64u << 20)
+int hb_batch_loss_static(const int32_t *layer_dims, int32_t n_dims, int activation, int loss,
+                         const float *d_params, const float *dX, const int32_t *dy, int64_t B, float *d_loss,
+                         void *hip_stream);
+
 /* Forward pass and mean loss of a CSR batch (arguments as hb_batch_step_csr), with and without
  * host synchronisation. */
 float hb_batch_loss_csr(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,

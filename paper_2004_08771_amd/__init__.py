@@ -8,5 +8,5 @@ binding's entry points raises.
 from .binding import (  # noqa: F401
     HB_ACT_RELU, HB_ACT_SIGMOID, HB_BF16_F32MASTER, HB_ERR_ALLOC, HB_ERR_DEVICE,
     HB_ERR_INVALID, HB_ERR_STATE, HB_ERR_UNSUPPORTED, HB_F32, HB_LOSS_LOGISTIC,
-    HB_LOSS_SOFTMAX_CE, HB_OK, HbError, Model, Sched, cpu_worker_run_epoch, hogbatch_run_epoch, lib, lib_path,
+    HB_LOSS_SOFTMAX_CE, HB_OK, HbError, Model, Sched, batch_loss_static, cpu_worker_run_epoch, hogbatch_run_epoch, lib, lib_path,
 )

@@ -30,6 +30,7 @@ SIGNATURES = {
     "hb_batch_grad_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "hb_batch_loss": (_f32, [_vp, _vp, _vp, _i64]),
     "hb_batch_loss_async": (_int, [_vp, _vp, _vp, _i64, _vp]),
+    "hb_batch_loss_static": (_int, [_i32p, _i32, _int, _int, _vp, _vp, _vp, _i64, _vp, _vp]),
     "hb_batch_loss_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64]),
     "hb_batch_loss_csr_async": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp]),
     "hb_model_merge": (_int, [_vp, _vp, _f32]),
@@ -247,6 +248,13 @@ class Model:
         _check(lib().hb_worker_eval_loss_csr(self._h, _ptr(host_row_ptr), _ptr(host_col_idx), _ptr(host_vals),
                                              _ptr(host_y), int(n_examples), int(batch), ctypes.byref(out)))
         return out.value
+
+
+def batch_loss_static(layer_dims, activation, loss, d_params, dX, dy, B, d_loss, stream=None):
+    """hb_batch_loss_static: forward pass + mean loss without a handle and without any allocation."""
+    dims = (ctypes.c_int32 * len(layer_dims))(*[int(d) for d in layer_dims])
+    _check(lib().hb_batch_loss_static(dims, len(layer_dims), int(activation), int(loss), _ptr(d_params), _ptr(dX),
+                                      _ptr(dy), int(B), _ptr(d_loss), stream if stream else None))
 
 
 class Sched:

@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -63,6 +64,40 @@ int round_up(int x, int m) { return (x + m - 1) / m * m; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 enum StepMode { MODE_STEP = 0, MODE_GRAD = 1, MODE_LOSS = 2 };
+
+// Workspace of hb_batch_loss_static (the entry point for callers that cannot allocate): the
+// activations of the forward pass and the per-block loss partials live in this file-scope
+// device array instead of buffers from hipMalloc.  Every device the library runs on holds
+// its own copy until the process ends.
+constexpr size_t STATIC_SCRATCH_BYTES = HB_STATIC_SCRATCH_BYTES;
+constexpr int STATIC_MAX_DEVICES = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char hb_static_scratch[HB_STATIC_SCRATCH_BYTES];
+
+namespace {
+// In host code the array's name is only a stand-in: the address each device holds it at comes
+// from hipGetSymbolAddress, asked once per device with that device current.
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+
+int static_scratch_for_current_device(unsigned char **out)
+{
+    int dev = -1;
+    HB_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES)
+        return fail(HB_ERR_UNSUPPORTED, "device %d is outside the %d devices the static workspace serves", dev,
+                    STATIC_MAX_DEVICES);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HB_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(hb_static_scratch)));
+        if (!p) return fail(HB_ERR_DEVICE, "hipGetSymbolAddress returned a null address for the static workspace");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return HB_OK;
+}
 
 }  // namespace
 
@@ -1173,6 +1208,74 @@ float hb_batch_loss(hb_model *m, const void *dX, const int32_t *dy, int64_t B)
     float out;
     if (fetch_loss(m, &out) != HB_OK) return std::numeric_limits<float>::quiet_NaN();
     return out;
+}
+
+int hb_batch_loss_static(const int32_t *layer_dims, int32_t n_dims, int activation, int loss,
+                         const float *d_params, const float *dX, const int32_t *dy, int64_t B, float *d_loss,
+                         void *hip_stream)
+{
+    if (!d_params) return fail(HB_ERR_INVALID, "d_params is NULL");
+    if (!dX) return fail(HB_ERR_INVALID, "input pointer is NULL");
+    if (!dy) return fail(HB_ERR_INVALID, "label pointer dy is NULL");
+    if (!d_loss) return fail(HB_ERR_INVALID, "d_loss is NULL");
+    if (!aligned16(d_params)) return fail(HB_ERR_INVALID, "d_params must be 16-byte aligned");
+    if (B < 1 || B > MAX_BATCH)
+        return fail(HB_ERR_INVALID, "B = %lld is outside [1, %lld]", (long long)B, (long long)MAX_BATCH);
+    // a handle on the host only (validates the network exactly as hb_mlp_create does); its device
+    // pointers are set to places inside the static workspace below, nothing is allocated on a device
+    hb_model *m = hb_mlp_create(layer_dims, n_dims, activation, loss);
+    if (!m) return g_err_code;
+    struct Free {
+        hb_model *m;
+        ~Free() { delete m; }  // owns no device memory: `owned` stays empty
+    } guard{m};
+    const int L = m->L;
+    m->dtype = HB_F32;
+    m->max_B = B;
+    m->stream = static_cast<hipStream_t>(hip_stream);
+    m->ld.assign(L + 1, 0);
+    m->acts.assign(L + 1, nullptr);
+    m->delta.assign(L + 1, nullptr);
+    m->partial_w.assign(L + 1, nullptr);
+    m->partial_b.assign(L + 1, nullptr);
+    m->cap_splits.assign(L + 1, 1);
+    for (int l = 1; l <= L; ++l) m->ld[l] = round_up(m->dims[l], 4);
+    m->ld[0] = m->dims[0];
+    if (L >= 2) m->out_rows = out_layer_rows(m->dims[L - 1], m->dims[L]);
+    size_t nblk = (size_t)loss_grid_blocks(B, m->dims[L]);
+    if (m->out_rows > 0) {
+        const size_t ob = (size_t)((B + out_layer_min_rows() - 1) / out_layer_min_rows());
+        if (ob > nblk) nblk = ob;
+    }
+    // layout: [activations of layer 1 .. L, each B x ld_l floats][loss partials][mean loss], every
+    // part starting on a 256-byte boundary
+    auto align256 = [](size_t b) { return (b + 255) / 256 * 256; };
+    size_t need = 0;
+    std::vector<size_t> act_off(L + 1, 0);
+    for (int l = 1; l <= L; ++l) {
+        act_off[l] = need;
+        need += align256(sizeof(float) * (size_t)B * m->ld[l]);
+    }
+    const size_t partial_off = need;
+    need += align256(sizeof(float) * (nblk + 1));
+    const size_t loss_off = need;
+    need += 256;
+    if (need > STATIC_SCRATCH_BYTES)
+        return fail(HB_ERR_UNSUPPORTED,
+                    "hb_batch_loss_static: B = %lld rows of this network need %zu bytes of workspace, the static "
+                    "workspace holds %zu (use a handle from hb_mlp_configure and hb_batch_loss_async instead)",
+                    (long long)B, need, STATIC_SCRATCH_BYTES);
+    unsigned char *ws = nullptr;
+    int rc = static_scratch_for_current_device(&ws);
+    if (rc != HB_OK) return rc;
+    for (int l = 1; l <= L; ++l) m->acts[l] = reinterpret_cast<float *>(ws + act_off[l]);
+    m->d_loss_partials = reinterpret_cast<float *>(ws + partial_off);
+    m->d_loss = reinterpret_cast<float *>(ws + loss_off);
+    m->d_params = const_cast<float *>(d_params);  // MODE_LOSS only reads the parameters
+    m->configured = true;
+    Input in;
+    in.X = dX;
+    return run_step(m, in, dy, B, 0.f, MODE_LOSS, nullptr, d_loss);
 }
 
 int hb_batch_step_csr_async(hb_model *m, const int32_t *d_row_ptr, const int32_t *d_col_idx,
