@@ -155,7 +155,9 @@ class _V:
                 p.g += d * n.g
 
 
-def _scalar_net_loss(dims, act, loss, pv, X, y):
+def _scalar_net_loss(dims, act, loss, pv, X, y, relu_on=None):
+    """relu_on: {l: boolean B x d_l} forces the derivative decision of ReLU units (the value
+    max(z, 0) is unchanged)."""
     B, L = X.shape[0], len(dims) - 1
     total = _V(0.0)
     offs = hi.param_offsets(dims)
@@ -169,7 +171,9 @@ def _scalar_net_loss(dims, act, loss, pv, X, y):
                 for k in range(dims[l - 1]):
                     s = s + pv[wo + j * dims[l - 1] + k] * a[k]
                 z.append(s)
-            if l < L:
+            if l < L and act == RELU and relu_on is not None and l in relu_on:
+                a = [_V(max(t.v, 0.0), ((t, 1.0 if relu_on[l][i, j] else 0.0),)) for j, t in enumerate(z)]
+            elif l < L:
                 a = [((-t).exp() + 1.0).recip() if act == SIG else t.relu() for t in z]
             else:
                 a = z
