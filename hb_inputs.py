@@ -180,6 +180,31 @@ def zipf_csr(n_rows: int, n_cols: int, rng: np.random.Generator, mean_nnz: float
     return (row_ptr.astype(np.int32), np.concatenate(cols_out), np.concatenate(vals_out))
 
 
+def scramble_csr_rows(row_ptr, col_idx, vals, rng: np.random.Generator, dup_prob: float = 0.2):
+    """The same batch with the entries of every row in random order and, with probability
+    dup_prob per entry, an entry split into two entries of the same column whose fp32 values
+    add up to (about) the original: a CSR batch as a caller may hand it over that has neither
+    sorted nor merged its rows.  Returns (row_ptr, col_idx, vals) of the new batch."""
+    cols_out, vals_out = [], []
+    new_ptr = np.zeros(row_ptr.size, dtype=np.int64)
+    for i in range(row_ptr.size - 1):
+        s, e = int(row_ptr[i]), int(row_ptr[i + 1])
+        c, v = col_idx[s:e].astype(np.int32), vals[s:e].astype(np.float32)
+        split = rng.random(c.size) < dup_prob
+        part = v[split] * rng.uniform(0.2, 0.8, int(split.sum())).astype(np.float32)
+        rest = v.copy()
+        rest[split] -= part
+        c = np.concatenate([c, c[split]])
+        v = np.concatenate([rest, part])
+        order = rng.permutation(c.size)
+        cols_out.append(c[order])
+        vals_out.append(v[order])
+        new_ptr[i + 1] = new_ptr[i] + c.size
+    if not cols_out:
+        return row_ptr.copy(), col_idx.copy(), vals.copy()
+    return new_ptr.astype(np.int32), np.concatenate(cols_out).astype(np.int32), np.concatenate(vals_out).astype(np.float32)
+
+
 def csr_pm1_labels(row_ptr, col_idx, vals, n_cols: int, rng: np.random.Generator) -> np.ndarray:
     w = rng.standard_normal(n_cols)
     contrib = vals.astype(np.float64) * w[col_idx]

@@ -17,7 +17,7 @@ def _first_layer(X, W, csr):
         return X.astype(np.float64) @ W.T
     import scipy.sparse as sp
     row_ptr, col_idx, vals = csr
-    Xs = sp.csr_matrix((vals.astype(np.float64), col_idx, row_ptr), shape=(row_ptr.size - 1, W.shape[1]))
+    Xs = sp.csr_matrix((vals.astype(np.float64), col_idx.copy(), row_ptr.copy()), shape=(row_ptr.size - 1, W.shape[1]))
     return np.asarray(Xs @ W.T)
 
 
