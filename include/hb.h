@@ -73,7 +73,7 @@ hb_model *hb_mlp_create(const int32_t *layer_dims, int32_t n_dims, int activatio
 
 /*
  * Allocate the device replica and the workspace for batches of up to max_B rows (Section
- * 5.2: "GPU workers ... have to allocate memory on the device").  dtype: HB_F32 or
+ * 5.2, initialisation: a GPU worker allocates its device memory up front).  dtype: HB_F32 or
  * HB_BF16_F32MASTER (bf16 weights/activations, fp32 master weights and accumulation).
  * sparse_first_layer != 0 selects CSR input for layer 1 (then only the *_csr step calls
  * are valid, and only HB_F32).  hip_stream is a hipStream_t (NULL = the default stream)
@@ -94,6 +94,15 @@ int hb_model_set_params(hb_model *m, const float *host_flat);
 
 /* host_flat <- replica (fp32 master weights).  Synchronises the stream. */
 int hb_model_get_params(hb_model *m, float *host_flat);
+
+/*
+ * host_out <- the hidden activations A_layer (Section 3, Eq. (1)) that the most recent batch call
+ * of this handle computed for its first B rows: B x d_layer fp32, row-major, HOST pointer;
+ * 1 <= layer < L.  In the bf16 mode the stored bf16 values are widened (exactly).  For
+ * inspection and tests: it shows which hidden units a ReLU network switched on.  Synchronises the
+ * stream.  The contents are those of whichever call ran last (step, gradient or loss).
+ */
+int hb_model_get_activations(hb_model *m, int32_t layer, int64_t B, float *host_out);
 
 /*
  * One GPU-worker step (Algorithm 1, worker lines "Gradient" and "Update model"; Section 3,
@@ -120,8 +129,12 @@ int hb_batch_step_async(hb_model *m, const void *dX, const int32_t *dy, int64_t 
  * real-sim-shaped configuration).  d_row_ptr: B + 1 int32 starting at 0; d_col_idx /
  * d_vals: nnz entries, column indices in [0, d_0), any order within a row (DEVICE
  * pointers).  nnz must equal d_row_ptr[B]; it is passed so that no device read is needed
- * to size the launch.  Column indices are trusted: an index outside [0, d_0) is an
- * out-of-bounds access.  Only the weight columns that occur in the batch are touched.
+ * to size the launch.  A column may occur more than once in a row (the products add).
+ * Column indices and the row pointer are trusted: an index outside [0, d_0) is an
+ * out-of-bounds access.  With HB_CHECK_INDICES=1 in the environment every CSR call first
+ * checks them on the device (one more pass over the arrays and a synchronisation) and fails
+ * with HB_ERR_INVALID before any kernel dereferences them.  Only the weight columns that occur
+ * in the batch are touched.
  * The CSR arrays are also read by a stream the handle owns (the per-batch column sort runs
  * beside the forward pass); that work is joined into the handle's stream before the step ends
  * there, so "until the stream reaches the end of the step" still bounds every read.
@@ -233,9 +246,21 @@ typedef struct hb_kernel_stat {
     double total_ms;         /* sum of the kernel execution times */
     double flops_per_launch; /* algorithmic: 2 M N K for a product */
     double bytes_per_launch; /* algorithmic HBM bytes: each operand read once, result written once */
+    double cache_bytes_per_launch; /* CSR kernels: bytes of the row gathers (one weight / delta row per
+                                      stored entry), served by the caches; 0 elsewhere */
 } hb_kernel_stat;
 int hb_profile_enable(hb_model *m, int on);
 int hb_profile_read(hb_model *m, hb_kernel_stat *out, int32_t cap, int32_t *n_out);
+
+/*
+ * Planning aid, host only (no device call): the number of slices of the batch in which the bf16
+ * mode computes the weight gradient dW_l = D_l^T A_{l-1} (Eq. (2)) of a d_out x d_in layer at batch
+ * size B -- products with too few output tiles to fill the device are split over the batch and
+ * their partial sums added in a fixed order; 1 = not split.  With capacity != 0: the largest
+ * count any batch size up to B can get, which is what hb_mlp_configure(max_B = B) reserves room
+ * for.  0 on invalid arguments.
+ */
+int32_t hb_plan_bf16_dw_slices(int32_t d_out, int32_t d_in, int64_t B, int32_t capacity);
 
 /* Library version string, e.g. for logs. */
 const char *hb_version(void);
@@ -308,7 +333,8 @@ int hb_worker_run_epoch(hb_model *m, hb_sched *s, int32_t worker, const void *ho
  * The same loop for a model configured with sparse_first_layer, over HOST-resident CSR training
  * data (sparse input is the future work of Section 8; the loop is that of Section 5.1 / 6.2
  * unchanged): host_row_ptr has n_examples + 1 non-decreasing int64 entries, host_col_idx /
- * host_vals the stored entries (column indices in [0, d_0), trusted as in hb_batch_step_csr).
+ * host_vals the stored entries (column indices in [0, d_0): every batch's indices are checked on
+ * the host before the batch is sent, and one outside the range is HB_ERR_INVALID).
  * For each batch the slice of the row pointer is rebased to start at 0 on the host (into a
  * page-locked array of the handle) and travels with the batch's column indices, values and
  * labels on the copy stream while the previous batch computes; the step is

@@ -22,6 +22,7 @@ SIGNATURES = {
     "hb_model_num_params": (_i64, [_vp]),
     "hb_model_set_params": (_int, [_vp, _vp]),
     "hb_model_get_params": (_int, [_vp, _vp]),
+    "hb_model_get_activations": (_int, [_vp, _i32, _i64, _vp]),
     "hb_batch_step": (_f32, [_vp, _vp, _vp, _i64, _f32]),
     "hb_batch_step_async": (_int, [_vp, _vp, _vp, _i64, _f32, _vp]),
     "hb_batch_step_csr": (_f32, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _f32]),
@@ -36,6 +37,7 @@ SIGNATURES = {
     "hb_model_merge": (_int, [_vp, _vp, _f32]),
     "hb_last_error": (ctypes.c_char_p, []),
     "hb_version": (ctypes.c_char_p, []),
+    "hb_plan_bf16_dw_slices": (_i32, [_i32, _i32, _i64, _i32]),
 }
 
 HB_K_NAMES = {0: "fwd_gemm", 1: "da_gemm", 2: "dw_gemm", 3: "loss", 4: "update", 5: "spmm_fwd",
@@ -47,7 +49,7 @@ class KernelStat(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("layer", ctypes.c_int32), ("M", ctypes.c_int64),
                 ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("launches", ctypes.c_int64),
                 ("total_ms", ctypes.c_double), ("flops_per_launch", ctypes.c_double),
-                ("bytes_per_launch", ctypes.c_double)]
+                ("bytes_per_launch", ctypes.c_double), ("cache_bytes_per_launch", ctypes.c_double)]
 
 
 SIGNATURES["hb_last_error_code"] = (_int, [])
@@ -158,6 +160,9 @@ class Model:
 
     def get_params(self, host_flat):
         _check(lib().hb_model_get_params(self._h, _ptr(host_flat)))
+
+    def get_activations(self, layer, B, host_out):
+        _check(lib().hb_model_get_activations(self._h, int(layer), int(B), _ptr(host_out)))
 
     def batch_step(self, dX, dy, B, lr) -> float:
         v = lib().hb_batch_step(self._h, _ptr(dX), _ptr(dy), int(B), float(lr))

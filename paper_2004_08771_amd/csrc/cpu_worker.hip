@@ -148,12 +148,9 @@ float example_grad(const Net &n, float *W, const float *x, int y, float scale, f
     return lossv;
 }
 
-}  // namespace
-
-extern "C" int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_t *layer_dims, int32_t n_dims,
-                                       int activation, int loss, const float *host_X, const int32_t *host_y,
-                                       float *host_model, float lr_per_example, int32_t threads, double beta,
-                                       double *updates, int64_t *batches_out, double *loss_sum_out)
+int cpu_worker_epoch(hb_sched *s, int32_t worker, const int32_t *layer_dims, int32_t n_dims, int activation, int loss,
+                     const float *host_X, const int32_t *host_y, float *host_model, float lr_per_example,
+                     int32_t threads, double beta, double *updates, int64_t *batches_out, double *loss_sum_out)
 {
     Net net;
     if (!make_net(layer_dims, n_dims, activation, loss, &net))
@@ -176,6 +173,15 @@ extern "C" int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_
         const int rc = hb_sched_request(s, worker, u, &begin, &count);
         if (rc != HB_OK) return rc;
         if (count == 0) break;
+        // labels index the output scores: a label outside its domain is an error, not a stray read
+        for (int64_t i = begin; i < begin + count; ++i) {
+            const int32_t yi = host_y[i];
+            const bool ok = (loss == HB_LOSS_LOGISTIC) ? (yi == 1 || yi == -1) : (yi >= 0 && yi < net.dims[net.L]);
+            if (!ok)
+                return hb::set_error(HB_ERR_INVALID, "hb_cpu_worker_run_epoch: label %d of example %lld is outside its domain (%s)",
+                                     (int)yi, (long long)i,
+                                     loss == HB_LOSS_LOGISTIC ? "+1 / -1" : "class index in [0, d_L)");
+        }
         // sub-batch i: rows [begin + i*count/t, begin + (i+1)*count/t)
         auto work = [&](int t) {
             const int64_t lo = begin + count * t / threads, hi = begin + count * (t + 1) / threads;
@@ -201,9 +207,16 @@ extern "C" int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_
             // a condition variable was measured SLOWER (8 threads, 54-512x4-7: 8.8k against 12.6k
             // rows/s at 8 rows per thread), the woken threads starting on the waker's core.
             std::vector<std::thread> pool;
-            pool.reserve(threads);
-            for (int t = 0; t < threads; ++t) pool.emplace_back(work, t);
+            bool started_all = true;
+            try {
+                pool.reserve(threads);
+                for (int t = 0; t < threads; ++t) pool.emplace_back(work, t);
+            } catch (...) {  // no exception may cross the C boundary
+                started_all = false;
+            }
             for (auto &th : pool) th.join();
+            if (!started_all)
+                return hb::set_error(HB_ERR_ALLOC, "hb_cpu_worker_run_epoch: could not start %d threads", (int)threads);
         }
         for (int t = 0; t < threads; ++t) loss_sum += tl[t];
         u += (double)threads * beta;  // Algorithm 2, CPU worker: t * beta surviving updates per batch
@@ -213,4 +226,19 @@ extern "C" int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_
     if (batches_out) *batches_out = batches;
     if (loss_sum_out) *loss_sum_out = loss_sum;
     return HB_OK;
+}
+
+}  // namespace
+
+extern "C" int hb_cpu_worker_run_epoch(hb_sched *s, int32_t worker, const int32_t *layer_dims, int32_t n_dims,
+                                       int activation, int loss, const float *host_X, const int32_t *host_y,
+                                       float *host_model, float lr_per_example, int32_t threads, double beta,
+                                       double *updates, int64_t *batches_out, double *loss_sum_out)
+{
+    try {
+        return cpu_worker_epoch(s, worker, layer_dims, n_dims, activation, loss, host_X, host_y, host_model,
+                                lr_per_example, threads, beta, updates, batches_out, loss_sum_out);
+    } catch (...) {  // allocation of the per-thread scratch: no exception may cross the C boundary
+        return hb::set_error(HB_ERR_ALLOC, "hb_cpu_worker_run_epoch: out of host memory");
+    }
 }

@@ -370,6 +370,33 @@ hipError_t launch_label_check(const int32_t *y, long long B, int K, int loss, un
     return hipGetLastError();
 }
 
+// Counts what makes a CSR batch unusable: column indices outside [0, d0), a row pointer that
+// does not start at 0, decreases, or does not end at nnz.
+__global__ __launch_bounds__(256) void csr_check_kernel(const int32_t *__restrict__ row_ptr,
+                                                        const int32_t *__restrict__ col_idx, long long nnz,
+                                                        long long B, int d0, unsigned int *bad)
+{
+    const long long step = (long long)gridDim.x * 256;
+    const long long t0 = (long long)blockIdx.x * 256 + threadIdx.x;
+    unsigned int n = 0;
+    for (long long i = t0; i < nnz; i += step) n += (unsigned int)col_idx[i] >= (unsigned int)d0;
+    for (long long i = t0; i <= B; i += step) {
+        const int v = row_ptr[i];
+        n += (i == 0 && v != 0) || (i == B && v != nnz) || (i > 0 && v < row_ptr[i - 1]) || v < 0 || v > nnz;
+    }
+    if (n) atomicAdd(bad, n);
+}
+
+hipError_t launch_csr_check(const int32_t *row_ptr, const int32_t *col_idx, long long nnz, long long B, int d0,
+                            unsigned int *bad, hipStream_t stream)
+{
+    long long b = ((nnz > B ? nnz : B + 1) + 255) / 256;
+    if (b > 1024) b = 1024;
+    if (b < 1) b = 1;
+    csr_check_kernel<<<(unsigned)b, 256, 0, stream>>>(row_ptr, col_idx, nnz, B, d0, bad);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_u32(unsigned int *p, long long n, unsigned int v, hipStream_t stream)
 {
     long long b = (n + 255) / 256;

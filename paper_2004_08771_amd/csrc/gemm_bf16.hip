@@ -982,17 +982,25 @@ hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, c
     return launch_shape_bf16<128, 128, 64>(kind, a, stream, ev);
 }
 
-int gemm_bf16_dw_splits(int M, int N, int K, long long lda, long long ldb)
+int gemm_bf16_dw_splits_cap(int M, int N, int K)
 {
-    if ((unsigned long long)M * (unsigned long long)lda * 2 >= (1ull << 32) ||
-        (unsigned long long)N * (unsigned long long)ldb * 2 >= (1ull << 32) || (lda & 7) || (ldb & 7))
-        return 1;
     const long long tiles = (long long)((M + DMA_BM - 1) / DMA_BM) * ((N + DMA_BN - 1) / DMA_BN);
     if (tiles > 128 || K < 2048) return 1;
     long long s = 256 / tiles;  // fill the chip once
     if (s > 8) s = 8;
     if (s > K / 1024) s = K / 1024;  // at least 16 k-tiles per slice
     return s < 2 ? 1 : (int)s;
+}
+
+int gemm_bf16_dw_splits(int M, int N, int K, long long lda, long long ldb)
+{
+    // the LDS-direct kernel (the only one that splits) addresses each operand with 32-bit byte
+    // offsets: an operand beyond 4 GiB is not split.  This makes the count non-monotonic in K
+    // (lda and ldb grow with the batch), which is why buffers are sized with ..._cap.
+    if ((unsigned long long)M * (unsigned long long)lda * 2 >= (1ull << 32) ||
+        (unsigned long long)N * (unsigned long long)ldb * 2 >= (1ull << 32) || (lda & 7) || (ldb & 7))
+        return 1;
+    return gemm_bf16_dw_splits_cap(M, N, K);
 }
 
 hipError_t launch_dw_reduce(const float *partial, int splits, long long stride, long long count, float *master,

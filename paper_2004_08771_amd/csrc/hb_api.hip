@@ -142,6 +142,7 @@ struct hb_model {
     int32_t *d_cursor = nullptr;  // per-block column histograms / cursors of the CSC build
     int32_t *d_csc_row = nullptr;
     float *dw_partial = nullptr;         // bf16 mode: slices of a split weight gradient (largest layer that splits)
+    size_t dw_partial_cap = 0;           // its capacity in floats
     void *worker_state = nullptr;        // staging buffers of the worker loop (worker.hip), kept between epochs
     void (*worker_state_free)(void *) = nullptr;
     int4 *d_chunk_desc = nullptr;        // descriptor of each gradient chunk (capacity follows the CSC arrays)
@@ -212,7 +213,7 @@ void release_device(hb_model *m)
 
 // Events for one profiled dispatch (empty when profiling is off or events run out).
 LaunchEvents prof_begin(hb_model *m, int kind, int layer, int64_t M, int64_t N, int64_t K, double flops,
-                        double bytes)
+                        double bytes, double cache_bytes = 0.0)
 {
     LaunchEvents ev;
     if (!m->prof_on) return ev;
@@ -227,7 +228,7 @@ LaunchEvents prof_begin(hb_model *m, int kind, int layer, int64_t M, int64_t N, 
         }
     }
     hb_model::ProfRec r;
-    r.info = hb_kernel_stat{kind, layer, M, N, K, 1, 0.0, flops, bytes};
+    r.info = hb_kernel_stat{kind, layer, M, N, K, 1, 0.0, flops, bytes, cache_bytes};
     r.start = e[0];
     r.stop = e[1];
     m->prof.push_back(r);
@@ -351,11 +352,17 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sp.d1 = m->dims[1];
             sp.act = (L > 1) ? m->act : ACT_NONE;
             sp.vec = (m->dims[1] % 4 == 0) && aligned16(sp.bias);
-            const double gather = (double)in.nnz * (8.0 + 4.0 * m->dims[1]);
+            // algorithmic HBM bytes: the CSR arrays, each touched weight row once (at most
+            // min(nnz, d_0) rows), the output; the row gathers themselves (one weight row per stored
+            // entry) are cache traffic and reported apart
+            const double touched_rows = (double)(in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
+            const double gather = (double)in.nnz * 4.0 * m->dims[1];
             HB_HIP(launch_spmm_fwd(sp, B, st,
                                    prof_begin(m, HB_K_SPMM_FWD, 1, B, m->dims[1], in.nnz,
                                               2.0 * in.nnz * m->dims[1],
-                                              gather + 4.0 * B * (m->dims[1] + 1.0))));
+                                              8.0 * in.nnz + 4.0 * (B + 1.0) + 4.0 * touched_rows * m->dims[1] +
+                                                  4.0 * B * (m->dims[1] + 1.0),
+                                              gather)));
             continue;
         }
         GemmArgs g = {};
@@ -559,7 +566,8 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
                                     prof_begin(m, HB_K_SPARSE_DW, 1, m->dims[1], m->dims[0], in.nnz,
                                                2.0 * in.nnz * m->dims[1],
                                                4.0 * B * m->dims[1] + 8.0 * in.nnz +
-                                                   8.0 * touched * m->dims[1])));
+                                                   8.0 * touched * m->dims[1],
+                                               (double)in.nnz * 4.0 * m->dims[1])));
             continue;
         }
         if (!dw_done)
@@ -710,7 +718,10 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.Ct_bf16 = m->shadow_t[l];
             g.ldct = m->ld8[l];
         }
-        const int sp = m->dw_partial ? gemm_bf16_dw_splits(g.M, g.N, g.K, g.lda, g.ldb) : 1;
+        int sp = m->dw_partial ? gemm_bf16_dw_splits(g.M, g.N, g.K, g.lda, g.ldb) : 1;
+        // never more slices than the buffer allocated at configure time holds
+        if (sp > 1 && (size_t)sp * (size_t)g.M * (size_t)g.N > m->dw_partial_cap)
+            sp = (int)(m->dw_partial_cap / ((size_t)g.M * (size_t)g.N));
         if (sp > 1) {
             // too few tiles for the chip: slices of the batch give partial products, summed (and
             // applied to the master weights) by a second kernel; the bf16 copies are refreshed after
@@ -785,6 +796,22 @@ int validate_csr_call(hb_model *m, const int32_t *rp, const int32_t *ci, const f
     if (nnz < 0 || nnz > 0x7fffffffLL || nnz > B * (int64_t)m->dims[0])
         return fail(HB_ERR_INVALID, "nnz = %lld is outside [0, min(2^31 - 1, B * d_0)]", (long long)nnz);
     if (nnz > 0 && (!ci || !va)) return fail(HB_ERR_INVALID, "d_col_idx / d_vals is NULL");
+    // HB_CHECK_INDICES=1 (debug aid, costs a pass over the CSR arrays and a synchronisation per
+    // call): a column index outside [0, d_0) or a malformed row pointer is an error here, before
+    // any kernel dereferences them, instead of an out-of-bounds access
+    static const bool check_indices = getenv("HB_CHECK_INDICES") && atoi(getenv("HB_CHECK_INDICES")) != 0;
+    if (check_indices) {
+        unsigned int *d_bad = reinterpret_cast<unsigned int *>(m->d_loss + 3);
+        unsigned int bad = 0;
+        HB_HIP(launch_fill_u32(d_bad, 1, 0u, m->stream));
+        HB_HIP(launch_csr_check(rp, ci, nnz, B, m->dims[0], d_bad, m->stream));
+        HB_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, m->stream));
+        HB_HIP(hipStreamSynchronize(m->stream));
+        if (bad)
+            return fail(HB_ERR_INVALID,
+                        "the CSR batch has %u defects (column index outside [0, %d), or a row pointer that does not "
+                        "start at 0, decreases, or does not end at nnz = %lld)", bad, m->dims[0], (long long)nnz);
+    }
     in->row_ptr = rp;
     in->col_idx = ci;
     in->vals = va;
@@ -905,7 +932,15 @@ int hb_profile_read(hb_model *m, hb_kernel_stat *out, int32_t cap, int32_t *n_ou
     *n_out = n;
     return HB_OK;
 }
-const char *hb_version(void) { return "hb-mlp 0.1 (gfx950)"; }
+const char *hb_version(void) { return "hb-mlp 0.2 (gfx950)"; }
+
+int32_t hb_plan_bf16_dw_slices(int32_t d_out, int32_t d_in, int64_t B, int32_t capacity)
+{
+    if (d_out < 1 || d_in < 1 || B < 1 || B > MAX_BATCH) return 0;
+    if (capacity) return gemm_bf16_dw_splits_cap(d_out, d_in, (int)B);
+    const long long ldB = round_up((int)B, 8);
+    return gemm_bf16_dw_splits(d_out, d_in, (int)B, ldB, ldB);
+}
 
 hb_model *hb_mlp_create(const int32_t *layer_dims, int32_t n_dims, int activation, int loss)
 {
@@ -1056,15 +1091,16 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
             m->delta_t[i] = p;
         }
         {
-            // weight gradients with too few 256 x 256 tiles are split over the batch (most slices
-            // at max_B: the count does not decrease with the batch)
+            // weight gradients with too few 256 x 256 tiles are split over the batch: room for the
+            // largest number of slices any batch size up to max_B can ask for, in any layer
             size_t need = 0;
             for (int l = 1; l <= L; ++l) {
-                const int sp = gemm_bf16_dw_splits(m->dims[l], m->dims[l - 1], (int)max_B, ldB, ldB);
+                const int sp = gemm_bf16_dw_splits_cap(m->dims[l], m->dims[l - 1], (int)max_B);
                 const size_t n = (sp > 1) ? (size_t)sp * m->dims[l] * m->dims[l - 1] : 0;
                 if (n > need) need = n;
             }
             if (need > 0 && rc == HB_OK) rc = dev_alloc(m, &m->dw_partial, need);
+            if (rc == HB_OK) m->dw_partial_cap = need;
         }
     }
     if (m->sparse && rc == HB_OK) {
@@ -1152,6 +1188,39 @@ int hb_model_get_params(hb_model *m, float *host_flat)
     HB_HIP(hipMemcpyAsync(host_flat, m->d_params, sizeof(float) * (size_t)m->P, hipMemcpyDeviceToHost,
                           m->stream));
     HB_HIP(hipStreamSynchronize(m->stream));
+    return HB_OK;
+}
+
+int hb_model_get_activations(hb_model *m, int32_t layer, int64_t B, float *host_out)
+{
+    int rc = check_handle(m, true);
+    if (rc != HB_OK) return rc;
+    if (!host_out) return fail(HB_ERR_INVALID, "host_out is NULL");
+    if (layer < 1 || layer >= m->L)
+        return fail(HB_ERR_INVALID, "layer = %d is not a hidden layer (1 .. %d)", layer, m->L - 1);
+    if (B < 1 || B > m->max_B)
+        return fail(HB_ERR_INVALID, "B = %lld is outside [1, max_B = %lld]", (long long)B, (long long)m->max_B);
+    const size_t d = (size_t)m->dims[layer];
+    if (m->dtype == HB_F32) {
+        HB_HIP(hipMemcpy2DAsync(host_out, d * sizeof(float), m->acts[layer], (size_t)m->ld[layer] * sizeof(float),
+                                d * sizeof(float), (size_t)B, hipMemcpyDeviceToHost, m->stream));
+        HB_HIP(hipStreamSynchronize(m->stream));
+        return HB_OK;
+    }
+    // bf16 storage: fetch the two-byte values and widen them on the host (exact)
+    std::vector<unsigned short> tmp;
+    try {
+        tmp.resize((size_t)B * d);
+    } catch (const std::bad_alloc &) {
+        return fail(HB_ERR_ALLOC, "out of host memory");
+    }
+    HB_HIP(hipMemcpy2DAsync(tmp.data(), d * 2, m->act_bf[layer], (size_t)m->ld8[layer] * 2, d * 2, (size_t)B,
+                            hipMemcpyDeviceToHost, m->stream));
+    HB_HIP(hipStreamSynchronize(m->stream));
+    for (size_t i = 0; i < tmp.size(); ++i) {
+        const uint32_t u = (uint32_t)tmp[i] << 16;
+        memcpy(&host_out[i], &u, 4);
+    }
     return HB_OK;
 }
 

@@ -108,8 +108,11 @@ struct GemmBf16Args {
 hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream,
                             const LaunchEvents &ev = LaunchEvents());
 // Slices for a weight-gradient product whose 256 x 256 tiles would leave half of the CUs (or
-// more) idle; 1 = do not split.  Non-decreasing in K.
+// more) idle; 1 = do not split.  gemm_bf16_dw_splits_cap(M, N, max_K) is the largest count
+// gemm_bf16_dw_splits returns for any K <= max_K and any leading dimensions (it is
+// non-decreasing in K): the figure to size the slice buffer with.
 int gemm_bf16_dw_splits(int M, int N, int K, long long lda, long long ldb);
+int gemm_bf16_dw_splits_cap(int M, int N, int K);
 // out[i] = sum_s partial[s * stride + i]  (grad != null: written there)  or  master[i] -= lr * sum
 hipError_t launch_dw_reduce(const float *partial, int splits, long long stride, long long count, float *master,
                             float *grad, float lr, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
@@ -202,6 +205,10 @@ hipError_t launch_merge(float *D, float *H, long long n, float w, hipStream_t st
 hipError_t launch_fill_u32(unsigned int *p, long long n, unsigned int v, hipStream_t stream);
 // adds the number of out-of-domain labels to *bad (device counter); debug aid
 hipError_t launch_label_check(const int32_t *y, long long B, int K, int loss, unsigned int *bad, hipStream_t stream);
+// adds the number of defects of a CSR batch to *bad: column indices outside [0, d0), row pointer
+// not starting at 0 / decreasing / not ending at nnz; debug aid
+hipError_t launch_csr_check(const int32_t *row_ptr, const int32_t *col_idx, long long nnz, long long B, int d0,
+                            unsigned int *bad, hipStream_t stream);
 
 
 // ---------------------------------------------------------------- CSR first layer

@@ -358,8 +358,8 @@ struct CsrHost {
 // Sends rows [begin, begin + count) of host-resident CSR data into staging buffer `buf` on the
 // copy stream: the row-pointer slice rebased to 0, column indices and values as they are.  The
 // caller has seen buffer buf's last reader finish.
-int send_csr_rows(const char *who, Staging &st, hipStream_t model_stream, const CsrHost &csr, int buf, int64_t begin,
-                  int64_t count)
+int send_csr_rows(const char *who, Staging &st, hipStream_t model_stream, const CsrHost &csr, int d0, int buf,
+                  int64_t begin, int64_t count)
 {
     const int64_t base = csr.row_ptr[begin];
     const int64_t nnz = csr.row_ptr[begin + count] - base;
@@ -382,6 +382,19 @@ int send_csr_rows(const char *who, Staging &st, hipStream_t model_stream, const 
             return hb::set_error(HB_ERR_INVALID, "%s: host_row_ptr is not non-decreasing at row %lld", who,
                                  (long long)(begin + i));
         rp[i] = (int32_t)off;
+    }
+    // the kernels trust column indices: one pass over the batch's indices on the host (it walks
+    // them anyway to copy them) turns an index outside [0, d_0) into an error
+    {
+        const int32_t *ci = csr.col_idx + base;
+        unsigned int bad = 0;
+        for (int64_t i = 0; i < nnz; ++i) bad |= (unsigned int)((unsigned int)ci[i] >= (unsigned int)d0);
+        if (bad) {
+            int64_t i = 0;
+            while ((unsigned int)ci[i] < (unsigned int)d0) ++i;
+            return hb::set_error(HB_ERR_INVALID, "%s: column index %d of stored entry %lld is outside [0, %d)", who,
+                                 (int)ci[i], (long long)(base + i), d0);
+        }
     }
     st.nnz[buf] = nnz;
     WK_HIP(hipMemcpyAsync(st.rp[buf], rp, sizeof(int32_t) * (size_t)(count + 1), hipMemcpyHostToDevice, st.copy));
@@ -530,7 +543,7 @@ static int run_epoch(const char *who, hb_model *m, hb_sched *s, int32_t worker, 
         // iteration: 215-490 us per iteration against 148 with this host-side wait).
         WK_HIP(hipEventSynchronize(st.consumed[buf]));
         if (csr) {
-            const int rc_s = send_csr_rows(who, st, mi.stream, *csr, buf, begin, *count);
+            const int rc_s = send_csr_rows(who, st, mi.stream, *csr, mi.d0, buf, begin, *count);
             if (rc_s != HB_OK) return rc_s;
         } else {
             WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,
@@ -708,7 +721,7 @@ static int eval_loss(const char *who, hb_model *m, const void *host_X, const Csr
     auto send = [&](int buf, int64_t begin, int64_t count) -> int {
         WK_HIP(hipEventSynchronize(st.consumed[buf]));  // host-side, see the worker loop
         if (csr) {
-            const int rc_s = send_csr_rows(who, st, mi.stream, *csr, buf, begin, count);
+            const int rc_s = send_csr_rows(who, st, mi.stream, *csr, mi.d0, buf, begin, count);
             if (rc_s != HB_OK) return rc_s;
         } else {
             WK_HIP(hipMemcpyAsync(st.x[buf], static_cast<const unsigned char *>(host_X) + row_bytes * (size_t)begin,

@@ -78,3 +78,23 @@ def test_configure_validates_before_any_device_call():
         hb.lib().hb_mlp_configure.restype  # keep the symbol referenced
         binding._check(hb.lib().hb_mlp_configure(None, 0, 16, 0, None))
     assert e.value.code == hb.HB_ERR_INVALID
+
+
+def test_bf16_weight_gradient_slice_buffer_covers_every_batch_size():
+    """The slice buffer of the bf16 weight gradient is sized at configure time for max_B; the
+    number of slices a smaller batch asks for must never exceed that (it is not monotonic in B:
+    an operand beyond 4 GiB is not split at all, so a wide layer can ask for 1 slice at max_B and
+    for several at a smaller B)."""
+    plan = hb.lib().hb_plan_bf16_dw_slices
+    grid_B = [1, 100, 1024, 2047, 2048, 3000, 4096, 8192, 16384, 1 << 16, 1 << 18, 1 << 20, 1 << 21, 1 << 22]
+    shapes = [(128, 128), (2048, 2048), (4096, 4096), (4096, 2048), (1000, 4096), (512, 54), (300, 300), (8192, 256)]
+    for d_out, d_in in shapes:
+        for max_B in grid_B:
+            cap = plan(d_out, d_in, max_B, 1)
+            assert cap >= 1
+            for B in [b for b in grid_B if b <= max_B] + [max_B - 1 if max_B > 1 else 1]:
+                got = plan(d_out, d_in, B, 0)
+                assert 1 <= got <= cap, (d_out, d_in, max_B, B, got, cap)
+    # the case that overflowed a buffer sized from the count at max_B: 2048 x 2048 at max_B = 2^21
+    assert plan(2048, 2048, 1 << 21, 0) == 1 and plan(2048, 2048, 8192, 0) == 4 and plan(2048, 2048, 1 << 21, 1) >= 4
+    assert plan(0, 5, 5, 0) == 0 and plan(5, 5, 0, 1) == 0

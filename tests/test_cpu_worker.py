@@ -122,3 +122,21 @@ def test_cpu_worker_rejects_bad_arguments():
         hb.cpu_worker_run_epoch(s, 0, (4, 3, 5), 0, hi.LOSS_LOGISTIC, X, y, H, 0.01)   # logistic needs d_L <= 2
     with pytest.raises(hb.HbError):
         hb.cpu_worker_run_epoch(s, 0, dims, 0, 0, None, y, H, 0.01)
+
+
+def test_label_outside_its_domain_is_an_error_not_a_stray_read():
+    import paper_2004_08771_amd as hb
+    dims = (6, 5, 3)
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((32, 6)).astype(np.float32)
+    model = hi.xavier_uniform_params(dims, rng, 0.1)
+    for loss, bad in ((hb.HB_LOSS_SOFTMAX_CE, 3), (hb.HB_LOSS_SOFTMAX_CE, -1), (hb.HB_LOSS_LOGISTIC, 0)):
+        d = dims if loss == hb.HB_LOSS_SOFTMAX_CE else (6, 5, 2)
+        y = np.ones(32, np.int32)
+        y[20] = bad
+        s = hb.Sched(32, [8], [8], [8])
+        m = hi.xavier_uniform_params(d, rng, 0.1)
+        with pytest.raises(hb.HbError) as e:
+            hb.cpu_worker_run_epoch(s, 0, d, hb.HB_ACT_SIGMOID, loss, X, y, m, 0.01)
+        assert e.value.code == hb.HB_ERR_INVALID
+        assert s.remaining() == 8          # batches 0 and 1 ran, the batch holding row 20 was refused

@@ -357,6 +357,18 @@ def test_csr_worker_buffers_grow_and_errors():
         m.worker_run_epoch_csr(s3, 0, bad, ci, va, y, 1e-3)
     with pytest.raises(hb.HbError):
         m.worker_run_epoch_csr(hb.Sched(n, [32], [32], [32]), 0, None, ci, va, y, 1e-3)
+    # a column index outside [0, d_0) is refused on the host, before the batch that holds it is sent
+    # (the kernels trust indices); the batches before it have been applied
+    for bad_value in (dims[0], -1):
+        bad_ci = ci.copy()
+        bad_ci[int(rp[40]) + 1] = bad_value             # row 40 = second batch of 32
+        s4 = hb.Sched(n, [32], [32], [32])
+        with pytest.raises(hb.HbError) as e:
+            m.worker_run_epoch_csr(s4, 0, rp, bad_ci, va, y, 1e-3)
+        assert e.value.code == hb.HB_ERR_INVALID and "column index" in str(e.value)
+        with pytest.raises(hb.HbError) as e:
+            m.worker_eval_loss_csr(rp, bad_ci, va, y, n, 256)
+        assert e.value.code == hb.HB_ERR_INVALID
     # dense and CSR loops are not interchangeable
     X = np.zeros((n, dims[0]), dtype=np.float32)
     with pytest.raises(hb.HbError):
