@@ -5,8 +5,9 @@
 
 A "step" is one hb_batch_step_async call over one batch of synthetic rows that are already
 resident in HBM; successive steps take successive contiguous row ranges of the dataset
-(the way the coordinator hands out batches, Algorithm 1 / 2 of the paper).  Prints ONE JSON
-line: throughput in training examples/s, the roofline figures of the dominant kernel
+(the way the coordinator hands out batches, Algorithm 1 / 2 of the paper).  After W warm-up
+steps (and at least half a second of them) five regions of exactly K steps are timed between
+synchronisations and the median is reported.  Prints ONE JSON line: throughput in training examples/s, the roofline figures of the dominant kernel
 (per-dispatch execution times read from events attached to the kernel launches in a second,
 profiled pass over the same steps), and the fp64 CPU oracle timed on a bounded sample of
 the same workload.
@@ -25,6 +26,8 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+WARM_SECONDS = 0.5     # untimed steps before the timed regions, at least
+REPEATS = 5            # timed regions of --steps steps each; the median is reported
 
 
 def parse_args():
@@ -152,18 +155,33 @@ def main():
         del src, dst
 
     d_loss = torch.zeros(1, dtype=torch.float32, device="cuda")
-    for i in range(args.warmup):
-        one_step(i, d_loss)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(args.warmup + i, d_loss)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    note(f"{args.steps} timed steps: {1e3 * elapsed / args.steps:.4f} ms per step")
+    # Warm-up: the W steps asked for, and then more until at least WARM_SECONDS of steps have run --
+    # a chip that has been idle takes a few hundred steps to reach its working clocks, and a
+    # timed region of a few milliseconds after a handful of steps measures that ramp, not the step.
+    it = 0
+    t_warm = time.perf_counter()
+    while it < args.warmup or time.perf_counter() - t_warm < WARM_SECONDS:
+        for _ in range(max(1, min(args.warmup, 50))):
+            one_step(it, d_loss)
+            it += 1
+        torch.cuda.synchronize()
+    warm_steps = it
+    # REPEATS timed regions of exactly K steps each, bracketed by synchronisations; the median counts
+    region_ms = []
+    for _ in range(REPEATS):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            one_step(it + i, d_loss)
+        torch.cuda.synchronize()
+        region_ms.append(1e3 * (time.perf_counter() - t0) / args.steps)
+        it += args.steps
+    ms_per_step = sorted(region_ms)[len(region_ms) // 2]
+    elapsed = 1e-3 * ms_per_step * args.steps
+    note(f"{warm_steps} warm-up steps, then {REPEATS} x {args.steps} timed steps: "
+         + ", ".join(f"{v:.4f}" for v in region_ms) + f" ms per step; median {ms_per_step:.4f}")
     last_loss = float(d_loss.item())
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = args.steps * B / elapsed
+    value = B / (1e-3 * ms_per_step)
     flops = step_flops(cfg.dims, B, mean_nnz)
 
     # ---- the synchronous entry point (hb_batch_step: the host waits for every step's loss),
@@ -174,16 +192,17 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for i in range(n_sync):
-            j = (args.warmup + args.steps + i) % n_batches
+            j = (it + i) % n_batches
             model.batch_step(x_ptr[j], y_ptr[j], B, lr)
         sync_ms_per_step = 1e3 * (time.perf_counter() - t1) / n_sync
 
     # ---- second pass over the same steps with per-dispatch events -> per-kernel times
     roofline, kernels = None, []
     if not args.no_profile:
+        n_prof = min(max(args.steps, 100), 1000)   # enough launches for a stable average
         model.profile_enable(True)
-        for i in range(args.steps):
-            one_step(args.warmup + i, d_loss)
+        for i in range(n_prof):
+            one_step(it + i, d_loss)
         stats = model.profile_read(512)
         model.profile_enable(False)
         for s in stats:
@@ -196,6 +215,8 @@ def main():
                 "gbs": round(s["bytes_per_launch"] / (avg_us * 1e-6) / 1e9, 1) if avg_us > 0 else None,
                 "_total_ms": s["total_ms"], "_flops": s["flops_per_launch"], "_bytes": s["bytes_per_launch"],
             })
+            if s["cache_bytes_per_launch"] > 0 and avg_us > 0:     # CSR row gathers: cache-level rate
+                kernels[-1]["gathered_gbs"] = round(s["cache_bytes_per_launch"] / (avg_us * 1e-6) / 1e9, 1)
         total = sum(k["_total_ms"] for k in kernels) or 1.0
         for k in kernels:
             k["share"] = round(k["_total_ms"] / total, 4)
@@ -222,13 +243,15 @@ def main():
         roofline.update({"traffic": None, "kernel": name, "shape": [M, N, K],
                          "avg_kernel_us": round(avg_s * 1e6, 3), "launches": g["n"],
                          "share_of_kernel_time": round(g["ms"] / total, 4),
-                         "sum_kernel_us_per_step": round(1e3 * total / args.steps, 2)})
+                         "sum_kernel_us_per_step": round(1e3 * total / n_prof, 2)})
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very
         # command (measured offline, scaled by a plain copy kernel; see profiles/)
         traffic_file = os.path.join(ROOT, "profiles", f"hbm_traffic_config{args.config}_B{B}.json")
         if os.path.exists(traffic_file):
             with open(traffic_file) as f:
                 roofline["traffic"] = json.load(f).get("bytes_per_launch", {}).get(name)
+                roofline["traffic_source"] = os.path.relpath(traffic_file, ROOT) + \
+                    " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command; not measured in this run)"
         for k in kernels:
             for key in ("_total_ms", "_flops", "_bytes"):
                 k.pop(key)
@@ -327,8 +350,10 @@ def main():
         "vs_baseline": None,
         "dtype": dtype_name,
         "data": "synthetic",
-        "config": {"workload": f"config {args.config}: {cfg.name}", "layer_dims": list(cfg.dims),
-                   "batch": B, "dataset_rows": rows, "lr": lr, "sparse_first_layer": cfg.sparse},
+        "config": {"workload": f"config {args.config}: {cfg.name}", "batch": B, "dataset_rows": rows, "lr": lr,
+                   "sparse_first_layer": cfg.sparse},
+        "timing": {"warmup_steps_run": warm_steps, "regions_ms_per_step": [round(v, 5) for v in region_ms],
+                   "what": f"median of {REPEATS} regions of {args.steps} steps after at least {WARM_SECONDS} s of warm-up"},
         "step_tflops": round(flops / (elapsed / args.steps) / 1e12, 3),
         "step_frac_of_mfma_peak": round(flops / (elapsed / args.steps) / 1e12 / PEAK_TFLOPS[dtype_name], 4),
         "last_loss": last_loss,
