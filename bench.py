@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
     ap.add_argument("--no-from-host", action="store_true",
                     help="skip the worker-loop leg (same steps with the dataset in page-locked host memory)")
+    ap.add_argument("--warm-seconds", type=float, default=WARM_SECONDS,
+                    help="warm-up lasts at least this long (0 for runs under a counter-collecting profiler)")
+    ap.add_argument("--repeats", type=int, default=REPEATS, help="timed regions of --steps steps (the median counts)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (reference for HBM byte counters)")
     return ap.parse_args()
@@ -160,7 +163,7 @@ def main():
     # timed region of a few milliseconds after a handful of steps measures that ramp, not the step.
     it = 0
     t_warm = time.perf_counter()
-    while it < args.warmup or time.perf_counter() - t_warm < WARM_SECONDS:
+    while it < args.warmup or time.perf_counter() - t_warm < args.warm_seconds:
         for _ in range(max(1, min(args.warmup, 50))):
             one_step(it, d_loss)
             it += 1
@@ -168,7 +171,7 @@ def main():
     warm_steps = it
     # REPEATS timed regions of exactly K steps each, bracketed by synchronisations; the median counts
     region_ms = []
-    for _ in range(REPEATS):
+    for _ in range(max(1, args.repeats)):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -178,7 +181,7 @@ def main():
         it += args.steps
     ms_per_step = sorted(region_ms)[len(region_ms) // 2]
     elapsed = 1e-3 * ms_per_step * args.steps
-    note(f"{warm_steps} warm-up steps, then {REPEATS} x {args.steps} timed steps: "
+    note(f"{warm_steps} warm-up steps, then {len(region_ms)} x {args.steps} timed steps: "
          + ", ".join(f"{v:.4f}" for v in region_ms) + f" ms per step; median {ms_per_step:.4f}")
     last_loss = float(d_loss.item())
     value = B / (1e-3 * ms_per_step)
@@ -353,7 +356,7 @@ def main():
         "config": {"workload": f"config {args.config}: {cfg.name}", "batch": B, "dataset_rows": rows, "lr": lr,
                    "sparse_first_layer": cfg.sparse},
         "timing": {"warmup_steps_run": warm_steps, "regions_ms_per_step": [round(v, 5) for v in region_ms],
-                   "what": f"median of {REPEATS} regions of {args.steps} steps after at least {WARM_SECONDS} s of warm-up"},
+                   "what": f"median of {len(region_ms)} regions of {args.steps} steps after at least {args.warm_seconds} s of warm-up"},
         "step_tflops": round(flops / (elapsed / args.steps) / 1e12, 3),
         "step_frac_of_mfma_peak": round(flops / (elapsed / args.steps) / 1e12 / PEAK_TFLOPS[dtype_name], 4),
         "last_loss": last_loss,

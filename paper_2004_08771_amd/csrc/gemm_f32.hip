@@ -465,7 +465,18 @@ __global__ __launch_bounds__(NT) void gemm_f32_bwd_pair_kernel(GemmArgs da, Gemm
     const int b = blockIdx.x;
     if (b < n_dw) {  // the weight-gradient blocks are the longer ones: they are dispatched first
         const int tiles = dw.tiles_m * dw.tiles_n;
-        gemm_f32_tile<DW_BM, 64, 32, 2, false, false, GEMM_DW>(dw, smem, xcd_tile_order(b % tiles, tiles), b / tiles);
+        if ((dw.splits & 7) == 0) {
+            // Workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own.  Slice s of
+            // the batch is given to XCD s % 8, all of its output tiles: the XCD then reads only its
+            // slices' rows of D_l and A_{l-1}, once.  (Dealt out tile by tile, every XCD read every
+            // row of A_{l-1}: 8 x 8.4 MB at B = 4096 for 8.4 MB of activations.)  The backward-data
+            // blocks below give XCD x a contiguous run of row tiles -- at the usual sizes the very
+            // rows of slice x -- so both products find D_l and A_{l-1} in the same L2.
+            const int q = b >> 3;
+            gemm_f32_tile<DW_BM, 64, 32, 2, false, false, GEMM_DW>(dw, smem, q % tiles, (b & 7) + 8 * (q / tiles));
+        } else {
+            gemm_f32_tile<DW_BM, 64, 32, 2, false, false, GEMM_DW>(dw, smem, xcd_tile_order(b % tiles, tiles), b / tiles);
+        }
     } else {
         const int n_da = gridDim.x - n_dw;
         gemm_f32_tile<64, 64, 32, 2, true, false, GEMM_DA>(da, smem, xcd_tile_order(b - n_dw, n_da), 0);
