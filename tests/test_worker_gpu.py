@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 import hb_inputs as hi
+from parity_checks import assert_close
 import oracle
 from oracle.sched import AdaptiveSchedule
 
@@ -50,6 +51,11 @@ def _rel(a, b):
     return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
 
 
+def _close(dims, got, ref, tol, what="parameters"):
+    """Per tensor: relative L2 and the element-wise bound of tests/parity_checks.py."""
+    assert_close(dims, np.asarray(got), np.asarray(ref), tol, what)
+
+
 def test_single_worker_epoch_matches_sequential_oracle_steps():
     import paper_2004_08771_amd as hb
     import torch
@@ -70,7 +76,7 @@ def test_single_worker_epoch_matches_sequential_oracle_steps():
     assert (u, steps) == (ref_u, ref_steps) == (64.0, 64)
     assert s.remaining() == 40
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
+    _close(dims, got, ref_p, TOL)
     # second epoch: the update count carries over, the data starts again
     s.new_epoch()
     u2, steps2, _ = m.worker_run_epoch(s, 0, hX, hy, lr_pe, updates=u)
@@ -104,7 +110,7 @@ def test_worker_epoch_at_the_benchmark_shape():
     m.destroy()
     assert (u, steps) == (ref_u, ref_steps) == (2.0, 2) and s.remaining() == 40
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
+    _close(cfg.dims, got, ref_p, TOL)
     assert _rel(got - params, ref_p - params) <= 1e-3   # the two updates themselves
     assert np.array_equal(H.numpy(), got)               # the last push carried the final replica
 
@@ -145,8 +151,8 @@ def test_adaptive_batch_sizes_pageable_memory_and_merging():
     assert (u, steps) == (ref_u, ref_steps)
     assert sl.batch_size(1) == 50 and sl.remaining() == so.remaining()
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
-    assert _rel(H, ref_H) <= TOL
+    _close(dims, got, ref_p, TOL)
+    _close(dims, H, ref_H, TOL)
 
 
 @pytest.mark.parametrize("locked", [True, False])
@@ -178,8 +184,8 @@ def test_asynchronous_push_of_the_replica(locked):
     m.get_params(got)
     assert (u, steps) == (ref_u, ref_steps) == (10.0, 10)
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
-    assert _rel(H.numpy(), ref_H) <= TOL
+    _close(dims, got, ref_p, TOL)
+    _close(dims, H.numpy(), ref_H, TOL)
     assert np.array_equal(H.numpy(), got)           # the closing push carried the final replica, bit for bit
     # every push of a longer run lands in order: push after every step, host model = final replica
     s.new_epoch()
@@ -214,7 +220,7 @@ def test_deep_copy_of_the_global_model_every_other_step():
     assert np.array_equal(H, host0)                 # the global model is only read
     assert np.array_equal(got, host0)               # 7 steps: the closing merge copies it once more
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
+    _close(dims, got, ref_p, TOL)
 
 
 def _replay_csr(sched, worker, dims, act, loss, params, rp, ci, va, y, lr_pe, host_model=None, merge_every=0, w=1.0):
@@ -291,9 +297,9 @@ def test_csr_worker_epoch_matches_sequential_oracle_steps(merge):
     assert (u, steps) == (ref_u, ref_steps)
     assert sl.remaining() == so.remaining()
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
+    _close(dims, got, ref_p, TOL)
     if H is not None:
-        assert _rel(H, ref_H) <= TOL
+        _close(dims, H, ref_H, TOL)
     m.destroy()
 
 
@@ -319,7 +325,7 @@ def test_csr_worker_epoch_at_the_benchmark_shape():
     m.destroy()
     assert (u, steps) == (ref_u, ref_steps) == (2.0, 2) and s.remaining() == 50
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
-    assert _rel(got, ref_p) <= TOL
+    _close(cfg.dims, got, ref_p, TOL)
     assert _rel(got - params, ref_p - params) <= 1e-3   # the two updates themselves
 
 
@@ -347,7 +353,7 @@ def test_csr_worker_buffers_grow_and_errors():
             l, p = oracle.batch_step_csr(dims, act, loss, p, brp, bci, bva, y[k * b:(k + 1) * b],
                                          float(np.float32(1e-3) * np.float32(b)))
             ref_loss += l if reps else 0.0
-    assert _rel(got, p) <= TOL
+    _close(dims, got, p, TOL)
     assert abs(loss_sum - ref_loss) <= TOL * abs(ref_loss)
     # a row pointer that decreases is refused before anything is copied
     bad = rp.copy()
@@ -409,7 +415,7 @@ def test_bf16_worker_epoch_follows_the_oracle_with_rounded_operands():
     m.destroy()
     assert (u, steps) == (8.0, 8) and s.remaining() == 100
     assert abs(loss_sum - ref_loss) <= 2e-2 * abs(ref_loss)
-    assert _rel(got, p) <= 2e-2
+    _close(dims, got, p, 2e-2)
     assert _rel(got - params, p - params) <= 5e-2      # the updates themselves, not only the weights they barely move
 
 
@@ -586,7 +592,7 @@ def test_two_gpu_workers_on_their_own_streams_share_an_epoch():
         p1 = np.empty_like(params)
         m.get_params(p1)
         assert abs(l - l_ref) <= TOL * abs(l_ref)
-        assert _rel(p1, p_ref) <= TOL
+        _close(dims, p1, p_ref, TOL)
         m.destroy()
 
 
