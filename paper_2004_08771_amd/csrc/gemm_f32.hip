@@ -209,7 +209,14 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
     // tiles that lie inside the matrix are loaded without guards (uniform per workgroup)
     const bool a_in = (m0 + BM <= a.M), b_in = (n0 + BN <= a.N);
 
-    float colsum = 0.f;  // DW only: column sums of the A tile (bias gradient)
+    // DW only: column sums of the A tile (the bias gradient), by the blocks of the first tile
+    // column.  All threads share the work: thread (crow, cpart) adds every CP-th k of row crow,
+    // the CP partial sums meet in LDS after the loop (one wavefront alone did 32 LDS reads per
+    // k-tile in front of its MFMAs, and its workgroup waited for it at every barrier: the paired
+    // launch at B = 4096 42.4 -> 42.0 us).
+    constexpr int CP = NT / BM;
+    const int crow = tid % BM, cpart = tid / BM;
+    float colsum = 0.f;
     const bool do_colsum = (KIND == GEMM_DW) && a.colsum != nullptr && tile_n == 0;
 
     // forward: the lane's bias values are requested now, not after the main loop
@@ -307,9 +314,9 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
             float *An = smem + ((kt + 1) & 1) * STAGE;
             const bool next = (kt + 1 < nk), next2 = (kt + 2 < nk);
             if (KIND == GEMM_DW && !A_KMAJ) {
-                if (do_colsum && tid < BM) {
+                if (do_colsum) {
 #pragma unroll
-                    for (int k = 0; k < BK; ++k) colsum += As[k * TA::LD + tid];
+                    for (int k = 0; k < BK / CP; ++k) colsum += As[(cpart + k * CP) * TA::LD + crow];
                 }
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
@@ -353,9 +360,9 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
         }
         if (kt + 2 < nk) load_tile(kt + 2);
         if (KIND == GEMM_DW && !A_KMAJ) {
-            if (do_colsum && tid < BM) {
+            if (do_colsum) {
 #pragma unroll
-                for (int k = 0; k < BK; ++k) colsum += As[k * TA::LD + tid];
+                for (int k = 0; k < BK / CP; ++k) colsum += As[(cpart + k * CP) * TA::LD + crow];
             }
         }
 #pragma unroll
@@ -367,6 +374,19 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
         if (kt + 1 < nk) read_frags(0, An, An + TA::FLOATS, 0);
         mfma_group((G - 1) & 1, G - 1);
     }
+    }
+
+    if (KIND == GEMM_DW) {
+        if (do_colsum) {  // uniform per workgroup; after the loop's last barrier nobody reads a stage
+            smem[cpart * BM + crow] = colsum;
+            __syncthreads();
+            if (tid < BM && m0 + tid < a.M) {
+                float s = smem[tid];
+#pragma unroll
+                for (int q = 1; q < CP; ++q) s += smem[q * BM + tid];
+                a.colsum[(size_t)split * a.M + m0 + tid] = s;
+            }
+        }
     }
 
     // ---- epilogue.  acc[i][j][v] is C(row, col) with
@@ -405,9 +425,6 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                 }
             }
         }
-        if (KIND == GEMM_DW) {
-            if (do_colsum && tid < BM) a.colsum[(size_t)split * a.M + m0 + tid] = colsum;
-        }
         return;
     }
 #pragma unroll
@@ -436,10 +453,6 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                 }
             }
         }
-    }
-    if (KIND == GEMM_DW) {
-        if (do_colsum && tid < BM && m0 + tid < a.M)
-            a.colsum[(size_t)split * a.M + m0 + tid] = colsum;
     }
 }
 
