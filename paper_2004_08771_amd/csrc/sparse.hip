@@ -21,6 +21,15 @@ namespace {
 
 constexpr int SP_NT = 128;    // threads per row / per chunk: one float4 each for d_1 = 512
 constexpr int CHUNK = 128;    // non-zeros per gradient chunk
+// Chunk descriptors are laid out by size class, so that the 16-lane groups of one wavefront
+// work on chunks of similar length (next to a 128-entry chunk three one-entry chunks sat idle
+// for seven of eight gather windows): first the whole columns of at most LIGHT_MAX entries (one
+// window of 16 gathers; most columns of a skewed distribution), then everything else, cut into
+// chunks of CHUNK entries.  (Four classes -- 16, 32, 64, more -- measured the same as these two.)
+constexpr int N_CLASS = 2;
+constexpr int LIGHT_MAX = 16;
+__host__ __device__ inline int chunk_class(int cnt) { return cnt <= LIGHT_MAX ? 0 : 1; }
+__host__ __device__ inline int chunks_of(int cnt) { return cnt <= LIGHT_MAX ? (cnt > 0 ? 1 : 0) : (cnt + CHUNK - 1) / CHUNK; }
 
 constexpr int SPMM_CAP = 512;  // entries of a row staged in LDS at a time (forward product)
 
@@ -189,29 +198,32 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane)
     return v;
 }
 
-// Sum over the workgroup's four wavefronts of (a, b); every thread gets the result.
-__device__ __forceinline__ void group_sum2(int &a, int &b, int *red /* 8 ints of LDS */)
+// Sums over the workgroup's four wavefronts of N values; every thread gets the results.
+template <int N>
+__device__ __forceinline__ void group_sum(int (&v)[N], int *red /* 4 N ints of LDS */)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        a += __shfl_xor(a, o, 64);
-        b += __shfl_xor(b, o, 64);
-    }
+    for (int i = 0; i < N; ++i)
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v[i] += __shfl_xor(v[i], o, 64);
     const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { red[wave] = a; red[4 + wave] = b; }
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) red[4 * i + wave] = v[i];
+    }
     __syncthreads();
-    a = red[0] + red[1] + red[2] + red[3];
-    b = red[4] + red[5] + red[6] + red[7];
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = red[4 * i] + red[4 * i + 1] + red[4 * i + 2] + red[4 * i + 3];
 }
 
 // Per column: exclusive prefix of its counts over the row blocks (in place in hist) and the
-// total cnt[c]; per group of 256 columns: the group's entry and chunk totals
-// (group_tot[g], group_tot[n_groups + g]).
+// total cnt[c]; per group of 256 columns: the group's totals of entries and of chunks per size
+// class (group_tot[g], group_tot[(1 + class) n_groups + g]).
 __global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ hist, int n_blocks, int d0,
                                                           int32_t *__restrict__ cnt,
                                                           int32_t *__restrict__ group_tot)
 {
-    __shared__ int red[8];
+    __shared__ int red[4 * (1 + N_CLASS)];
     const int c = blockIdx.x * COLG + threadIdx.x;
     int run = 0;
     if (c < d0) {
@@ -228,21 +240,23 @@ __global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ 
         }
         cnt[c] = run;
     }
-    int sa = run, sb = (run + CHUNK - 1) / CHUNK;
-    group_sum2(sa, sb, red);
+    int tot[1 + N_CLASS] = {run};
+    tot[1 + chunk_class(run)] = chunks_of(run);
+    group_sum(tot, red);
     if (threadIdx.x == 0) {
-        group_tot[blockIdx.x] = sa;
-        group_tot[gridDim.x + blockIdx.x] = sb;
+#pragma unroll
+        for (int i = 0; i <= N_CLASS; ++i) group_tot[i * gridDim.x + blockIdx.x] = tot[i];
     }
 }
 
-// Exclusive scans of cnt[0..n) (-> col_start) and of the chunk counts ceil(cnt / CHUNK)
-// (-> chunk_start), totals at index n, plus one descriptor per chunk {column, first entry,
-// end entry, chunks of the column} so that the gradient kernel finds its work with one load.
-// One workgroup per group of 256 columns: it adds up the totals of the groups before it,
-// scans its own columns with shuffles, and writes its outputs coalesced.  A column with more
-// than two chunks (the head of a skewed column distribution has hundreds) goes on an LDS
-// list and the whole workgroup writes its descriptors.
+// Exclusive scan of cnt[0..n) (-> col_start) and the position of every column's first chunk
+// descriptor (-> chunk_start; [n] = number of chunks): the chunks of size class 0 come first, in
+// column order, then class 1, and so on.  One descriptor per chunk {column, first entry, end
+// entry, chunks of the column} lets the gradient kernel find its work with one load.
+// One workgroup per group of 256 columns: it adds up the totals of the groups before it (and the
+// class totals of ALL groups), scans its own columns with shuffles, and writes its outputs
+// coalesced.  A column with more than two chunks (the head of a skewed column distribution has
+// hundreds) goes on an LDS list and the whole workgroup writes its descriptors.
 // (A single-workgroup scan of all 21k columns took 20-60 us in three different forms: one
 // CU's shuffle latency and store issue rate bound it.)
 __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restrict__ cnt,
@@ -251,39 +265,68 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
                                                         int32_t *__restrict__ chunk_start,
                                                         int4 *__restrict__ chunk_desc)
 {
-    __shared__ int red[8], w_a[4], w_b[4];
+    __shared__ int red[4 * (1 + N_CLASS)], w_a[4], w_c[4][N_CLASS];
     __shared__ int n_heavy;
     __shared__ int4 heavy[COLG];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int g = blockIdx.x, n_groups = gridDim.x;
     const int c = g * COLG + t;
     const int v = (c < n) ? cnt[c] : 0;
-    int pa = 0, pb = 0;  // entries / chunks in the groups before this one
-    for (int j = t; j < g; j += COLG) {
-        pa += group_tot[j];
-        pb += group_tot[n_groups + j];
+    int before[1 + N_CLASS] = {};  // entries / chunks per class in the groups before this one
+    int all[N_CLASS] = {};         // chunks per class of all groups
+    for (int j = t; j < n_groups; j += COLG) {
+        if (j < g) before[0] += group_tot[j];
+#pragma unroll
+        for (int k = 0; k < N_CLASS; ++k) {
+            const int x = group_tot[(1 + k) * n_groups + j];
+            if (j < g) before[1 + k] += x;
+            all[k] += x;
+        }
     }
     if (t == 0) n_heavy = 0;
-    group_sum2(pa, pb, red);  // its barrier also publishes n_heavy
-    const int ch = (v + CHUNK - 1) / CHUNK;
-    const int ia = wave_incl_scan(v, lane), ib = wave_incl_scan(ch, lane);
-    if (lane == 63) { w_a[wave] = ia; w_b[wave] = ib; }
+    group_sum(before, red);  // its barrier also publishes n_heavy
+    __syncthreads();         // red is reused
+    group_sum(all, red);
+    const int cls = chunk_class(v), ch = chunks_of(v);
+    const int ia = wave_incl_scan(v, lane);
+    int ic[N_CLASS];
+#pragma unroll
+    for (int k = 0; k < N_CLASS; ++k) ic[k] = wave_incl_scan(k == cls ? ch : 0, lane);
+    if (lane == 63) {
+        w_a[wave] = ia;
+#pragma unroll
+        for (int k = 0; k < N_CLASS; ++k) w_c[wave][k] = ic[k];
+    }
     __syncthreads();
-    int first_e = pa + ia - v, first_ch = pb + ib - ch;
-    for (int w = 0; w < wave; ++w) { first_e += w_a[w]; first_ch += w_b[w]; }
+    int first_e = before[0] + ia - v;
+    int first_ch = 0;  // chunks of the classes before this column's, then the earlier chunks of its own class
+#pragma unroll
+    for (int k = 0; k < N_CLASS; ++k) {
+        if (k < cls) first_ch += all[k];
+        if (k == cls) {
+            first_ch += before[1 + k] + ic[k] - ch;
+            for (int w = 0; w < wave; ++w) first_ch += w_c[w][k];
+        }
+    }
+    for (int w = 0; w < wave; ++w) first_e += w_a[w];
     if (c < n) {
         col_start[c] = first_e;
         chunk_start[c] = first_ch;
         if (c == n - 1) {
+            int total = 0;
+#pragma unroll
+            for (int k = 0; k < N_CLASS; ++k) total += all[k];
             col_start[n] = first_e + v;
-            chunk_start[n] = first_ch + ch;
+            chunk_start[n] = total;
         }
-        if (ch > 2)
+        if (ch > 2) {
             heavy[atomicAdd(&n_heavy, 1)] = make_int4(c, first_e, v, first_ch);
-        else
-            for (int q = 0; q < ch; ++q)
-                chunk_desc[first_ch + q] = make_int4(c, first_e + q * CHUNK,
-                                                     min(first_e + v, first_e + (q + 1) * CHUNK), ch);
+        } else if (ch == 1) {
+            chunk_desc[first_ch] = make_int4(c, first_e, first_e + v, 1);
+        } else if (ch == 2) {
+            chunk_desc[first_ch] = make_int4(c, first_e, first_e + CHUNK, 2);
+            chunk_desc[first_ch + 1] = make_int4(c, first_e + CHUNK, first_e + v, 2);
+        }
     }
     __syncthreads();
     const int nh = n_heavy;
@@ -662,7 +705,7 @@ bool csc_supported(int d0, long long max_B)
 }
 
 // cnt[d0 + 1] followed by the per-group totals of the column scan
-size_t csc_cnt_elems(int d0) { return (size_t)d0 + 1 + 2 * (size_t)((d0 + COLG - 1) / COLG); }
+size_t csc_cnt_elems(int d0) { return (size_t)d0 + 1 + (1 + N_CLASS) * (size_t)((d0 + COLG - 1) / COLG); }
 
 size_t csc_hist_elems(long long max_B, int d0) { return (size_t)csc_blocks(max_B) * (size_t)d0; }
 
