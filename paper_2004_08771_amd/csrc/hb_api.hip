@@ -1108,7 +1108,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         rc = dev_alloc(m, &m->d_w1t, d0 * m->dims[1]);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_cnt, csc_cnt_elems(d0));
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_start, d0 + 1);
-        if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 1);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 2);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, csc_hist_elems(max_B, m->dims[0]));
         // HB_CSC_INLINE=1 (tuning aid) keeps the CSC build on the handle's stream, before the weight gradient
         static const bool csc_inline = getenv("HB_CSC_INLINE") && atoi(getenv("HB_CSC_INLINE")) != 0;

@@ -230,7 +230,7 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream,
 
 struct SparseDwArgs {
     const int32_t *col_start;    // d_0 + 1: segment of each column in csc_row / csc_val
-    const int32_t *chunk_start;  // d_0 + 1: first chunk of each column; [d_0] = number of chunks
+    const int32_t *chunk_start;  // d_0 + 2: first chunk of each column; [d_0] = number of chunks, [d_0 + 1] = of class 0
     const int4 *chunk_desc;      // per chunk: {column, first entry, end entry, chunks of the column}
     const int32_t *csc_row;
     const float *csc_val;

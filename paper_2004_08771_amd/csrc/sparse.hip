@@ -250,7 +250,7 @@ __global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ 
 }
 
 // Exclusive scan of cnt[0..n) (-> col_start) and the position of every column's first chunk
-// descriptor (-> chunk_start; [n] = number of chunks): the chunks of size class 0 come first, in
+// descriptor (-> chunk_start; [n] = number of chunks, [n + 1] = chunks of class 0): the chunks of size class 0 come first, in
 // column order, then class 1, and so on.  One descriptor per chunk {column, first entry, end
 // entry, chunks of the column} lets the gradient kernel find its work with one load.
 // One workgroup per group of 256 columns: it adds up the totals of the groups before it (and the
@@ -318,6 +318,7 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
             for (int k = 0; k < N_CLASS; ++k) total += all[k];
             col_start[n] = first_e + v;
             chunk_start[n] = total;
+            chunk_start[n + 1] = all[0];
         }
         if (ch > 2) {
             heavy[atomicAdd(&n_heavy, 1)] = make_int4(c, first_e, v, first_ch);
@@ -569,24 +570,9 @@ __global__ __launch_bounds__(XS_NT) void spmm_fwd_sliced_kernel(SpmmArgs a, long
     *reinterpret_cast<float4 *>(a.out + (size_t)row * a.ldo + col0) = acc;
 }
 
-// g[slice] = sum_e csc_val[e] * delta_1[csc_row[e], slice] over one chunk, then the update of
-// W1t[c, slice] (or the gradient output) as in sparse_dw_kernel; unit = 16 consecutive chunks.
-// (Requesting the descriptor together with the chunk count, and the weight row of a single-chunk
-// column before the gathers instead of after them, made the kernel slower: 70 -> 76 us.)
-__global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a, SliceMap m, int units)
+// W1t[c, slice] -= lr * g (or the gradient output) for one chunk's sum g, as in sparse_dw_kernel
+__device__ __forceinline__ void apply_chunk_sum(const SparseDwArgs &a, int c, int col0, float4 g, bool single)
 {
-    int slice, unit;
-    slice_of_block(m, blockIdx.x, slice, unit);
-    if (unit >= units) return;
-    const int g16 = threadIdx.x >> 4, l = threadIdx.x & 15;
-    const int chunk = unit * 16 + g16;
-    if (chunk >= a.chunk_start[a.d0]) return;
-    const int4 desc = a.chunk_desc[chunk];
-    const int c = desc.x;
-    const bool single = (desc.w == 1);
-    const int col0 = slice * SL + 4 * l;
-    float4 g = {0.f, 0.f, 0.f, 0.f};
-    g = group_gather_sum(g, a.csc_row, a.csc_val, desc.y, desc.z, a.delta + col0, (size_t)a.ldd, l);
     if (a.grad_out) {
         float *o = a.grad_out + (size_t)col0 * a.d0 + c;
         if (single) { o[0] = g.x; o[a.d0] = g.y; o[2 * (size_t)a.d0] = g.z; o[3 * (size_t)a.d0] = g.w; }
@@ -605,6 +591,89 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
             atomicAdd(w + 2, -a.lr * g.z); atomicAdd(w + 3, -a.lr * g.w);
         }
     }
+}
+
+// g[slice] = sum_e csc_val[e] * delta_1[csc_row[e], slice] over one chunk, then the update of
+// W1t[c, slice] (or the gradient output) as in sparse_dw_kernel.
+// The chunks of class 0 (whole columns of at most 16 entries, most of them with one to three)
+// come first: a group of 16 lanes takes LP of them at once and issues every step of their
+// chains (descriptors, indices, gathers LR per column and round, weight rows) for all LP
+// together -- one such column alone is five dependent round trips with nothing to overlap
+// them but other groups.  The other chunks follow, one per group.  unit = 16 groups.
+// (Requesting the descriptor together with the chunk count, and the weight row of a single-chunk
+// column before the gathers instead of after them, made the one-chunk form slower: 70 -> 76 us.)
+constexpr int LP = 4, LR = 2;
+__global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a, SliceMap m, int units)
+{
+    int slice, unit;
+    slice_of_block(m, blockIdx.x, slice, unit);
+    if (unit >= units) return;
+    const int g16 = threadIdx.x >> 4, l = threadIdx.x & 15;
+    const int n_chunks = a.chunk_start[a.d0], n_light = a.chunk_start[a.d0 + 1];
+    const int light_units = (n_light + 16 * LP - 1) / (16 * LP);
+    const int col0 = slice * SL + 4 * l;
+    if (unit < light_units) {
+        const int first = (unit * 16 + g16) * LP;
+        if (first >= n_light) return;
+        int c[LP], n[LP], my_i[LP];
+        float my_v[LP];
+        int4 desc[LP];
+#pragma unroll
+        for (int k = 0; k < LP; ++k) desc[k] = a.chunk_desc[min(first + k, n_light - 1)];
+        int n_max = 0;
+#pragma unroll
+        for (int k = 0; k < LP; ++k) {
+            c[k] = desc[k].x;
+            n[k] = (first + k < n_light) ? desc[k].z - desc[k].y : 0;  // a class-0 chunk holds 1..16 entries
+            n_max = max(n_max, n[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < LP; ++k) {  // lanes past the end hold the last entry's row and a zero value
+            const int at = desc[k].y + min(l, max(n[k], 1) - 1);
+            my_i[k] = a.csc_row[at];
+            my_v[k] = (l < n[k]) ? a.csc_val[at] : 0.f;
+        }
+        float4 g[LP];
+#pragma unroll
+        for (int k = 0; k < LP; ++k) g[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float *src = a.delta + col0;
+        for (int u0 = 0; u0 < n_max; u0 += LR) {
+            float4 w[LP][LR];
+#pragma unroll
+            for (int k = 0; k < LP; ++k)
+#pragma unroll
+                for (int u = 0; u < LR; ++u)
+                    w[k][u] = *reinterpret_cast<const float4 *>(src + (size_t)__shfl(my_i[k], u0 + u, 16) * a.ldd);
+#pragma unroll
+            for (int k = 0; k < LP; ++k)
+#pragma unroll
+                for (int u = 0; u < LR; ++u) {
+                    const float v = __shfl(my_v[k], u0 + u, 16);
+                    g[k].x += v * w[k][u].x; g[k].y += v * w[k][u].y; g[k].z += v * w[k][u].z; g[k].w += v * w[k][u].w;
+                }
+        }
+        if (a.grad_out) {
+#pragma unroll
+            for (int k = 0; k < LP; ++k)
+                if (first + k < n_light) apply_chunk_sum(a, c[k], col0, g[k], true);
+        } else {  // the LP weight rows are requested together (distinct columns: no row twice)
+            float4 x[LP];
+#pragma unroll
+            for (int k = 0; k < LP; ++k) x[k] = *reinterpret_cast<const float4 *>(a.W1t + (size_t)c[k] * a.ldw + col0);
+#pragma unroll
+            for (int k = 0; k < LP; ++k) {
+                x[k].x -= a.lr * g[k].x; x[k].y -= a.lr * g[k].y; x[k].z -= a.lr * g[k].z; x[k].w -= a.lr * g[k].w;
+                if (first + k < n_light) *reinterpret_cast<float4 *>(a.W1t + (size_t)c[k] * a.ldw + col0) = x[k];
+            }
+        }
+        return;
+    }
+    const int chunk = n_light + (unit - light_units) * 16 + g16;
+    if (chunk >= n_chunks) return;
+    const int4 desc = a.chunk_desc[chunk];
+    float4 g = {0.f, 0.f, 0.f, 0.f};
+    g = group_gather_sum(g, a.csc_row, a.csc_val, desc.y, desc.z, a.delta + col0, (size_t)a.ldd, l);
+    apply_chunk_sum(a, desc.x, col0, g, desc.w == 1);
 }
 
 // partial[s][j] = sum over the s-th slice of rows of delta[i][j]   (bias gradient of layer 1)
@@ -771,7 +840,8 @@ hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStre
     if (max_chunks <= 0) return hipSuccess;
     SliceMap m;
     if (slice_map(a.d1, a.vec, &m)) {
-        const long long units = (max_chunks + 15) / 16;
+        // ceil(light / (16 LP)) + ceil(others / 16) units are needed, whatever the split
+        const long long units = (max_chunks + 15) / 16 + 1;
         const long long blocks = sliced_blocks(m, units);
         if (blocks <= 0x7fffffffLL)
             return launch_kernel(sparse_dw_sliced_kernel, dim3((unsigned)blocks), dim3(XS_NT), stream, ev, a, m,
