@@ -105,6 +105,29 @@ __device__ __forceinline__ float act_fwd(float z, int act)
     return z;
 }
 
+// ReLU decision bits of one 32 x 32 block (see GemmBf16Args::mask_out): position of the value
+// (q, e) = row 8 q + 4 h + e in the lane's 16-bit word, the word from the lane's 16 packed
+// bf16 values (pk[q] = rows e = 0..3 of group q), and the use of a bit on a backward value.
+// "Positive" is: sign clear and magnitude not zero (true for a NaN as well, where `> 0` is not).
+__device__ __forceinline__ constexpr int relu_bit_pos(int q, int e) { return 8 * (e & 1) + 2 * q + (e >> 1); }
+__device__ __forceinline__ unsigned relu_bits(const uint2 (&pk)[4])
+{
+    unsigned acc = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {  // dword k holds (q, e) = (k / 2, 2 (k % 2)) below (q, e + 1)
+        const unsigned x = (k & 1) ? pk[k >> 1].y : pk[k >> 1].x;
+        const unsigned t = ((x & 0x7fff7fffu) + 0x7fff7fffu) & ~x;  // bits 15 / 31: the half is positive
+        acc = (t & 0x80008000u) | (acc >> 1);
+    }
+    // the low halves of dwords 0..7 now sit at bits 8..15, the high halves at bits 24..31
+    return ((acc >> 8) & 0xffu) | ((acc >> 16) & 0xff00u);
+}
+__device__ __forceinline__ float relu_keep(float val, unsigned word, int q, int e)
+{
+    const int m = (int)(word << (31 - relu_bit_pos(q, e))) >> 31;  // 0 or -1 (one v_bfe_i32)
+    return __uint_as_float(__float_as_uint(val) & (unsigned)m);
+}
+
 template <int BM, int BN, int BK>
 constexpr size_t lds_bytes_bf16()
 {
@@ -127,6 +150,7 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
     const bool has_cf = a.C_f32 != nullptr, has_cb = a.C_bf16 != nullptr;
     const bool has_ct = a.Ct_bf16 != nullptr && !(KIND == GEMM_DW && a.write_grad);
     const bool use_t = (KIND == GEMM_DA) && a.aux_t != nullptr && (a.ldauxt & 3) == 0;
+    const bool use_mask = (KIND == GEMM_DA) && a.mask_in != nullptr && a.act == ACT_RELU;
     const bool ct_vec = (a.ldct & 3) == 0;
     // per-lane byte offsets (row part 4 h, column part r)
     const unsigned lo_cf = (unsigned)(4 * h * (int)a.ldc + r) * 4u;
@@ -147,7 +171,7 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
         float bias = 0.f;
         if (KIND == GEMM_FWD && a.bias != nullptr && n_ok) bias = a.bias[n];
         uint2 ot[TM][4];
-        if (KIND == GEMM_DA && FULL) {
+        if (KIND == GEMM_DA && FULL && !use_mask) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -156,8 +180,18 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                         at0 + ((size_t)nb * a.ldauxt + (mw + i * 32 + 8 * q)) * 2 + lo_at);
             __builtin_amdgcn_sched_barrier(0);
         }
+        // ReLU decision bits: a block is addressed only when it holds a valid element (the
+        // array covers ceil(M / 32) x ceil(N / 32) blocks)
+        unsigned mword[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            mword[i] = 0u;
+            if (KIND == GEMM_DA && use_mask && (FULL || (mw + i * 32 < a.M && nb < a.N)))
+                mword[i] = a.mask_in[((size_t)((mw + i * 32) >> 5) * a.mask_nb + (nb >> 5)) * 64 + 32 * h + r];
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            unsigned mbits = 0u;
             float w[16];
             if (KIND == GEMM_DW && FULL && !a.write_grad) {
 #pragma unroll
@@ -171,7 +205,7 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                 const int mb = mw + i * 32 + 8 * q;  // uniform; this lane's rows are mb + 4 h + e
                 const int mq = mb + 4 * h;
                 uint2 o4 = {0u, 0u};
-                if (KIND == GEMM_DA) {
+                if (KIND == GEMM_DA && !use_mask) {
                     if (FULL) o4 = ot[i][q];
                     else if (use_t && n_ok && mq < a.M)  // rows of the copy are padded to 4: in bounds
                         o4 = *reinterpret_cast<const uint2 *>(at0 + ((size_t)nb * a.ldauxt + mb) * 2 + lo_at);
@@ -185,6 +219,12 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                             val = act_fwd(val + bias, a.act);
                             if (has_cf)
                                 *reinterpret_cast<float *>(cf0 + ((size_t)(mb + e) * a.ldc + nb) * 4 + lo_cf) = val;
+                            if (a.mask_out != nullptr) {
+                                const bf16_t b = f2bf(val);
+                                if ((b & 0x7fffu) != 0 && (b & 0x8000u) == 0) mbits |= 1u << relu_bit_pos(q, e);
+                            }
+                        } else if (KIND == GEMM_DA && use_mask) {
+                            val = relu_keep(val, mword[i], q, e);
                         } else if (KIND == GEMM_DA) {
                             float o;
                             if (FULL || use_t) {
@@ -223,6 +263,9 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                 // accumulators live it runs out of registers
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (KIND == GEMM_FWD && a.mask_out != nullptr && (FULL || (mw + i * 32 < a.M && nb < a.N)))
+                a.mask_out[((size_t)((mw + i * 32) >> 5) * a.mask_nb + (nb >> 5)) * 64 + 32 * h + r] =
+                    (unsigned short)mbits;
         }
     }
 }
@@ -233,7 +276,8 @@ __device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)
 {
     const bool full = (mw + 32 * TM <= a.M) && (nw + 32 * TN <= a.N) &&
                       (a.Ct_bf16 == nullptr || (a.ldct & 3) == 0) &&
-                      (KIND != GEMM_DA || (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
+                      (KIND != GEMM_DA || (a.mask_in != nullptr && a.act == ACT_RELU) ||
+                       (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
     if (full) epilogue_bf16_impl<KIND, TM, TN, true>(a, acc, mw, nw, r, h);
     else epilogue_bf16_impl<KIND, TM, TN, false>(a, acc, mw, nw, r, h);
 }
@@ -393,9 +437,12 @@ constexpr int EPI_SC = 144;  // row stride of the 128 x 64 row-major tile (128 b
 constexpr int EPI_ST = 272;  // row stride of the 64 x 128 transposed tile (256 bytes + 16)
 static_assert(128 * EPI_SC <= EPI_REGION && 64 * EPI_ST <= EPI_REGION && 8 * EPI_REGION <= (int)DMA_LDS_BYTES, "LDS");
 
+// mword: backward-data product with ReLU decision bits (use_mask): the lane's words of its eight
+// blocks, requested by the caller before the main loop.
 template <int KIND>
 __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&acc)[4][2], unsigned char *region,
-                                                  int mw, int nw, int lane)
+                                                  int mw, int nw, int lane, const unsigned (&mword)[4][2],
+                                                  bool use_mask)
 {
     constexpr int TM = 4, TN = 2;
     const int r = lane & 31, h = lane >> 5;
@@ -411,7 +458,7 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
         float bias = 0.f;
         if (KIND == GEMM_FWD && a.bias != nullptr) bias = a.bias[nb + r];
         uint2 ot[TM][4];
-        if (KIND == GEMM_DA) {
+        if (KIND == GEMM_DA && !use_mask) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -446,10 +493,14 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
                     if (KIND == GEMM_FWD) {
                         val = act_fwd(val + bias, a.act);
                     } else if (KIND == GEMM_DA) {
-                        const unsigned int pw = (e < 2) ? ot[i][q].x : ot[i][q].y;
-                        const float o = __uint_as_float((e & 1) ? (pw & 0xffff0000u) : (pw << 16));
-                        if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
-                        else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
+                        if (use_mask) {
+                            val = relu_keep(val, mword[i][j], q, e);
+                        } else {
+                            const unsigned int pw = (e < 2) ? ot[i][q].x : ot[i][q].y;
+                            const float o = __uint_as_float((e & 1) ? (pw & 0xffff0000u) : (pw << 16));
+                            if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
+                            else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
+                        }
                     } else {  // Eq. (3) on the fp32 master weight, stored back directly
                         val = w[e] - a.lr * val;
                         *reinterpret_cast<float *>(cf0 + ((size_t)(mw + i * 32 + 8 * q + e) * a.ldc + nb) * 4 + lo_cf) = val;
@@ -483,6 +534,15 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
             const uint4 v = *reinterpret_cast<const uint4 *>(region + row * EPI_SC + ch * 16);
             *reinterpret_cast<uint4 *>(cb + (size_t)row * a.ldcb * 2 + ch * 16) = v;
         }
+    }
+    // ---- forward product of a ReLU layer: the decision bits of the lane's eight blocks, worked
+    // out while the stores above drain
+    if (KIND == GEMM_FWD && a.mask_out != nullptr) {
+        unsigned short *const mo = a.mask_out + ((size_t)(mw >> 5) * a.mask_nb + (nw >> 5)) * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) mo[((size_t)i * a.mask_nb + j) * 64] = (unsigned short)relu_bits(pk[i][j]);
     }
     // ---- transposed copy: T[n][m], lane writes 8 bytes (its four rows) into row j*32 + r.  The
     // region is reused: LDS operations of a wavefront execute in order
@@ -601,6 +661,32 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // Epilogue through LDS (uniform for the workgroup): both bf16 outputs wanted (and, except for
+    // the fused update, nothing else), workgroup tile inside the matrix, 16-byte alignment of every row
+    const bool use_mask = (KIND == GEMM_DA) && a.mask_in != nullptr && a.act == ACT_RELU;
+    const bool via_lds = !(KIND == GEMM_DW && a.k_chunk > 0) && a.C_bf16 != nullptr && a.Ct_bf16 != nullptr &&
+                         (KIND == GEMM_DW ? (a.C_f32 != nullptr && !a.write_grad) : a.C_f32 == nullptr) &&
+                         (m0 + BM <= a.M) && (n0 + BN <= a.N) && (a.ldcb & 7) == 0 && (a.ldct & 7) == 0 &&
+                         ((reinterpret_cast<size_t>(a.C_bf16) | reinterpret_cast<size_t>(a.Ct_bf16)) & 15) == 0 &&
+                         (KIND != GEMM_DA || use_mask || (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
+    // backward-data product: the ReLU decision bits of the lane's eight blocks are requested
+    // now and have arrived long before the epilogue (they are older than every operand load,
+    // so the waits of the main loop cover them)
+    unsigned mword[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) mword[i][j] = 0u;
+    if (KIND == GEMM_DA && use_mask && via_lds) {
+        const unsigned short *mi =
+            a.mask_in + ((size_t)((m0 + wm * 128) >> 5) * a.mask_nb + ((n0 + wn * 64) >> 5)) * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) mword[i][j] = mi[((size_t)i * a.mask_nb + j) * 64];
+    }
+
     auto mfma_step = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -737,16 +823,13 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
         as.C_f32 = static_cast<float *>(a.C_f32) + (size_t)blockIdx.y * (size_t)a.c_split_stride;
         epilogue_bf16<KIND, TM, TN>(as, acc, m0 + wm * 128, n0 + wn * 64, r, h);
     } else {
-        // both bf16 outputs wanted (and, except for the fused update, nothing else), workgroup tile
-        // inside the matrix, 16-byte alignment of every row: through LDS (uniform for the workgroup)
-        const bool via_lds = a.C_bf16 != nullptr && a.Ct_bf16 != nullptr &&
-                             (KIND == GEMM_DW ? (a.C_f32 != nullptr && !a.write_grad) : a.C_f32 == nullptr) &&
-                             (m0 + BM <= a.M) && (n0 + BN <= a.N) && (a.ldcb & 7) == 0 && (a.ldct & 7) == 0 &&
-                             ((reinterpret_cast<size_t>(a.C_bf16) | reinterpret_cast<size_t>(a.Ct_bf16)) & 15) == 0 &&
-                             (KIND != GEMM_DA || (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
         if (via_lds) {
-            __syncthreads();  // every wavefront is done with the operand stages
-            epilogue_bf16_lds<KIND>(a, acc, smem_raw + wave * EPI_REGION, m0 + wm * 128, n0 + wn * 64, lane);
+            // Every wavefront must be done with the operand stages.  After the main loop it is:
+            // the last fragments were read before the loop's last barrier.  A K tail, or no
+            // whole k-tile at all, ends with reads of stage 0.
+            if (ktail > 0 || nkf == 0) __syncthreads();
+            epilogue_bf16_lds<KIND>(a, acc, smem_raw + wave * EPI_REGION, m0 + wm * 128, n0 + wn * 64, lane, mword,
+                                    use_mask);
         } else {
             epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * 128, n0 + wn * 64, r, h);
         }

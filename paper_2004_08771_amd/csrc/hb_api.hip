@@ -132,6 +132,7 @@ struct hb_model {
     std::vector<int> ld8;                       // d_l rounded up to 8
     std::vector<void *> shadow, shadow_t;       // [1..L]
     std::vector<void *> act_bf, act_t;          // [1..L-1] / [0..L-1]
+    std::vector<unsigned short *> relu_mask;    // [1..L-1], ReLU nets: decision bits of the hidden activations
     void *delta_bf[2] = {nullptr, nullptr};
     void *delta_t[2] = {nullptr, nullptr};
 
@@ -640,6 +641,10 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             if (back) {
                 g.Ct_bf16 = m->act_t[l];
                 g.ldct = ldB;
+                if (m->act == ACT_RELU) {  // the decisions the backward-data product of layer l+1 applies
+                    g.mask_out = m->relu_mask[l];
+                    g.mask_nb = (m->dims[l] + 31) / 32;
+                }
             }
         } else {
             g.act = ACT_NONE;
@@ -686,6 +691,10 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.ldaux = m->ld8[l - 1];
             g.aux_t = m->act_t[l - 1];  // written by the forward pass of layer l-1
             g.ldauxt = ldB;
+            if (m->act == ACT_RELU) {
+                g.mask_in = m->relu_mask[l - 1];
+                g.mask_nb = (m->dims[l - 1] + 31) / 32;
+            }
             g.act = m->act;
             g.C_bf16 = m->delta_bf[(l - 1) & 1];
             g.ldcb = m->ld8[l - 1];
@@ -1060,6 +1069,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         m->shadow_t.assign(L + 1, nullptr);
         m->act_bf.assign(L + 1, nullptr);
         m->act_t.assign(L + 1, nullptr);
+        m->relu_mask.assign(L + 1, nullptr);
         int max_ld8 = 8, max_d = 1;
         for (int l = 0; l <= L; ++l) {
             m->ld8[l] = round_up(m->dims[l], 8);
@@ -1082,6 +1092,10 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
             }
             if (rc == HB_OK) rc = dev_alloc(m, &p, (size_t)m->dims[l] * ldB);
             m->act_t[l] = p;
+            if (l >= 1 && m->act == ACT_RELU && rc == HB_OK) {  // 64 words per 32 x 32 block
+                rc = dev_alloc(m, &p, (size_t)((max_B + 31) / 32) * (size_t)((m->dims[l] + 31) / 32) * 64);
+                m->relu_mask[l] = p;
+            }
         }
         for (int i = 0; i < 2 && rc == HB_OK; ++i) {
             unsigned short *p = nullptr;

@@ -95,6 +95,15 @@ struct GemmBf16Args {
     long long ldaux;
     const void *aux_t;     // ... and, optional, their transposed copy [N x ldauxt]: four rows per 8-byte load
     long long ldauxt;
+    // ReLU decisions of a hidden layer as bits, one 16-bit word per lane and 32 x 32 block of the
+    // layer's activations, word ((m / 32) * mask_nb + n / 32) * 64 + lane in the MFMA accumulator
+    // layout (lane = 32 h + r owns rows 8 q + 4 h + e of column r: bit 8 (e & 1) + 2 q + (e >> 1)
+    // is set when the stored bf16 activation is positive).  The forward product writes them
+    // (mask_out), the backward-data product of the layer above reads them (mask_in) instead of
+    // the activations themselves: 128 bytes per block instead of 2 KB.
+    unsigned short *mask_out;
+    const unsigned short *mask_in;
+    int mask_nb;           // 32-column blocks per block row: ceil(N / 32)
     int act;
     int write_grad;
     float lr;
