@@ -405,6 +405,26 @@ __global__ __launch_bounds__(NT, 2) void gemm_bf16_nt_kernel(GemmBf16Args a)  //
 // compiler would also wait for the direct loads that were only just issued.
 typedef __attribute__((address_space(1))) const void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
+typedef int v2i __attribute__((ext_vector_type(2)));
+template <int K>
+struct KStep {
+    static constexpr int value = K;
+};
+
+// gfx950's transposing LDS read of 8 bytes per lane at LDS byte address addr + OFF.  Written as
+// an instruction, not through the compiler's builtin: for the builtin the compiler cannot
+// tell that the read does not touch what the LDS-direct loads in flight are writing, and puts
+// a wait for ALL of them (vmcnt(0)) in front of every read (the weight gradient
+// 4096 x 4096 x 16384 took 530 us that way).  The compiler does not wait for the result
+// either: every use below sits behind an explicit lgkmcnt(0) and a scheduling barrier.
+template <int OFF>
+__device__ __forceinline__ v2i lds_read_tr16_b64(unsigned addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+    v2i v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
 
 // slot permutation of tile row R: bit 0 of the chunk index (the half-wavefront h of a fragment
 // read) is never mixed with the row bits that vary inside one 16-lane group
@@ -544,6 +564,7 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
 #pragma unroll
             for (int j = 0; j < TN; ++j) mo[((size_t)i * a.mask_nb + j) * 64] = (unsigned short)relu_bits(pk[i][j]);
     }
+    if (a.Ct_bf16 == nullptr) return;  // uniform
     // ---- transposed copy: T[n][m], lane writes 8 bytes (its four rows) into row j*32 + r.  The
     // region is reused: LDS operations of a wavefront execute in order
 #pragma unroll
@@ -564,9 +585,20 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
     }
 }
 
-template <int KIND>
+// BMAJ (weight gradient only): both operands are batch-major, A[k * lda + m] and B[k * ldb + n],
+// i.e. the row-major deltas and activations themselves, so that no transposed copy of either
+// has to exist.  An operand tile is then 64 k-rows of 512 bytes; the MFMA still wants 8
+// consecutive k per lane, which gfx950's transposing LDS read delivers: ds_read_b64_tr_b16
+// works in groups of 16 lanes, lane 4 j + q of a group supplies the address of an 8-byte word
+// (k-row j, columns 4 q .. 4 q + 3 of a 16-column strip) and lane l receives column l at
+// k-rows 0..3 (layout checked with an in-bounds probe).  Two such reads make one operand
+// fragment.  The four k-rows a group reads together are 512 bytes apart, i.e. on the same
+// banks: the 64-byte segments of k-row k are therefore stored at segment index s ^ (k & 3)
+// (the direct loads fetch the permuted segment, their LDS side stays contiguous).
+template <int KIND, bool BMAJ = false>
 __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a)
 {
+    static_assert(!BMAJ || KIND == GEMM_DW, "batch-major operands: weight gradient only");
     constexpr int BM = DMA_BM, BN = DMA_BN, BK = DMA_BK;
     constexpr int TM = 4, TN = 2;  // 32 x 32 blocks per wavefront: 128 x 64
     constexpr int G = BK / 16;     // MFMA k-steps per tile
@@ -607,51 +639,91 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
     const int klen = (a.k_chunk > 0) ? min(a.K - kbeg, a.k_chunk) : a.K;
     const int nkf = klen / BK;  // full k-tiles
 
-    const unsigned char *__restrict__ Ab = static_cast<const unsigned char *>(a.A) + (size_t)kbeg * 2;
-    const unsigned char *__restrict__ Bb = static_cast<const unsigned char *>(a.B) + (size_t)kbeg * 2;
+    // operand base at the first k of the slice, and the step from one k-tile to the next
+    const size_t a_tile_step = BMAJ ? (size_t)BK * (size_t)a.lda * 2 : (size_t)DMA_ROW_BYTES;
+    const size_t b_tile_step = BMAJ ? (size_t)BK * (size_t)a.ldb * 2 : (size_t)DMA_ROW_BYTES;
+    const unsigned char *__restrict__ Ab =
+        static_cast<const unsigned char *>(a.A) + (BMAJ ? (size_t)kbeg * (size_t)a.lda * 2 : (size_t)kbeg * 2);
+    const unsigned char *__restrict__ Bb =
+        static_cast<const unsigned char *>(a.B) + (BMAJ ? (size_t)kbeg * (size_t)a.ldb * 2 : (size_t)kbeg * 2);
 
-    // ---- global side of the direct loads.  One wavefront load covers 8 tile rows (1 KB):
-    // lane -> (row lane / 8, slot lane % 8); the wavefront takes row blocks wave, wave + 8, ..
+    // ---- global side of the direct loads.  One wavefront load fills 1 KB of LDS, lane i its
+    // bytes 16 i ..: 8 tile rows of 128 bytes (lane -> row lane / 8, slot lane % 8), or, BMAJ,
+    // 2 k-rows of 512 bytes (lane -> k-row lane / 32, slot lane % 32).  The wavefront takes
+    // the 1 KB blocks wave, wave + 8, ..  BMAJ: columns past the end of a row (edge tiles; their
+    // results are never stored) are clamped to the row's last 16 bytes.
     const int blk_row = lane >> 3;
     unsigned offA[4], offB[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int R = (wave + 8 * v) * 8 + blk_row;
-        const int chunk = (lane & 7) ^ swz(R);  // the chunk whose slot is lane % 8
-        offA[v] = (unsigned)((size_t)min(m0 + R, a.M - 1) * (size_t)a.lda * 2 + chunk * 16);
-        offB[v] = (unsigned)((size_t)min(n0 + R, a.N - 1) * (size_t)a.ldb * 2 + chunk * 16);
+        if (BMAJ) {
+            const int k = (wave + 8 * v) * 2 + (lane >> 5);
+            const int chunk = (lane & 31) ^ ((k & 3) << 2);  // the chunk whose slot is lane % 32
+            offA[v] = (unsigned)((size_t)k * (size_t)a.lda * 2 +
+                                 (size_t)min((long long)m0 * 2 + chunk * 16, a.lda * 2 - 16));
+            offB[v] = (unsigned)((size_t)k * (size_t)a.ldb * 2 +
+                                 (size_t)min((long long)n0 * 2 + chunk * 16, a.ldb * 2 - 16));
+        } else {
+            const int R = (wave + 8 * v) * 8 + blk_row;
+            const int chunk = (lane & 7) ^ swz(R);  // the chunk whose slot is lane % 8
+            offA[v] = (unsigned)((size_t)min(m0 + R, a.M - 1) * (size_t)a.lda * 2 + chunk * 16);
+            offB[v] = (unsigned)((size_t)min(n0 + R, a.N - 1) * (size_t)a.ldb * 2 + chunk * 16);
+        }
     }
     // loads first .. first + 1 of the wavefront's four of an A / B tile (tile t -> given stage)
     auto issue_a = [&](int t, int stage, int first) {
         unsigned char *st = smem_raw + stage * DMA_A_BYTES;
 #pragma unroll
         for (int v = first; v < first + 2; ++v)
-            __builtin_amdgcn_global_load_lds((gptr_t)(Ab + (size_t)t * DMA_ROW_BYTES + offA[v]),
+            __builtin_amdgcn_global_load_lds((gptr_t)(Ab + (size_t)t * a_tile_step + offA[v]),
                                              (lptr_t)(st + (wave + 8 * v) * 1024), 16, 0, 0);
     };
     auto issue_b = [&](int t, int stage, int first) {
         unsigned char *st = smem_raw + DMA_B_BASE + stage * DMA_B_BYTES;
 #pragma unroll
         for (int v = first; v < first + 2; ++v)
-            __builtin_amdgcn_global_load_lds((gptr_t)(Bb + (size_t)t * DMA_ROW_BYTES + offB[v]),
+            __builtin_amdgcn_global_load_lds((gptr_t)(Bb + (size_t)t * b_tile_step + offB[v]),
                                              (lptr_t)(st + (wave + 8 * v) * 1024), 16, 0, 0);
     };
 
     // ---- LDS side of the fragment reads: lane (r, h) reads chunk 2 kk + h of its row.  The
     // block offsets i * 32 rows leave (R >> 1) & 7 unchanged, so the swizzle depends on r only.
+    // BMAJ: lane 16 g + 4 j + q addresses k-row 16 kk + 8 h + 4 t + j (t = 0, 1: the two reads of
+    // a fragment), bytes 32 (g & 1) + 8 q of the block's 64-byte segment, which is stored at
+    // segment index (true index) ^ j; the block index enters as one more XOR.
     const int fr = swz(r);
-    const int a_off = (wm * 128 + r) * DMA_ROW_BYTES + ((h ^ fr) << 4);  // k-step kk: a_off ^ (kk << 5)
-    const int b_off = DMA_B_BASE + (wn * 64 + r) * DMA_ROW_BYTES + ((h ^ fr) << 4);
+    const int tj = (lane & 15) >> 2;
+    const int a_off = BMAJ ? (8 * h + tj) * 512 + (((wm * 4) ^ tj) << 6) + 32 * ((lane >> 4) & 1) + 8 * (lane & 3)
+                         : (wm * 128 + r) * DMA_ROW_BYTES + ((h ^ fr) << 4);  // k-step kk: a_off ^ (kk << 5)
+    const int b_off = DMA_B_BASE + (BMAJ ? (8 * h + tj) * 512 + (((wn * 2) ^ tj) << 6) + 32 * ((lane >> 4) & 1) + 8 * (lane & 3)
+                                       : (wn * 64 + r) * DMA_ROW_BYTES + ((h ^ fr) << 4));
     v8bf fa[2][TM], fb[2][TN];
-    auto read_frags = [&](int slot, int sa, int sb, int kk) {
+    const unsigned lds0 = (unsigned)(size_t)(lptr_t)smem_raw;  // LDS byte address of the stages
+    // one operand fragment (block q of the A or B tile at p, k-step kk; kk is a KStep<> so
+    // that the batch-major form can put it into the instruction's offset field)
+    auto frag = [&](const unsigned char *p, int off, int q, auto kkc) -> v8bf {
+        constexpr int kk = decltype(kkc)::value;
+        if (BMAJ) {
+            const unsigned addr = lds0 + (unsigned)(p - smem_raw) + (unsigned)(off ^ (q << 6));
+            const v2i lo = lds_read_tr16_b64<kk * 16 * 512>(addr);
+            const v2i hi = lds_read_tr16_b64<kk * 16 * 512 + 4 * 512>(addr);
+            return __builtin_bit_cast(v8bf, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
+        } else {
+            return *reinterpret_cast<const v8bf *>(p + ((off ^ (kk << 5)) + q * 32 * DMA_ROW_BYTES));
+        }
+    };
+    auto read_frags = [&](int slot, int sa, int sb, auto kkc) {
         const unsigned char *pa = smem_raw + sa * DMA_A_BYTES;
         const unsigned char *pb = smem_raw + sb * DMA_B_BYTES;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[slot][i] = *reinterpret_cast<const v8bf *>(pa + ((a_off ^ (kk << 5)) + i * 32 * DMA_ROW_BYTES));
+        for (int i = 0; i < TM; ++i) fa[slot][i] = frag(pa, a_off, i, kkc);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[slot][j] = *reinterpret_cast<const v8bf *>(pb + ((b_off ^ (kk << 5)) + j * 32 * DMA_ROW_BYTES));
+        for (int j = 0; j < TN; ++j) fb[slot][j] = frag(pb, b_off, j, kkc);
+    };
+    // the compiler does not know when the batch-major form's fragments have arrived
+    auto frags_landed = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     v16f acc[TM][TN];
@@ -662,12 +734,15 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Epilogue through LDS (uniform for the workgroup): both bf16 outputs wanted (and, except for
-    // the fused update, nothing else), workgroup tile inside the matrix, 16-byte alignment of every row
+    // Epilogue through LDS (uniform for the workgroup): bf16 output wanted, row-major or in both
+    // layouts (and, except for the fused update, nothing else), workgroup tile inside the
+    // matrix, 16-byte alignment of every row
     const bool use_mask = (KIND == GEMM_DA) && a.mask_in != nullptr && a.act == ACT_RELU;
-    const bool via_lds = !(KIND == GEMM_DW && a.k_chunk > 0) && a.C_bf16 != nullptr && a.Ct_bf16 != nullptr &&
-                         (KIND == GEMM_DW ? (a.C_f32 != nullptr && !a.write_grad) : a.C_f32 == nullptr) &&
-                         (m0 + BM <= a.M) && (n0 + BN <= a.N) && (a.ldcb & 7) == 0 && (a.ldct & 7) == 0 &&
+    const bool via_lds = !(KIND == GEMM_DW && a.k_chunk > 0) && a.C_bf16 != nullptr &&
+                         (KIND == GEMM_DW ? (a.Ct_bf16 != nullptr && a.C_f32 != nullptr && !a.write_grad)
+                                          : a.C_f32 == nullptr) &&
+                         (m0 + BM <= a.M) && (n0 + BN <= a.N) && (a.ldcb & 7) == 0 &&
+                         (a.Ct_bf16 == nullptr || (a.ldct & 7) == 0) &&
                          ((reinterpret_cast<size_t>(a.C_bf16) | reinterpret_cast<size_t>(a.Ct_bf16)) & 15) == 0 &&
                          (KIND != GEMM_DA || use_mask || (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
     // backward-data product: the ReLU decision bits of the lane's eight blocks are requested
@@ -701,7 +776,7 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
     // requests are issued by both wavefronts of a SIMD at the same time (the barrier keeps
     // them in step) and the MFMA pipe idles meanwhile.  Only the requests are conditional,
     // so that there is one MFMA stream.
-    auto group = [&](int slot, bool rd, int sa, int sb, int kk, bool ld, bool is_a, int t, int stage, int first) {
+    auto group = [&](int slot, bool rd, int sa, int sb, auto kk, bool ld, bool is_a, int t, int stage, int first) {
         const unsigned char *pa = smem_raw + sa * DMA_A_BYTES;
         const unsigned char *pb = smem_raw + sb * DMA_B_BYTES;
         const int rs = slot ^ 1;
@@ -715,14 +790,12 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
                 if (b < 2) {
                     if (rd) {
 #pragma unroll
-                        for (int q = 2 * b; q < 2 * b + 2; ++q)
-                            fa[rs][q] = *reinterpret_cast<const v8bf *>(pa + ((a_off ^ (kk << 5)) + q * 32 * DMA_ROW_BYTES));
+                        for (int q = 2 * b; q < 2 * b + 2; ++q) fa[rs][q] = frag(pa, a_off, q, kk);
                     }
                 } else if (b == 2) {
                     if (rd) {
 #pragma unroll
-                        for (int q = 0; q < TN; ++q)
-                            fb[rs][q] = *reinterpret_cast<const v8bf *>(pb + ((b_off ^ (kk << 5)) + q * 32 * DMA_ROW_BYTES));
+                        for (int q = 0; q < TN; ++q) fb[rs][q] = frag(pb, b_off, q, kk);
                     }
                 } else if (b == 4) {
                     if (ld) {
@@ -747,7 +820,7 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
         } else {
             asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
         }
-        read_frags(0, 0, 0, 0);
+        read_frags(0, 0, 0, KStep<0>());
         static_assert(G == 4, "the load schedule below is written for four k-steps per tile");
         int b_cur = 0, b_nxt = 1, b_ld = 2;  // B stages of tiles kt, kt+1, kt+2
         for (int kt = 0; kt < nkf; ++kt) {
@@ -756,21 +829,27 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
             // The explicit lgkmcnt(0) at the head of a group tells the compiler that the
             // fragments requested during the previous group have arrived (they have: five
             // MFMAs lie in between); it cannot track them across the small branches.
+            // (batch-major form: the compiler does not see the reads at all, and a scheduling
+            // barrier keeps the MFMAs behind the wait)
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            group(0, true, a_cur, b_cur, 1, next, true, kt + 1, a_cur ^ 1, 2);   // + second half of A(kt+1)
+            if (BMAJ) __builtin_amdgcn_sched_barrier(0);
+            group(0, true, a_cur, b_cur, KStep<1>(), next, true, kt + 1, a_cur ^ 1, 2);   // + second half of A(kt+1)
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            group(1, true, a_cur, b_cur, 2, next2, false, kt + 2, b_ld, 0);      // + B(kt+2): its stage held B(kt-1)
+            if (BMAJ) __builtin_amdgcn_sched_barrier(0);
+            group(1, true, a_cur, b_cur, KStep<2>(), next2, false, kt + 2, b_ld, 0);      // + B(kt+2): its stage held B(kt-1)
             __builtin_amdgcn_s_waitcnt(0xc07f);
-            group(0, true, a_cur, b_cur, 3, next2, false, kt + 2, b_ld, 2);
+            if (BMAJ) __builtin_amdgcn_sched_barrier(0);
+            group(0, true, a_cur, b_cur, KStep<3>(), next2, false, kt + 2, b_ld, 2);
             // Tile kt+1 must have landed (this wavefront's share; the barrier covers the others');
             // the four loads of B(kt+2) just issued may stay in flight.  This wavefront's reads of
             // tile kt must be done before anyone overwrites its stages.
             if (next2) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) again, this time visible to the compiler
+            if (BMAJ) __builtin_amdgcn_sched_barrier(0);
             // last k-step of tile kt; k-step 0 of tile kt+1 is requested from the stages that have
             // just been completed, and the first half of A(kt+2) goes into the stage just released
-            group(1, next, a_cur ^ 1, b_nxt, 0, next2, true, kt + 2, a_cur, 0);
+            group(1, next, a_cur ^ 1, b_nxt, KStep<0>(), next2, true, kt + 2, a_cur, 0);
             const int t = b_cur;
             b_cur = b_nxt;
             b_nxt = b_ld;
@@ -788,6 +867,18 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
             const int idx = tid + v * DMA_NT;
             const bool isA = idx < BM * 8;
             const int q = isA ? idx : idx - BM * 8;
+            if (BMAJ) {  // k-row q / 32, slot q % 32; k-rows past the end of the slice are zero
+                const int k = q >> 5, slot = q & 31;
+                const int chunk = slot ^ ((k & 3) << 2);
+                uint4 x = {0u, 0u, 0u, 0u};
+                if (kbase + k < klen) {
+                    const long long ld = isA ? a.lda : a.ldb;
+                    const long long col = min((long long)(isA ? m0 : n0) * 2 + chunk * 16, ld * 2 - 16);
+                    x = *reinterpret_cast<const uint4 *>((isA ? Ab : Bb) + (size_t)(kbase + k) * (size_t)ld * 2 + col);
+                }
+                *reinterpret_cast<uint4 *>(smem_raw + (isA ? 0 : DMA_B_BASE) + k * 512 + slot * 16) = x;
+                continue;
+            }
             const int R = q >> 3, c = q & 7;
             const int k = kbase + c * 8;
             uint4 x = {0u, 0u, 0u, 0u};
@@ -811,11 +902,18 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
                                        ((c ^ swz(R)) << 4)) = x;
         }
         __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < G; ++kk) {
-            read_frags(kk & 1, 0, 0, kk);
-            mfma_step(kk & 1);
-        }
+        read_frags(0, 0, 0, KStep<0>());
+        if (BMAJ) frags_landed();
+        mfma_step(0);
+        read_frags(1, 0, 0, KStep<1>());
+        if (BMAJ) frags_landed();
+        mfma_step(1);
+        read_frags(0, 0, 0, KStep<2>());
+        if (BMAJ) frags_landed();
+        mfma_step(0);
+        read_frags(1, 0, 0, KStep<3>());
+        if (BMAJ) frags_landed();
+        mfma_step(1);
     }
 
     if (KIND == GEMM_DW && a.k_chunk > 0) {
@@ -974,6 +1072,82 @@ __global__ __launch_bounds__(256) void rowsum_bias_kernel(const bf16_t *__restri
     }
 }
 
+// Bias gradient from the row-major delta D [B x ld] (16-byte aligned rows): column sums over
+// the batch in two steps, both in a fixed order.  Step 1, block (x, s): columns 512 x .. + 511 of
+// the rows of slice s; a thread owns 8 columns (one 16-byte load per row) and every fourth row,
+// four loads in flight; the four row lanes meet in LDS.  Step 2 adds the slices in index order
+// and applies Eq. (3) to the bias (or stores the gradient).
+constexpr int CSB_COLS = 512, CSB_MAX_SLICES = 128;
+__global__ __launch_bounds__(256) void colsum_bf16_kernel(const bf16_t *__restrict__ D, long long ld, int d,
+                                                          long long B, int rows_per_slice,
+                                                          float *__restrict__ partial)
+{
+    __shared__ float red[4][CSB_COLS + 8];
+    const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const long long c0 = (long long)blockIdx.x * CSB_COLS + cl * 8;
+    const long long r0 = (long long)blockIdx.y * rows_per_slice, r1 = min(B, r0 + (long long)rows_per_slice);
+    float s[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] = 0.f;
+    auto add = [&](const uint4 &x) {
+        const unsigned int w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s[2 * e] += __uint_as_float(w[e] << 16);
+            s[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+        }
+    };
+    if (c0 < ld) {  // ld is a multiple of 8: the whole 16-byte piece lies inside the row
+        const bf16_t *p = D + c0;
+        long long i = r0 + rl;
+        for (; i + 12 < r1; i += 16) {
+            uint4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const uint4 *>(p + (size_t)(i + 4 * u) * ld);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add(x[u]);
+        }
+        for (; i < r1; i += 4) add(*reinterpret_cast<const uint4 *>(p + (size_t)i * ld));
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[rl][cl * 8 + e] = s[e];
+    __syncthreads();
+    for (int c = threadIdx.x; c < CSB_COLS; c += 256) {
+        const long long col = (long long)blockIdx.x * CSB_COLS + c;
+        if (col < d) partial[(size_t)blockIdx.y * d + col] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+    }
+}
+
+__global__ __launch_bounds__(256) void colsum_bias_finalize_kernel(const float *__restrict__ partial, int slices,
+                                                                   int d, float *__restrict__ bias,
+                                                                   float *__restrict__ grad, float lr)
+{
+    // 64 columns per block, four lanes per column: lane q adds slices q, q + 4, .. (eight loads
+    // in flight), the four meet in LDS in lane order
+    __shared__ float red[4][64];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + c;
+    float s = 0.f;
+    if (j < d) {
+        int k = q;
+        for (; k + 28 < slices; k += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(k + 4 * u) * d + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; k < slices; k += 4) s += partial[(size_t)k * d + j];
+    }
+    red[q][c] = s;
+    __syncthreads();
+    if (q == 0 && j < d) {
+        const float t = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+        if (grad) grad[j] = t;
+        else bias[j] -= lr * t;
+    }
+}
+
 template <int BM, int BN, int BK>
 hipError_t launch_shape_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, const LaunchEvents &ev)
 {
@@ -1015,16 +1189,18 @@ hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, co
 {
     void (*k)(GemmBf16Args) = kind == GEMM_FWD  ? gemm_bf16_dma_kernel<GEMM_FWD>
                               : kind == GEMM_DA ? gemm_bf16_dma_kernel<GEMM_DA>
+                              : a.bmaj          ? gemm_bf16_dma_kernel<GEMM_DW, true>
                                                 : gemm_bf16_dma_kernel<GEMM_DW>;
+    const int slot = (kind == GEMM_DW && a.bmaj) ? 3 : (int)kind;
     static std::mutex attr_mu;
-    static bool attr_set[3] = {false, false, false};
+    static bool attr_set[4] = {false, false, false, false};
     {
         std::lock_guard<std::mutex> lk(attr_mu);
-        if (!attr_set[kind]) {
+        if (!attr_set[slot]) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)DMA_LDS_BYTES);
             if (e != hipSuccess) return e;
-            attr_set[kind] = true;
+            attr_set[slot] = true;
         }
     }
     a.tiles_m = (a.M + DMA_BM - 1) / DMA_BM;
@@ -1052,8 +1228,19 @@ hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, c
     const long long dma_tiles = (long long)((a.M + DMA_BM - 1) / DMA_BM) * ((a.N + DMA_BN - 1) / DMA_BN);
     const long long big_tiles = (long long)((a.M + 255) / 256) * ((a.N + 127) / 128);
     // the LDS-direct kernel addresses each operand with 32-bit byte offsets from its base
-    const bool dma_ok = a.a_vec && a.b_vec && (unsigned long long)a.M * (unsigned long long)a.lda * 2 < (1ull << 32) &&
-                        (unsigned long long)a.N * (unsigned long long)a.ldb * 2 < (1ull << 32);
+    // (batch-major operands: rows are batch rows, and only the first k-tile is addressed that way)
+    const bool dma_ok = a.a_vec && a.b_vec &&
+                        (a.bmaj ? ((unsigned long long)DMA_BK * (unsigned long long)a.lda * 2 < (1ull << 32) &&
+                                   (unsigned long long)DMA_BK * (unsigned long long)a.ldb * 2 < (1ull << 32) &&
+                                   a.lda >= a.M && a.ldb >= a.N)
+                                : ((unsigned long long)a.M * (unsigned long long)a.lda * 2 < (1ull << 32) &&
+                                   (unsigned long long)a.N * (unsigned long long)a.ldb * 2 < (1ull << 32)));
+    if (a.bmaj) {  // batch-major operands: weight gradient through the LDS-direct kernel only
+        if (kind != GEMM_DW || !dma_ok || (a.k_chunk > 0 && (!a.write_grad || a.C_bf16 || a.Ct_bf16 ||
+                                                              (a.k_chunk % DMA_BK) != 0)))
+            return hipErrorInvalidValue;
+        return launch_dma_bf16(kind, a, stream, ev);
+    }
     if (a.k_chunk > 0) {  // split weight gradient: only the LDS-direct kernel implements it
         if (kind != GEMM_DW || !dma_ok || !a.write_grad || a.C_bf16 || a.Ct_bf16 || (a.k_chunk % DMA_BK) != 0)
             return hipErrorInvalidValue;
@@ -1063,6 +1250,18 @@ hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, c
     if (forced == 4 || (forced == 0 && big_tiles >= 512)) return launch_shape_bf16<256, 128, 32>(kind, a, stream, ev);
     if (forced == 3) return launch_shape_bf16<128, 128, 32>(kind, a, stream, ev);
     return launch_shape_bf16<128, 128, 64>(kind, a, stream, ev);
+}
+
+bool gemm_bf16_dw_bmaj_ok(int M, int N, int K, long long lda, long long ldb, const void *A, const void *B)
+{
+    // what launch_gemm_bf16 asks of batch-major operands, and a product the LDS-direct kernel
+    // is chosen for anyway (split over the batch, or at least 128 tiles)
+    if ((lda & 7) || (ldb & 7) || ((reinterpret_cast<size_t>(A) | reinterpret_cast<size_t>(B)) & 15) || lda < M ||
+        ldb < N || (unsigned long long)DMA_BK * (unsigned long long)lda * 2 >= (1ull << 32) ||
+        (unsigned long long)DMA_BK * (unsigned long long)ldb * 2 >= (1ull << 32))
+        return false;
+    const long long tiles = (long long)((M + DMA_BM - 1) / DMA_BM) * ((N + DMA_BN - 1) / DMA_BN);
+    return tiles >= 128 || gemm_bf16_dw_splits_cap(M, N, K) > 1;
 }
 
 int gemm_bf16_dw_splits_cap(int M, int N, int K)
@@ -1113,6 +1312,27 @@ hipError_t launch_shadow(const float *W, int R, int C, void *shadow, long long l
     return launch_kernel(shadow_kernel, dim3((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64)), dim3(256),
                          stream, LaunchEvents(), W, R, C, static_cast<bf16_t *>(shadow), lds_,
                          static_cast<bf16_t *>(shadow_t), ldt);
+}
+
+int colsum_bias_slices(long long B)
+{
+    long long s = (B + 63) / 64;  // at least 64 rows per slice
+    if (s > CSB_MAX_SLICES) s = CSB_MAX_SLICES;
+    return s < 1 ? 1 : (int)s;
+}
+
+hipError_t launch_colsum_bias(const void *D, long long ld, int d, long long B, float *partial, float *bias,
+                              float *grad, float lr, hipStream_t stream, const LaunchEvents &ev)
+{
+    if ((ld & 7) != 0 || (reinterpret_cast<size_t>(D) & 15) != 0 || B <= 0) return hipErrorInvalidValue;
+    const int slices = colsum_bias_slices(B);
+    const int rows_per_slice = (int)((B + slices - 1) / slices);
+    hipError_t e = launch_kernel(colsum_bf16_kernel, dim3((unsigned)((ld + CSB_COLS - 1) / CSB_COLS), (unsigned)slices),
+                                 dim3(256), stream, ev, static_cast<const bf16_t *>(D), ld, d, B, rows_per_slice,
+                                 partial);
+    if (e != hipSuccess) return e;
+    return launch_kernel(colsum_bias_finalize_kernel, dim3((unsigned)((d + 63) / 64)), dim3(256), stream,
+                         LaunchEvents(), static_cast<const float *>(partial), slices, d, bias, grad, lr);
 }
 
 hipError_t launch_rowsum_bias(const void *Dt, long long ld, int d, long long B, float *bias, float *grad,

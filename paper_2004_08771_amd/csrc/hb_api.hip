@@ -132,6 +132,7 @@ struct hb_model {
     std::vector<int> ld8;                       // d_l rounded up to 8
     std::vector<void *> shadow, shadow_t;       // [1..L]
     std::vector<void *> act_bf, act_t;          // [1..L-1] / [0..L-1]
+    float *bias_partial = nullptr;              // slices x max d_l: column sums of a row-major delta
     std::vector<unsigned short *> relu_mask;    // [1..L-1], ReLU nets: decision bits of the hidden activations
     void *delta_bf[2] = {nullptr, nullptr};
     void *delta_t[2] = {nullptr, nullptr};
@@ -619,7 +620,17 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
     hipStream_t st = m->stream;
     const bool back = (mode != MODE_LOSS);
 
-    if (back)  // X^T for dW_1 = D_1^T X
+    // bmaj[l]: the weight gradient of layer l reads the row-major D_l and A_{l-1} themselves
+    // (batch-major operands); then neither D_l^T nor A_{l-1}^T is needed for it.  Transposed
+    // activations are still written for a sigmoid layer, whose backward-data epilogue reads them.
+    std::vector<char> bmaj((size_t)L + 2, 0);
+    static const bool bmaj_off = getenv("HB_BF16_BMAJ") && atoi(getenv("HB_BF16_BMAJ")) == 0;  // tuning aid
+    if (back && !bmaj_off)
+        for (int l = 1; l <= L; ++l)
+            bmaj[l] = gemm_bf16_dw_bmaj_ok(m->dims[l], m->dims[l - 1], Bi, m->ld8[l],
+                                           (l == 1) ? (long long)m->dims[0] : (long long)m->ld8[l - 1],
+                                           m->delta_bf[l & 1], (l == 1) ? X : m->act_bf[l - 1]);
+    if (back && !bmaj[1])  // X^T for dW_1 = D_1^T X
         HB_HIP(launch_transpose_bf16(X, m->dims[0], m->act_t[0], ldB, Bi, m->dims[0], st,
                                      prof_begin(m, HB_K_OTHER, 1, 0, 0, 0, 0.0, 4.0 * B * m->dims[0])));
     for (int l = 1; l <= L; ++l) {
@@ -639,8 +650,10 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.C_bf16 = m->act_bf[l];
             g.ldcb = m->ld8[l];
             if (back) {
-                g.Ct_bf16 = m->act_t[l];
-                g.ldct = ldB;
+                if (!bmaj[l + 1] || m->act == ACT_SIGMOID) {
+                    g.Ct_bf16 = m->act_t[l];
+                    g.ldct = ldB;
+                }
                 if (m->act == ACT_RELU) {  // the decisions the backward-data product of layer l+1 applies
                     g.mask_out = m->relu_mask[l];
                     g.mask_nb = (m->dims[l] + 31) / 32;
@@ -671,8 +684,9 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
     LossFinalize fin = {m->d_loss_partials, loss_grid_blocks(B, la.K), B, m->d_loss, d_loss_user};
     HB_HIP(launch_loss_finalize(fin, st));
     if (!back) return HB_OK;
-    HB_HIP(launch_transpose_bf16(m->delta_bf[L & 1], m->ld8[L], m->delta_t[L & 1], ldB, Bi, m->dims[L], st,
-                                 prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * B * m->dims[L])));
+    if (!bmaj[L])
+        HB_HIP(launch_transpose_bf16(m->delta_bf[L & 1], m->ld8[L], m->delta_t[L & 1], ldB, Bi, m->dims[L], st,
+                                     prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * B * m->dims[L])));
 
     const bool grad_mode = (mode == MODE_GRAD);
     for (int l = L; l >= 1; --l) {
@@ -698,17 +712,27 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.act = m->act;
             g.C_bf16 = m->delta_bf[(l - 1) & 1];
             g.ldcb = m->ld8[l - 1];
-            g.Ct_bf16 = m->delta_t[(l - 1) & 1];
-            g.ldct = ldB;
+            if (!bmaj[l - 1]) {
+                g.Ct_bf16 = m->delta_t[(l - 1) & 1];
+                g.ldct = ldB;
+            }
             HB_HIP(launch_gemm_bf16(GEMM_DA, g, st,
                                     prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
                                                2.0 * ((double)g.M * g.K + (double)g.N * g.K + 3.0 * g.M * g.N))));
         }
         GemmBf16Args g = {};
-        g.A = m->delta_t[l & 1];
-        g.lda = ldB;
-        g.B = m->act_t[l - 1];
-        g.ldb = ldB;
+        if (bmaj[l]) {
+            g.bmaj = 1;
+            g.A = m->delta_bf[l & 1];
+            g.lda = m->ld8[l];
+            g.B = (l == 1) ? X : m->act_bf[l - 1];
+            g.ldb = (l == 1) ? m->dims[0] : m->ld8[l - 1];
+        } else {
+            g.A = m->delta_t[l & 1];
+            g.lda = ldB;
+            g.B = m->act_t[l - 1];
+            g.ldb = ldB;
+        }
         g.M = m->dims[l];
         g.N = m->dims[l - 1];
         g.K = Bi;
@@ -727,7 +751,9 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.Ct_bf16 = m->shadow_t[l];
             g.ldct = m->ld8[l];
         }
-        int sp = m->dw_partial ? gemm_bf16_dw_splits(g.M, g.N, g.K, g.lda, g.ldb) : 1;
+        int sp = m->dw_partial ? (g.bmaj ? gemm_bf16_dw_splits_cap(g.M, g.N, g.K)
+                                         : gemm_bf16_dw_splits(g.M, g.N, g.K, g.lda, g.ldb))
+                               : 1;
         // never more slices than the buffer allocated at configure time holds
         if (sp > 1 && (size_t)sp * (size_t)g.M * (size_t)g.N > m->dw_partial_cap)
             sp = (int)(m->dw_partial_cap / ((size_t)g.M * (size_t)g.N));
@@ -759,10 +785,17 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
                                                2.0 * ((double)g.M * g.K + (double)g.N * g.K) +
                                                    (grad_mode ? 4.0 : 12.0) * g.M * g.N)));
         }
-        HB_HIP(launch_rowsum_bias(m->delta_t[l & 1], ldB, m->dims[l], B, m->d_params + m->b_off[l],
-                                  grad_mode ? d_grad_flat + m->b_off[l] : nullptr, lr, st,
-                                  prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)B * m->dims[l],
-                                             2.0 * B * m->dims[l])));
+        if (bmaj[l])
+            HB_HIP(launch_colsum_bias(m->delta_bf[l & 1], m->ld8[l], m->dims[l], B, m->bias_partial,
+                                      m->d_params + m->b_off[l], grad_mode ? d_grad_flat + m->b_off[l] : nullptr,
+                                      lr, st,
+                                      prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)B * m->dims[l],
+                                                 2.0 * B * m->dims[l])));
+        else
+            HB_HIP(launch_rowsum_bias(m->delta_t[l & 1], ldB, m->dims[l], B, m->d_params + m->b_off[l],
+                                      grad_mode ? d_grad_flat + m->b_off[l] : nullptr, lr, st,
+                                      prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)B * m->dims[l],
+                                                 2.0 * B * m->dims[l])));
     }
     return HB_OK;
 }
@@ -1116,6 +1149,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
             if (need > 0 && rc == HB_OK) rc = dev_alloc(m, &m->dw_partial, need);
             if (rc == HB_OK) m->dw_partial_cap = need;
         }
+        if (rc == HB_OK) rc = dev_alloc(m, &m->bias_partial, (size_t)colsum_bias_slices(max_B) * (size_t)max_d);
     }
     if (m->sparse && rc == HB_OK) {
         const size_t d0 = (size_t)m->dims[0];

@@ -107,6 +107,9 @@ struct GemmBf16Args {
     int act;
     int write_grad;
     float lr;
+    // weight gradient with batch-major operands: A[k * lda + m], B[k * ldb + n] (the row-major
+    // deltas and activations themselves; LDS-direct kernel only, see gemm_bf16_dw_bmaj_ok)
+    int bmaj;
     int tiles_m, tiles_n;
     // weight gradient split over the contraction (the batch): slice s covers k in
     // [s k_chunk, (s+1) k_chunk) and writes its plain fp32 partial product at
@@ -121,6 +124,8 @@ hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream,
 // gemm_bf16_dw_splits returns for any K <= max_K and any leading dimensions (it is
 // non-decreasing in K): the figure to size the slice buffer with.
 int gemm_bf16_dw_splits(int M, int N, int K, long long lda, long long ldb);
+// The weight gradient M x N over K batch rows can take its operands batch-major (bmaj).
+bool gemm_bf16_dw_bmaj_ok(int M, int N, int K, long long lda, long long ldb, const void *A, const void *B);
 int gemm_bf16_dw_splits_cap(int M, int N, int K);
 // out[i] = sum_s partial[s * stride + i]  (grad != null: written there)  or  master[i] -= lr * sum
 hipError_t launch_dw_reduce(const float *partial, int splits, long long stride, long long count, float *master,
@@ -133,6 +138,12 @@ hipError_t launch_shadow(const float *W, int R, int C, void *shadow, long long l
 // g[j] = sum_b Dt[j*ld + b];  bias[j] -= lr g[j]  (grad == null)  or  grad[j] = g[j]
 hipError_t launch_rowsum_bias(const void *Dt, long long ld, int d, long long B, float *bias, float *grad,
                               float lr, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
+
+// the same from the row-major delta D [B x ld] (ld % 8 == 0, 16-byte aligned): column sums in
+// colsum_bias_slices(B) slices of the batch (partial: slices x d floats), added in index order
+int colsum_bias_slices(long long B);
+hipError_t launch_colsum_bias(const void *D, long long ld, int d, long long B, float *partial, float *bias,
+                              float *grad, float lr, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
 // ---------------------------------------------------------------- loss / delta
 struct LossArgs {
