@@ -98,11 +98,32 @@ struct TileB {
     }
 };
 
-__device__ __forceinline__ float act_fwd(float z, int act)
+// The activation is a template argument of the epilogues: tested at run time per value, it
+// became three scalar branches in front of each of a lane's 128 outputs (about 5 us per
+// 256 x 256 tile, with the MFMA pipes idle).
+template <int ACT>
+__device__ __forceinline__ float act_fwd(float z)
 {
-    if (act == ACT_SIGMOID) return __builtin_amdgcn_rcpf(1.0f + __expf(-z));
-    if (act == ACT_RELU) return fmaxf(z, 0.f);
+    if (ACT == ACT_SIGMOID) return __builtin_amdgcn_rcpf(1.0f + __expf(-z));
+    if (ACT == ACT_RELU) return fmaxf(z, 0.f);
     return z;
+}
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
+// calls f(IntC<activation>, IntC<mask ? 1 : 0>) with the run-time activation as a constant
+template <typename F>
+__device__ __forceinline__ void with_activation(int act, bool mask, F &&f)
+{
+    if (act == ACT_RELU) {
+        if (mask) f(IntC<ACT_RELU>(), IntC<1>());
+        else f(IntC<ACT_RELU>(), IntC<0>());
+    } else if (act == ACT_SIGMOID) {
+        f(IntC<ACT_SIGMOID>(), IntC<0>());
+    } else {
+        f(IntC<ACT_NONE>(), IntC<0>());
+    }
 }
 
 // ReLU decision bits of one 32 x 32 block (see GemmBf16Args::mask_out): position of the value
@@ -143,14 +164,16 @@ constexpr size_t lds_bytes_bf16()
 // guards, and what a column block needs from memory (bias, the activations of the
 // backward-data derivative, the fp32 master weights of the fused update) is requested before
 // its first use, so that those loads are in flight together instead of one round trip each.
-template <int KIND, int TM, int TN, bool FULL>
+// ACT: the activation (forward, backward-data).  MASK: the ReLU decision bits are written
+// (forward: mask_out) / read instead of the activations (backward-data: mask_in).
+template <int KIND, int TM, int TN, bool FULL, int ACT, bool MASK>
 __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (&acc)[TM][TN], int mw, int nw, int r,
                                                    int h)
 {
     const bool has_cf = a.C_f32 != nullptr, has_cb = a.C_bf16 != nullptr;
     const bool has_ct = a.Ct_bf16 != nullptr && !(KIND == GEMM_DW && a.write_grad);
     const bool use_t = (KIND == GEMM_DA) && a.aux_t != nullptr && (a.ldauxt & 3) == 0;
-    const bool use_mask = (KIND == GEMM_DA) && a.mask_in != nullptr && a.act == ACT_RELU;
+    constexpr bool use_mask = (KIND == GEMM_DA) && MASK;
     const bool ct_vec = (a.ldct & 3) == 0;
     // per-lane byte offsets (row part 4 h, column part r)
     const unsigned lo_cf = (unsigned)(4 * h * (int)a.ldc + r) * 4u;
@@ -216,10 +239,10 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                     float val = acc[i][j][4 * q + e];
                     if (FULL || (mq + e < a.M && n_ok)) {
                         if (KIND == GEMM_FWD) {
-                            val = act_fwd(val + bias, a.act);
+                            val = act_fwd<ACT>(val + bias);
                             if (has_cf)
                                 *reinterpret_cast<float *>(cf0 + ((size_t)(mb + e) * a.ldc + nb) * 4 + lo_cf) = val;
-                            if (a.mask_out != nullptr) {
+                            if (MASK) {
                                 const bf16_t b = f2bf(val);
                                 if ((b & 0x7fffu) != 0 && (b & 0x8000u) == 0) mbits |= 1u << relu_bit_pos(q, e);
                             }
@@ -234,8 +257,8 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                                 o = bf2f(*reinterpret_cast<const bf16_t *>(ax0 + ((size_t)(mb + e) * a.ldaux + nb) * 2 +
                                                                             lo_ax));
                             }
-                            if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
-                            else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
+                            if (ACT == ACT_SIGMOID) val *= o * (1.f - o);
+                            else if (ACT == ACT_RELU) val = (o > 0.f) ? val : 0.f;
                         } else {  // GEMM_DW
                             float *cf = reinterpret_cast<float *>(cf0 + ((size_t)(mb + e) * a.ldc + nb) * 4 + lo_cf);
                             if (!a.write_grad) val = (FULL ? w[4 * q + e] : *cf) - a.lr * val;  // Eq. (3), fp32 master
@@ -263,7 +286,7 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                 // accumulators live it runs out of registers
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (KIND == GEMM_FWD && a.mask_out != nullptr && (FULL || (mw + i * 32 < a.M && nb < a.N)))
+            if (KIND == GEMM_FWD && MASK && (FULL || (mw + i * 32 < a.M && nb < a.N)))
                 a.mask_out[((size_t)((mw + i * 32) >> 5) * a.mask_nb + (nb >> 5)) * 64 + 32 * h + r] =
                     (unsigned short)mbits;
         }
@@ -274,12 +297,18 @@ template <int KIND, int TM, int TN>
 __device__ __forceinline__ void epilogue_bf16(const GemmBf16Args &a, v16f (&acc)[TM][TN], int mw, int nw, int r,
                                               int h)
 {
+    const bool mask = KIND == GEMM_FWD  ? (a.mask_out != nullptr && a.act == ACT_RELU)
+                      : KIND == GEMM_DA ? (a.mask_in != nullptr && a.act == ACT_RELU)
+                                        : false;
     const bool full = (mw + 32 * TM <= a.M) && (nw + 32 * TN <= a.N) &&
                       (a.Ct_bf16 == nullptr || (a.ldct & 3) == 0) &&
-                      (KIND != GEMM_DA || (a.mask_in != nullptr && a.act == ACT_RELU) ||
-                       (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
-    if (full) epilogue_bf16_impl<KIND, TM, TN, true>(a, acc, mw, nw, r, h);
-    else epilogue_bf16_impl<KIND, TM, TN, false>(a, acc, mw, nw, r, h);
+                      (KIND != GEMM_DA || mask || (a.aux_t != nullptr && (a.ldauxt & 3) == 0));
+    with_activation(KIND == GEMM_DW ? (int)ACT_NONE : a.act, mask, [&](auto act_c, auto mask_c) {
+        constexpr int ACT = decltype(act_c)::value;
+        constexpr bool MASK = decltype(mask_c)::value != 0;
+        if (full) epilogue_bf16_impl<KIND, TM, TN, true, ACT, MASK>(a, acc, mw, nw, r, h);
+        else epilogue_bf16_impl<KIND, TM, TN, false, ACT, MASK>(a, acc, mw, nw, r, h);
+    });
 }
 
 // Workgroup tile BM x BN, four wavefronts as 2 x 2, each (BM/2) x (BN/2) = TM x TN blocks of
@@ -459,11 +488,11 @@ static_assert(128 * EPI_SC <= EPI_REGION && 64 * EPI_ST <= EPI_REGION && 8 * EPI
 
 // mword: backward-data product with ReLU decision bits (use_mask): the lane's words of its eight
 // blocks, requested by the caller before the main loop.
-template <int KIND>
+template <int KIND, int ACT, bool MASK>
 __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&acc)[4][2], unsigned char *region,
-                                                  int mw, int nw, int lane, const unsigned (&mword)[4][2],
-                                                  bool use_mask)
+                                                  int mw, int nw, int lane, const unsigned (&mword)[4][2])
 {
+    constexpr bool use_mask = (KIND == GEMM_DA) && MASK;
     constexpr int TM = 4, TN = 2;
     const int r = lane & 31, h = lane >> 5;
     // ---- values -> bf16, four consecutive rows packed per (i, j, q)
@@ -511,15 +540,15 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
                 for (int e = 0; e < 4; ++e) {
                     float val = acc[i][j][4 * q + e];
                     if (KIND == GEMM_FWD) {
-                        val = act_fwd(val + bias, a.act);
+                        val = act_fwd<ACT>(val + bias);
                     } else if (KIND == GEMM_DA) {
                         if (use_mask) {
                             val = relu_keep(val, mword[i][j], q, e);
                         } else {
                             const unsigned int pw = (e < 2) ? ot[i][q].x : ot[i][q].y;
                             const float o = __uint_as_float((e & 1) ? (pw & 0xffff0000u) : (pw << 16));
-                            if (a.act == ACT_SIGMOID) val *= o * (1.f - o);
-                            else if (a.act == ACT_RELU) val = (o > 0.f) ? val : 0.f;
+                            if (ACT == ACT_SIGMOID) val *= o * (1.f - o);
+                            else if (ACT == ACT_RELU) val = (o > 0.f) ? val : 0.f;
                         }
                     } else {  // Eq. (3) on the fp32 master weight, stored back directly
                         val = w[e] - a.lr * val;
@@ -557,7 +586,7 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
     }
     // ---- forward product of a ReLU layer: the decision bits of the lane's eight blocks, worked
     // out while the stores above drain
-    if (KIND == GEMM_FWD && a.mask_out != nullptr) {
+    if (KIND == GEMM_FWD && MASK) {
         unsigned short *const mo = a.mask_out + ((size_t)(mw >> 5) * a.mask_nb + (nw >> 5)) * 64 + lane;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -926,8 +955,11 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
             // the last fragments were read before the loop's last barrier.  A K tail, or no
             // whole k-tile at all, ends with reads of stage 0.
             if (ktail > 0 || nkf == 0) __syncthreads();
-            epilogue_bf16_lds<KIND>(a, acc, smem_raw + wave * EPI_REGION, m0 + wm * 128, n0 + wn * 64, lane, mword,
-                                    use_mask);
+            const bool mask = (KIND == GEMM_FWD) ? (a.mask_out != nullptr && a.act == ACT_RELU) : use_mask;
+            with_activation(KIND == GEMM_DW ? (int)ACT_NONE : a.act, mask, [&](auto act_c, auto mask_c) {
+                epilogue_bf16_lds<KIND, decltype(act_c)::value, decltype(mask_c)::value != 0>(
+                    a, acc, smem_raw + wave * EPI_REGION, m0 + wm * 128, n0 + wn * 64, lane, mword);
+            });
         } else {
             epilogue_bf16<KIND, TM, TN>(a, acc, m0 + wm * 128, n0 + wn * 64, r, h);
         }

@@ -153,6 +153,19 @@ __device__ __forceinline__ float sigmoidf_fast(float z)
     return __builtin_amdgcn_rcpf(1.0f + __expf(-z));  // v_rcp_f32: 1 ulp, no division sequence
 }
 
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
+// calls f(IntC<activation>) with the run-time activation as a constant
+template <typename F>
+__device__ __forceinline__ void with_activation(int act, F &&f)
+{
+    if (act == ACT_SIGMOID) f(IntC<ACT_SIGMOID>());
+    else if (act == ACT_RELU) f(IntC<ACT_RELU>());
+    else f(IntC<ACT_NONE>());
+}
+
 // LDS floats one workgroup of this shape needs (two stages of an A and a B tile)
 template <int BM, int BN, int BK, bool A_KMAJ, bool B_KMAJ>
 constexpr int lds_floats()
@@ -391,7 +404,11 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
 
     // ---- epilogue.  acc[i][j][v] is C(row, col) with
     //      row = 8 (v / 4) + 4 h + (v % 4), col = r   inside its 32 x 32 block.
+    // The activation enters as a constant: tested per value at run time it was three scalar
+    // branches in front of every one of the lane's outputs.
     float *__restrict__ C = static_cast<float *>(a.C) + (size_t)split * a.c_split_stride;
+    auto epilogue = [&](auto act_c) {
+    constexpr int ACT = decltype(act_c)::value;
     if (a_in && b_in) {
         // Interior tile: no guards.  The backward-data product requests the 16 activation
         // values a lane needs for the derivative together; behind a bounds check per element
@@ -415,11 +432,11 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                     if (CHAINS == 2) x += acc[i][j][CHAINS - 1][v];
                     if (KIND == GEMM_FWD) {
                         x += bias;
-                        if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
-                        else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
+                        if (ACT == ACT_SIGMOID) x = sigmoidf_fast(x);
+                        else if (ACT == ACT_RELU) x = fmaxf(x, 0.f);
                     } else if (KIND == GEMM_DA) {
-                        if (a.act == ACT_SIGMOID) x *= o[v] * (1.f - o[v]);
-                        else if (a.act == ACT_RELU) x = (o[v] > 0.f) ? x : 0.f;
+                        if (ACT == ACT_SIGMOID) x *= o[v] * (1.f - o[v]);
+                        else if (ACT == ACT_RELU) x = (o[v] > 0.f) ? x : 0.f;
                     }
                     C[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldc + n] = x;
                 }
@@ -442,18 +459,20 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                     if (CHAINS == 2) x += acc[i][j][CHAINS - 1][v];
                     if (KIND == GEMM_FWD) {
                         x += bias;
-                        if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
-                        else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
+                        if (ACT == ACT_SIGMOID) x = sigmoidf_fast(x);
+                        else if (ACT == ACT_RELU) x = fmaxf(x, 0.f);
                     } else if (KIND == GEMM_DA) {
                         const float o = static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
-                        if (a.act == ACT_SIGMOID) x *= o * (1.f - o);
-                        else if (a.act == ACT_RELU) x = (o > 0.f) ? x : 0.f;
+                        if (ACT == ACT_SIGMOID) x *= o * (1.f - o);
+                        else if (ACT == ACT_RELU) x = (o > 0.f) ? x : 0.f;
                     }
                     C[(size_t)m * a.ldc + n] = x;
                 }
             }
         }
     }
+    };
+    with_activation(KIND == GEMM_DW ? (int)ACT_NONE : a.act, epilogue);
 }
 
 template <int BM, int BN, int BK, int WAVES_M, bool A_KMAJ, bool B_KMAJ, int KIND>
@@ -623,25 +642,28 @@ __device__ __forceinline__ void gemm_f32_small_tile(const GemmArgs &a, float *sm
         for (int p = 0; p < 4; ++p)
             o4[p] = static_cast<const float *>(a.aux)[(size_t)(m0 + 8 * wave + 2 * p + h) * a.ldaux + n];
     }
+    with_activation(KIND == GEMM_DW ? (int)ACT_NONE : a.act, [&](auto act_c) {
+        constexpr int ACT = decltype(act_c)::value;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int row = 8 * wave + 2 * p + h;
-        const int m = m0 + row;
-        float x = smem[row * RED_LD + r] + smem[RED + row * RED_LD + r] +
-                  (smem[2 * RED + row * RED_LD + r] + smem[3 * RED + row * RED_LD + r]);
-        if (m < a.M && n_ok) {
-            if (KIND == GEMM_FWD) {
-                x += bias;
-                if (a.act == ACT_SIGMOID) x = sigmoidf_fast(x);
-                else if (a.act == ACT_RELU) x = fmaxf(x, 0.f);
-            } else if (KIND == GEMM_DA) {
-                const float o = (a_in && b_in) ? o4[p] : static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
-                if (a.act == ACT_SIGMOID) x *= o * (1.f - o);
-                else if (a.act == ACT_RELU) x = (o > 0.f) ? x : 0.f;
+        for (int p = 0; p < 4; ++p) {
+            const int row = 8 * wave + 2 * p + h;
+            const int m = m0 + row;
+            float x = smem[row * RED_LD + r] + smem[RED + row * RED_LD + r] +
+                      (smem[2 * RED + row * RED_LD + r] + smem[3 * RED + row * RED_LD + r]);
+            if (m < a.M && n_ok) {
+                if (KIND == GEMM_FWD) {
+                    x += bias;
+                    if (ACT == ACT_SIGMOID) x = sigmoidf_fast(x);
+                    else if (ACT == ACT_RELU) x = fmaxf(x, 0.f);
+                } else if (KIND == GEMM_DA) {
+                    const float o = (a_in && b_in) ? o4[p] : static_cast<const float *>(a.aux)[(size_t)m * a.ldaux + n];
+                    if (ACT == ACT_SIGMOID) x *= o * (1.f - o);
+                    else if (ACT == ACT_RELU) x = (o > 0.f) ? x : 0.f;
+                }
+                C[(size_t)m * a.ldc + n] = x;
             }
-            C[(size_t)m * a.ldc + n] = x;
         }
-    }
+    });
     if (KIND == GEMM_DW) {
         if (do_colsum && tid < 32 && m0 + tid < a.M)
             a.colsum[(size_t)split * a.M + m0 + tid] = colsum;

@@ -853,9 +853,14 @@ def test_bf16_overshooting_step_on_one_row():
     # every product of the two 2050-wide layers takes the LDS-direct 256 x 256 x 64 kernel (at least
     # 128 tiles: 15 x 9) with a steady-state k loop: forward K = 520 and 2050 (8 and 32 k-tiles +
     # tails), backward-data K = 2050 and 10 (tail only), weight gradients K = B = 3700 (split over
-    # the batch); ragged edges in every dimension
+    # the batch, operands batch-major: the row-major deltas and activations, a ragged last k-tile
+    # in every slice); ragged edges in every dimension
     ((520, 2050, 2050, 10), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 3700),
     ((520, 2050, 2050, 10), hi.ACT_SIGMOID, hi.LOSS_SOFTMAX_CE, 3700),
+    # rows of X that are not 16-byte aligned (d_0 = 516): the first layer's weight gradient cannot
+    # read X itself and takes the transposed copies of X and of D_1 (written by the transpose
+    # kernel and by the backward-data epilogue of layer 2), the other layers the row-major tensors
+    ((516, 2050, 2050, 10), hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, 3700),
 ])
 def test_bf16_wide_layers_with_many_k_tiles(dims, act, loss, B):
     params, X, y = _problem(dims, loss, B, seed=600 + B + len(dims), bias_scale=0.1)
