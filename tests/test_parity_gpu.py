@@ -872,11 +872,12 @@ def test_bf16_wide_layers_with_many_k_tiles(dims, act, loss, B):
 
 @pytest.mark.parametrize("B", [130, 259, 3841, 3842, 3843])
 def test_bf16_relu_batch_edges_of_the_backward_data_epilogue(B):
-    """The backward-data epilogue takes the ReLU decision from the stored activations, four batch
-    rows per 8-byte read of their transposed copy; in the last group of a ragged batch one, two or
-    three of the four rows exist (B mod 4 = 1, 2, 3).  130 and 259 rows run the 128 x 128 kernel,
-    3841-3843 the LDS-direct 256 x 256 kernel (15 full tile rows and one row tile holding 1-3
-    rows), with 2050 = 8 x 256 + 2 columns: ragged in both directions."""
+    """The backward-data epilogue applies the ReLU decisions the forward epilogue left as bits, 16 per
+    lane and 32 x 32 block of the activations; a block cut by the end of the batch or of a row is
+    written and read under guards, and in the last group of four rows of a ragged batch one, two
+    or three exist (B mod 4 = 1, 2, 3).  130 and 259 rows run the 128 x 128 kernel, 3841-3843 the
+    LDS-direct 256 x 256 kernel (15 full tile rows and one row tile holding 1-3 rows), with
+    2050 = 8 x 256 + 2 columns: ragged in both directions."""
     dims = (264, 2050, 520, 5)
     params, X, y = _problem(dims, hi.LOSS_SOFTMAX_CE, B, seed=700 + B, bias_scale=0.1)
     check_bf16_case(dims, hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, params, X, y, lr=0.1, condition_relu=False)
