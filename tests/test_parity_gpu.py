@@ -883,6 +883,53 @@ def test_bf16_relu_batch_edges_of_the_backward_data_epilogue(B):
     check_bf16_case(dims, hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, params, X, y, lr=0.1, condition_relu=False)
 
 
+@pytest.mark.parametrize("act", [hi.ACT_RELU, hi.ACT_SIGMOID])
+def test_bf16_one_replica_through_changing_batch_sizes(act):
+    """What Adaptive Hogbatch does to the GPU worker: ONE replica, configured for the largest batch,
+    takes steps on batches of changing size.  The sizes move the weight gradients between their
+    two forms from step to step (below 2048 rows the transposed copies and K-major operands, from
+    2048 rows on the row-major tensors themselves, split over the batch) and the other products
+    between the 128 x 128 and the LDS-direct kernel, so every step finds the buffers as another
+    form left them.  Each step is compared with an oracle step from the replica's parameters
+    before it (read back), so errors do not add up over the ladder."""
+    import paper_2004_08771_amd as hb
+    torch = _torch()
+    dims, loss, lr = (264, 2050, 520, 5), hi.LOSS_SOFTMAX_CE, 0.1
+    sizes = [300, 2500, 64, 4096, 1000, 2049, 1]
+    rng = np.random.default_rng(4242 + act)
+    params = hi.xavier_uniform_params(dims, rng, bias_scale=0.1)
+    m = hb.Model(dims, act, loss).configure(hb.HB_BF16_F32MASTER, max(sizes))
+    m.set_params(params)
+    try:
+        for step, B in enumerate(sizes):
+            X = rng.standard_normal((B, dims[0]), dtype=np.float32)
+            y = rng.integers(0, dims[-1], size=B).astype(np.int32)
+            before = np.empty_like(params)
+            m.get_params(before)
+            dX = torch.from_numpy(X).cuda().to(torch.bfloat16)
+            dy = torch.from_numpy(y).cuda()
+            ls = m.batch_step(dX, dy, B, lr)
+            after = np.empty_like(params)
+            m.get_params(after)
+            Wr = mf.round_weights_bf16(dims, before)
+            Xr = mf.bf16_round(X).astype(np.float64)
+            relu_on = None
+            if act == hi.ACT_RELU:
+                acts = gpu_hidden_activations(m, dims, B)
+                relu_on, _, _ = relu_decisions(dims, Wr, Xr, acts, EPS_Z_BF16, store_bf16=True)
+            l_ref, g_ref, scale = mf.batch_grad(dims, act, loss, Wr, Xr, y, with_error_scale=True, relu_on=relu_on)
+            p_ref = oracle.sgd_update(before, g_ref, lr)
+            what = f"step {step}, B = {B}"
+            assert abs(ls - l_ref) <= TOL_BF16 * abs(l_ref), f"{what}: loss {ls} vs {l_ref}"
+            assert_close(dims, after, p_ref, TOL_BF16, f"{what}: parameters after the step", scale=scale,
+                         scale_factor=lr, rho=RHO_BF16)
+            # the step itself, not only its sum with the old parameters: lr * g is small next to W
+            assert_close(dims, (before.astype(np.float64) - after) / lr, g_ref, TOL_BF16, f"{what}: applied gradient",
+                         scale=scale, rho=RHO_BF16)
+    finally:
+        m.destroy()
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_bf16_shapes_match_oracle(seed):
     """Seeded sweep of the bf16 mode over the same shape generator as the fp32 sweep."""
