@@ -2,18 +2,20 @@
 // weights and accumulation) of the mini-batch step: the same three layer products as the
 // fp32 path (Section 3 of the paper, Eq. (1) forward and Eq. (2) backward).
 //
-// gfx950 design: ONE kernel shape -- both operands K-major ("NT"), the layout
-// v_mfma_f32_32x32x16_bf16 wants (8 consecutive k per lane) -- and no transposing loads in
-// the hot loop.  The other two products are brought to that shape by keeping every bf16
-// tensor that is later contracted over its row index in a second, transposed copy, written
-// by the epilogue that produces it:
-//   forward   Z_l     = A_{l-1} . W_l^T        A = A_{l-1} [B x d],   B = W_l   [d_l x d_{l-1}]
-//   backward  D_{l-1} = (D_l . W_l) * f'       A = D_l     [B x d_l], B = W_l^T [d_{l-1} x d_l]
-//   gradient  dW_l    = D_l^T . A_{l-1}        A = D_l^T   [d_l x B], B = A_{l-1}^T [d_{l-1} x B]
-// 256-thread workgroups, 256 x 128 x 32 (or 128 x 128 x 32) tiles, four wavefronts of 4 x 2 (2 x 2)
-// MFMA blocks, operands global -> registers -> LDS (double-buffered, 16-byte accesses throughout).
-// The weight-gradient epilogue applies the SGD update (Eq. (3)) to the fp32 master weights
-// and refreshes both bf16 copies of W_l in the same pass.
+// gfx950 design: v_mfma_f32_32x32x16_bf16 wants 8 consecutive k per lane.
+//   forward   Z_l     = A_{l-1} . W_l^T        A = A_{l-1} [B x d],   B = W_l   [d_l x d_{l-1}]   both K-major
+//   backward  D_{l-1} = (D_l . W_l) * f'       A = D_l     [B x d_l], B = W_l^T [d_{l-1} x d_l]   both K-major
+//   gradient  dW_l    = D_l^T . A_{l-1}        contraction over the batch, the ROW index of both
+// The weights exist as two bf16 copies (W_l and W_l^T), rewritten by the weight-gradient
+// epilogue, which also applies the SGD update (Eq. (3)) to the fp32 master weights.  The
+// weight gradient reads D_l and A_{l-1} as they are, batch-major, through the transposing LDS
+// read of gfx950 (LDS-direct kernel, BMAJ form); only where it cannot (rows that are not
+// 16-byte aligned, products too small for 256 x 256 tiles) do the epilogues that produce a
+// tensor also write its transposed copy, and the product runs K-major like the other two.
+// Two kernel families: gemm_bf16_nt_kernel (256-thread workgroups, 256 x 128 x 32 or
+// 128 x 128 tiles, four wavefronts, operands global -> registers -> LDS, double-buffered,
+// 16-byte accesses throughout) for small or unaligned products, gemm_bf16_dma_kernel
+// (256 x 256 x 64, LDS-direct loads) for the large ones.
 #include "hb_internal.h"
 
 #include <mutex>

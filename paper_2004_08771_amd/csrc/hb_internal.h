@@ -72,8 +72,9 @@ hipError_t launch_gemm_f32_bwd_pair(GemmArgs da, GemmArgs dw, int max_splits, in
 // (so that the caller can size the partial buffers).
 int gemm_f32_dw_splits(int M, int N, int K, int max_splits);
 
-// ---------------------------------------------------------------- bf16 MFMA GEMM (NT only)
-// C[M x N] = sum_k A[m*lda + k] * B[n*ldb + k], bf16 operands, fp32 accumulation.  Outputs
+// ---------------------------------------------------------------- bf16 MFMA GEMM
+// C[M x N] = sum_k A[m*lda + k] * B[n*ldb + k] (bmaj: A[k*lda + m] * B[k*ldb + n]), bf16 operands,
+// fp32 accumulation.  Outputs
 // (each optional): fp32 C, bf16 C, and a transposed bf16 copy Ct[n*ldct + m].
 //   FWD: C = act(acc + bias)                    DA: C = acc * f'(aux)
 //   DW : C_f32 is the fp32 master weight: C_f32 -= lr * acc, and C / Ct are its bf16 copies
