@@ -98,3 +98,26 @@ def test_bf16_weight_gradient_slice_buffer_covers_every_batch_size():
     # the case that overflowed a buffer sized from the count at max_B: 2048 x 2048 at max_B = 2^21
     assert plan(2048, 2048, 1 << 21, 0) == 1 and plan(2048, 2048, 8192, 0) == 4 and plan(2048, 2048, 1 << 21, 1) >= 4
     assert plan(0, 5, 5, 0) == 0 and plan(5, 5, 0, 1) == 0
+
+
+def test_traffic_summaries_have_the_form_the_benchmark_reads():
+    """bench.py takes `roofline.traffic` from profiles/hbm_traffic_config<c>_B<B>.json:
+    {"bytes_per_launch": {<kernel name as bench.py prints it>: bytes}}.  A summary in another
+    form would silently turn the field into null."""
+    import glob
+    import json
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    files = sorted(glob.glob(os.path.join(root, "profiles", "hbm_traffic_config*_B*.json")))
+    assert files, "no traffic summaries under profiles/"
+    dominant = {"2": "bwd_pair", "4": "bwd_pair", "5": "fwd_gemm"}
+    for f in files:
+        with open(f) as fh:
+            d = json.load(fh)
+        per = d.get("bytes_per_launch")
+        assert isinstance(per, dict) and per, f"{f}: no bytes_per_launch table"
+        assert all(isinstance(v, (int, float)) and v > 0 for v in per.values()), f
+        cfg = os.path.basename(f)[len("hbm_traffic_config")]
+        if cfg in dominant:
+            assert dominant[cfg] in per, f"{f}: no entry for the dominant kernel {dominant[cfg]}"
+        assert os.path.exists(f[:-5] + ".md"), f"{f}: the summary it was taken from is missing"
