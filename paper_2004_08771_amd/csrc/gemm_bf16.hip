@@ -214,6 +214,7 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
             if (KIND == GEMM_DA && use_mask && (FULL || (mw + i * 32 < a.M && nb < a.N)))
                 mword[i] = a.mask_in[((size_t)((mw + i * 32) >> 5) * a.mask_nb + (nb >> 5)) * 64 + 32 * h + r];
         }
+        float csum = 0.f;  // backward-data: sum of the lane's stored results of this column
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             unsigned mbits = 0u;
@@ -268,6 +269,7 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
                         }
                         if (has_cb)
                             *reinterpret_cast<bf16_t *>(cb0 + ((size_t)(mb + e) * a.ldcb + nb) * 2 + lo_cb) = f2bf(val);
+                        if (KIND == GEMM_DA && a.colsum_partial != nullptr) csum += bf2f(f2bf(val));
                     }
                     x[e] = val;
                 }
@@ -291,6 +293,12 @@ __device__ __forceinline__ void epilogue_bf16_impl(const GemmBf16Args &a, v16f (
             if (KIND == GEMM_FWD && MASK && (FULL || (mw + i * 32 < a.M && nb < a.N)))
                 a.mask_out[((size_t)((mw + i * 32) >> 5) * a.mask_nb + (nb >> 5)) * 64 + 32 * h + r] =
                     (unsigned short)mbits;
+        }
+        // column sums over the wavefront's 128 rows (LDS-direct kernel only: mw is a multiple of
+        // 128): the two half-wavefronts hold alternate groups of four rows
+        if (KIND == GEMM_DA && a.colsum_partial != nullptr) {
+            csum += __shfl_xor(csum, 32, 64);
+            if (h == 0 && n_ok) a.colsum_partial[(size_t)(mw >> 7) * a.N + n] = csum;
         }
     }
 }
@@ -562,6 +570,25 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
                 pk[i][j][q].y = pack2bf(x[2], x[3]);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    }
+    // ---- backward-data: column sums of the stored values over the wavefront's 128 rows (the
+    // bias gradient of the layer below), in a fixed order; the two half-wavefronts hold
+    // alternate groups of four rows
+    if (KIND == GEMM_DA && a.colsum_partial != nullptr) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint2 v = pk[i][j][q];
+                    s += (__uint_as_float(v.x << 16) + __uint_as_float(v.x & 0xffff0000u)) +
+                         (__uint_as_float(v.y << 16) + __uint_as_float(v.y & 0xffff0000u));
+                }
+            s += __shfl_xor(s, 32, 64);
+            if (h == 0) a.colsum_partial[(size_t)(mw >> 7) * a.N + nw + j * 32 + r] = s;
         }
     }
     // ---- row-major copy: T[m][n], lane writes its four rows of column j*32 + r
@@ -1252,8 +1279,10 @@ hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, co
 
 }  // namespace
 
-hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, const LaunchEvents &ev)
+hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, const LaunchEvents &ev,
+                            int *colsum_slices_out)
 {
+    if (colsum_slices_out) *colsum_slices_out = 0;
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     // The 256 x 256 LDS-direct kernel when both operands allow it and its tiles cover at least
     // half of the CUs; else 256 x 128 tiles when they give two workgroups per CU, else 128 x 128.
@@ -1280,7 +1309,14 @@ hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, c
             return hipErrorInvalidValue;
         return launch_dma_bf16(kind, a, stream, ev);
     }
-    if (dma_ok && (forced == 1 || (forced == 0 && dma_tiles >= 128))) return launch_dma_bf16(kind, a, stream, ev);
+    if (dma_ok && (forced == 1 || (forced == 0 && dma_tiles >= 128))) {
+        // column sums of a backward-data result: two slices per tile row, if the caller has room
+        const int slices = 2 * ((a.M + DMA_BM - 1) / DMA_BM);
+        if (kind != GEMM_DA || a.colsum_partial == nullptr || slices > a.colsum_cap) a.colsum_partial = nullptr;
+        else if (colsum_slices_out) *colsum_slices_out = slices;
+        return launch_dma_bf16(kind, a, stream, ev);
+    }
+    a.colsum_partial = nullptr;  // the other kernels do not produce them
     if (forced == 4 || (forced == 0 && big_tiles >= 512)) return launch_shape_bf16<256, 128, 32>(kind, a, stream, ev);
     if (forced == 3) return launch_shape_bf16<128, 128, 32>(kind, a, stream, ev);
     return launch_shape_bf16<128, 128, 64>(kind, a, stream, ev);
@@ -1353,6 +1389,13 @@ int colsum_bias_slices(long long B)
     long long s = (B + 63) / 64;  // at least 64 rows per slice
     if (s > CSB_MAX_SLICES) s = CSB_MAX_SLICES;
     return s < 1 ? 1 : (int)s;
+}
+
+hipError_t launch_colsum_bias_finalize(const float *partial, int slices, int d, float *bias, float *grad, float lr,
+                                       hipStream_t stream, const LaunchEvents &ev)
+{
+    return launch_kernel(colsum_bias_finalize_kernel, dim3((unsigned)((d + 63) / 64)), dim3(256), stream, ev,
+                         partial, slices, d, bias, grad, lr);
 }
 
 hipError_t launch_colsum_bias(const void *D, long long ld, int d, long long B, float *partial, float *bias,

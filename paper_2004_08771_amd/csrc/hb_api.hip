@@ -132,7 +132,8 @@ struct hb_model {
     std::vector<int> ld8;                       // d_l rounded up to 8
     std::vector<void *> shadow, shadow_t;       // [1..L]
     std::vector<void *> act_bf, act_t;          // [1..L-1] / [0..L-1]
-    float *bias_partial = nullptr;              // slices x max d_l: column sums of a row-major delta
+    float *bias_partial[2] = {nullptr, nullptr};  // slices x max d_l each: column sums of a row-major delta
+    int bias_partial_slices = 0;                  // rows of each
     std::vector<unsigned short *> relu_mask;    // [1..L-1], ReLU nets: decision bits of the hidden activations
     void *delta_bf[2] = {nullptr, nullptr};
     void *delta_t[2] = {nullptr, nullptr};
@@ -689,6 +690,7 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
                                      prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * B * m->dims[L])));
 
     const bool grad_mode = (mode == MODE_GRAD);
+    std::vector<int> colsum_slices((size_t)L + 2, 0);  // [l] > 0: slices of column sums of D_l already written
     for (int l = L; l >= 1; --l) {
         if (l > 1) {
             GemmBf16Args g = {};
@@ -716,9 +718,12 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
                 g.Ct_bf16 = m->delta_t[(l - 1) & 1];
                 g.ldct = ldB;
             }
+            g.colsum_partial = m->bias_partial[(l - 1) & 1];  // the bias gradient of layer l-1, if this kernel can
+            g.colsum_cap = m->bias_partial_slices;
             HB_HIP(launch_gemm_bf16(GEMM_DA, g, st,
                                     prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
-                                               2.0 * ((double)g.M * g.K + (double)g.N * g.K + 3.0 * g.M * g.N))));
+                                               2.0 * ((double)g.M * g.K + (double)g.N * g.K + 3.0 * g.M * g.N)),
+                                    &colsum_slices[l - 1]));
         }
         GemmBf16Args g = {};
         if (bmaj[l]) {
@@ -785,8 +790,15 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
                                                2.0 * ((double)g.M * g.K + (double)g.N * g.K) +
                                                    (grad_mode ? 4.0 : 12.0) * g.M * g.N)));
         }
-        if (bmaj[l])
-            HB_HIP(launch_colsum_bias(m->delta_bf[l & 1], m->ld8[l], m->dims[l], B, m->bias_partial,
+        if (colsum_slices[l] > 0)  // the backward-data epilogue that wrote D_l left its column sums
+            HB_HIP(launch_colsum_bias_finalize(m->bias_partial[l & 1], colsum_slices[l], m->dims[l],
+                                               m->d_params + m->b_off[l],
+                                               grad_mode ? d_grad_flat + m->b_off[l] : nullptr, lr, st,
+                                               prof_begin(m, HB_K_UPDATE, l, 0, 0, 0,
+                                                          (double)colsum_slices[l] * m->dims[l],
+                                                          4.0 * colsum_slices[l] * m->dims[l])));
+        else if (bmaj[l])
+            HB_HIP(launch_colsum_bias(m->delta_bf[l & 1], m->ld8[l], m->dims[l], B, m->bias_partial[l & 1],
                                       m->d_params + m->b_off[l], grad_mode ? d_grad_flat + m->b_off[l] : nullptr,
                                       lr, st,
                                       prof_begin(m, HB_K_UPDATE, l, 0, 0, 0, (double)B * m->dims[l],
@@ -1149,7 +1161,17 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
             if (need > 0 && rc == HB_OK) rc = dev_alloc(m, &m->dw_partial, need);
             if (rc == HB_OK) m->dw_partial_cap = need;
         }
-        if (rc == HB_OK) rc = dev_alloc(m, &m->bias_partial, (size_t)colsum_bias_slices(max_B) * (size_t)max_d);
+        {
+            // the bias gradient's partial column sums: from a pass over D of its own, or two per
+            // 256-row tile from the backward-data epilogue that wrote D (the sums of D_{l-1} are
+            // written while those of D_l wait for their turn: two buffers)
+            int rows = colsum_bias_slices(max_B);
+            const long long fused = 2 * ((max_B + 255) / 256);
+            if (fused <= 1024 && fused > rows) rows = (int)fused;
+            m->bias_partial_slices = rows;
+            for (int i = 0; i < 2 && rc == HB_OK; ++i)
+                rc = dev_alloc(m, &m->bias_partial[i], (size_t)rows * (size_t)max_d);
+        }
     }
     if (m->sparse && rc == HB_OK) {
         const size_t d0 = (size_t)m->dims[0];

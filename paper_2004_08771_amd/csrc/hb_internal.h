@@ -105,6 +105,13 @@ struct GemmBf16Args {
     unsigned short *mask_out;
     const unsigned short *mask_in;
     int mask_nb;           // 32-column blocks per block row: ceil(N / 32)
+    // backward-data product, optional: column sums of the stored (bf16) result over slices of its
+    // rows, colsum_partial[slice * N + n] -- the bias gradient of the layer below, which then
+    // needs no pass of its own over D.  Only the LDS-direct kernel produces them (slice =
+    // 128 rows: the two row halves of each tile row); launch_gemm_bf16 reports the number of
+    // slices written, 0 if the product went to another kernel or colsum_cap slices are too few.
+    float *colsum_partial;
+    int colsum_cap;
     int act;
     int write_grad;
     float lr;
@@ -119,7 +126,7 @@ struct GemmBf16Args {
     long long c_split_stride;
 };
 hipError_t launch_gemm_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream,
-                            const LaunchEvents &ev = LaunchEvents());
+                            const LaunchEvents &ev = LaunchEvents(), int *colsum_slices_out = nullptr);
 // Slices for a weight-gradient product whose 256 x 256 tiles would leave half of the CUs (or
 // more) idle; 1 = do not split.  gemm_bf16_dw_splits_cap(M, N, max_K) is the largest count
 // gemm_bf16_dw_splits returns for any K <= max_K and any leading dimensions (it is
@@ -143,6 +150,9 @@ hipError_t launch_rowsum_bias(const void *Dt, long long ld, int d, long long B, 
 // the same from the row-major delta D [B x ld] (ld % 8 == 0, 16-byte aligned): column sums in
 // colsum_bias_slices(B) slices of the batch (partial: slices x d floats), added in index order
 int colsum_bias_slices(long long B);
+// the second step alone, on `slices` x d partial sums that are already there
+hipError_t launch_colsum_bias_finalize(const float *partial, int slices, int d, float *bias, float *grad, float lr,
+                                       hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 hipError_t launch_colsum_bias(const void *D, long long ld, int d, long long B, float *partial, float *bias,
                               float *grad, float lr, hipStream_t stream, const LaunchEvents &ev = LaunchEvents());
 
