@@ -794,7 +794,7 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             HB_HIP(launch_colsum_bias_finalize(m->bias_partial[l & 1], colsum_slices[l], m->dims[l],
                                                m->d_params + m->b_off[l],
                                                grad_mode ? d_grad_flat + m->b_off[l] : nullptr, lr, st,
-                                               prof_begin(m, HB_K_UPDATE, l, 0, 0, 0,
+                                               prof_begin(m, HB_K_OTHER, 3, 0, 0, 0,
                                                           (double)colsum_slices[l] * m->dims[l],
                                                           4.0 * colsum_slices[l] * m->dims[l])));
         else if (bmaj[l])
