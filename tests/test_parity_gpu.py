@@ -870,6 +870,16 @@ def test_bf16_wide_layers_with_many_k_tiles(dims, act, loss, B):
         assert 0 < free_n < 0.02 * B * (dims[1] + dims[2]), f"{free_n} units within rounding of the kink"
 
 
+@pytest.mark.parametrize("B", [5, 37, 64, 100])
+def test_bf16_batch_shorter_than_a_k_tile_in_the_batch_major_weight_gradient(B):
+    """dW_2 is 2050 x 4096 (144 tiles of 256 x 256: the LDS-direct kernel with batch-major operands)
+    and contracts over B rows: fewer than one k-tile of 64 (only the masked tail runs), exactly
+    one, or one and a tail."""
+    dims = (264, 4096, 2050, 5)
+    params, X, y = _problem(dims, hi.LOSS_SOFTMAX_CE, B, seed=900 + B, bias_scale=0.1)
+    check_bf16_case(dims, hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, params, X, y, lr=0.05, condition_relu=False)
+
+
 @pytest.mark.parametrize("B", [130, 259, 3841, 3842, 3843])
 def test_bf16_relu_batch_edges_of_the_backward_data_epilogue(B):
     """The backward-data epilogue applies the ReLU decisions the forward epilogue left as bits, 16 per
