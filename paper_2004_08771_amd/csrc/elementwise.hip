@@ -38,6 +38,9 @@ __global__ __launch_bounds__(LOSS_NT) void loss_kernel(LossArgs a)
     if (row < a.B) {
         const float *z = a.Z + row * a.ldz;
         const int yi = a.y[row];
+        // bf16 delta with padded rows: the padding is part of the next product's contraction
+        if (a.delta && a.delta_bf16 && a.zero_pad)
+            for (int k = a.K + g; k < a.ldd; k += G) static_cast<unsigned short *>(a.delta)[row * a.ldd + k] = 0;
         if (a.loss == 1 && a.K == 1) {
             if (g == 0) {
                 const float yf = (float)yi;

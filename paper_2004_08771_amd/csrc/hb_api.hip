@@ -129,7 +129,7 @@ struct hb_model {
 
     // bf16 mode: bf16 copies of every weight matrix (row-major and transposed), bf16
     // activations / deltas in both layouts; acts[L] holds the fp32 logits
-    std::vector<int> ld8;                       // d_l rounded up to 8
+    std::vector<int> ld8;                       // row length of the bf16 tensors of layer l: d_l rounded up to 8 (output layer: see configure)
     std::vector<void *> shadow, shadow_t;       // [1..L]
     std::vector<void *> act_bf, act_t;          // [1..L-1] / [0..L-1]
     float *bias_partial[2] = {nullptr, nullptr};  // slices x max d_l each: column sums of a row-major delta
@@ -680,6 +680,7 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
     la.delta = back ? m->delta_bf[L & 1] : nullptr;
     la.ldd = m->ld8[L];
     la.delta_bf16 = 1;
+    la.zero_pad = 1;
     la.block_partials = m->d_loss_partials;
     HB_HIP(launch_loss(la, st, prof_begin(m, HB_K_LOSS, 0, 0, 0, 0, 0.0, B * (4.0 * la.K + 2.0 * la.K + 4.0))));
     LossFinalize fin = {m->d_loss_partials, loss_grid_blocks(B, la.K), B, m->d_loss, d_loss_user};
@@ -700,7 +701,7 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             g.ldb = m->ld8[l];
             g.M = Bi;
             g.N = m->dims[l - 1];
-            g.K = m->dims[l];
+            g.K = (l == L) ? m->ld8[l] : m->dims[l];  // output layer: zero padding included (see ld8)
             g.a_vec = 1;
             g.b_vec = 1;
             g.aux = m->act_bf[l - 1];
@@ -720,9 +721,10 @@ int run_step_bf16(hb_model *m, const void *X, const int32_t *y, int64_t B, float
             }
             g.colsum_partial = m->bias_partial[(l - 1) & 1];  // the bias gradient of layer l-1, if this kernel can
             g.colsum_cap = m->bias_partial_slices;
+            const double Kd = m->dims[l];  // priced without the padding
             HB_HIP(launch_gemm_bf16(GEMM_DA, g, st,
-                                    prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, g.K, 2.0 * g.M * g.N * g.K,
-                                               2.0 * ((double)g.M * g.K + (double)g.N * g.K + 3.0 * g.M * g.N)),
+                                    prof_begin(m, HB_K_DA_GEMM, l, g.M, g.N, m->dims[l], 2.0 * g.M * g.N * Kd,
+                                               2.0 * ((double)g.M * Kd + (double)g.N * Kd + 3.0 * g.M * g.N)),
                                     &colsum_slices[l - 1]));
         }
         GemmBf16Args g = {};
@@ -1117,7 +1119,11 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         m->relu_mask.assign(L + 1, nullptr);
         int max_ld8 = 8, max_d = 1;
         for (int l = 0; l <= L; ++l) {
-            m->ld8[l] = round_up(m->dims[l], 8);
+            // rows of 8 elements (16 bytes); the output layer's rows are padded to a whole k-tile
+            // of 64 when that adds less than half a tile: its delta is the left operand of the
+            // last layer's backward-data product, which then needs no masked tail (the padding
+            // is zero on both sides: the loss kernel writes it, the weight copies keep it)
+            m->ld8[l] = (l == L && m->dims[l] % 64 >= 32) ? round_up(m->dims[l], 64) : round_up(m->dims[l], 8);
             if (l >= 1 && m->ld8[l] > max_ld8) max_ld8 = m->ld8[l];
             if (l >= 1 && m->dims[l] > max_d) max_d = m->dims[l];
         }

@@ -167,6 +167,7 @@ struct LossArgs {
     void *delta;      // B x ldd, receives d(mean loss)/dZ (fp32, or bf16 when delta_bf16); may be null
     int ldd;
     int delta_bf16;
+    int zero_pad;            // bf16 delta: columns K .. ldd-1 of every row are written as zeros
     float *block_partials;   // one loss sum per block (>= loss_grid_blocks entries)
     int vec4;                // set by launch_loss: rows of Z and delta allow 16-byte / 8-byte accesses
 };
