@@ -653,16 +653,15 @@ __device__ __forceinline__ void epilogue_bf16_lds(const GemmBf16Args &a, v16f (&
 // fragment.  The four k-rows a group reads together are 512 bytes apart, i.e. on the same
 // banks: the 64-byte segments of k-row k are therefore stored at segment index s ^ (k & 3)
 // (the direct loads fetch the permuted segment, their LDS side stays contiguous).
-template <int KIND, bool BMAJ = false>
-__global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a)
+template <int KIND, bool BMAJ>
+__device__ __forceinline__ void gemm_bf16_dma_tile(const GemmBf16Args &a, unsigned char *smem_raw, int id, int T,
+                                                   int tid)
 {
     static_assert(!BMAJ || KIND == GEMM_DW, "batch-major operands: weight gradient only");
     constexpr int BM = DMA_BM, BN = DMA_BN, BK = DMA_BK;
     constexpr int TM = 4, TN = 2;  // 32 x 32 blocks per wavefront: 128 x 64
     constexpr int G = BK / 16;     // MFMA k-steps per tile
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
-    const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS bases of the direct loads are scalars
     const int r = lane & 31, h = lane >> 5;
@@ -672,8 +671,6 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
     // workgroups at a time (one per CU), so the j-th group of 32 ids of XCD x gets a block of
     // 4 x 8 (or 8 x 4) tiles: per k-tile its L2 then fetches 12 operand panels for 32 tiles,
     // against 18 for two rows of 16 (1.26 instead of 1.07 PFLOP/s on the weight gradient).
-    int id = blockIdx.x;
-    const int T = gridDim.x;
     int tile_m, tile_n;
     int bm = 0, bn = 0;
     if ((T & 255) == 0) {
@@ -995,6 +992,27 @@ __global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a
     }
 }
 
+// Workgroup b computes tiles b, b + gridDim.x, ..: with a whole number of tiles per compute unit
+// the launcher starts one workgroup per compute unit, which saves the dispatch of a new
+// workgroup at every tile boundary (16384 x 4096 x 4096: 428 -> 425 us); otherwise one
+// workgroup per tile.  The thread number goes through an empty asm in every round: everything
+// the tile derives from it would otherwise be computed once in front of the loop and sit in
+// registers through the main loop, which has none to spare.  Between two tiles every
+// wavefront must be done with the LDS staging of its results before the next tile's operand
+// loads may land on it.
+template <int KIND, bool BMAJ = false>
+__global__ __launch_bounds__(DMA_NT, 1) void gemm_bf16_dma_kernel(GemmBf16Args a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const int T = a.tiles_m * a.tiles_n;
+    for (int id = blockIdx.x; id < T; id += (int)gridDim.x) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        gemm_bf16_dma_tile<KIND, BMAJ>(a, smem_raw, id, T, tid);
+        if (id + (int)gridDim.x < T) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+}
+
 // out[c][r] = in[r][c] for bf16 matrices (R x C, leading dimensions ldi / ldo), 64 x 64 tiles.
 // Interior tiles of 16-byte aligned matrices move 16 bytes per lane on both sides (two-byte
 // accesses reach 2.3 TB/s, a third of what the memory gives): rows come in as eight 16-byte
@@ -1269,7 +1287,11 @@ hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, co
     const long long tiles = (long long)a.tiles_m * a.tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     const int splits = (kind == GEMM_DW && a.k_chunk > 0) ? (a.K + a.k_chunk - 1) / a.k_chunk : 1;
-    const dim3 grid((unsigned)tiles, (unsigned)splits), block(DMA_NT);
+    // one workgroup per compute unit (256 on this part) when that divides the tiles evenly
+    // (HB_BF16_PERSIST=0, tuning aid: one workgroup per tile)
+    static const int persist = env_int_bf16("HB_BF16_PERSIST", 1);
+    const long long wgs = (persist && tiles > 256 && tiles % 256 == 0) ? 256 : tiles;
+    const dim3 grid((unsigned)wgs, (unsigned)splits), block(DMA_NT);
     if (ev.start)
         hipExtLaunchKernelGGL(k, grid, block, (unsigned)DMA_LDS_BYTES, stream, ev.start, ev.stop, 0, a);
     else
