@@ -992,8 +992,8 @@ __device__ __forceinline__ void gemm_bf16_dma_tile(const GemmBf16Args &a, unsign
     }
 }
 
-// Workgroup b computes tiles b, b + gridDim.x, ..: with a whole number of tiles per compute unit
-// the launcher starts one workgroup per compute unit, which saves the dispatch of a new
+// Workgroup b computes tiles b, b + gridDim.x, ..: with more tiles than compute units the
+// launcher starts one workgroup per compute unit, which saves the dispatch of a new
 // workgroup at every tile boundary (16384 x 4096 x 4096: 428 -> 425 us); otherwise one
 // workgroup per tile.  The thread number goes through an empty asm in every round: everything
 // the tile derives from it would otherwise be computed once in front of the loop and sit in
@@ -1287,10 +1287,10 @@ hipError_t launch_dma_bf16(GemmKind kind, GemmBf16Args a, hipStream_t stream, co
     const long long tiles = (long long)a.tiles_m * a.tiles_n;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     const int splits = (kind == GEMM_DW && a.k_chunk > 0) ? (a.K + a.k_chunk - 1) / a.k_chunk : 1;
-    // one workgroup per compute unit (256 on this part) when that divides the tiles evenly
+    // one workgroup per compute unit (256 on this part) when there are more tiles than that
     // (HB_BF16_PERSIST=0, tuning aid: one workgroup per tile)
     static const int persist = env_int_bf16("HB_BF16_PERSIST", 1);
-    const long long wgs = (persist && tiles > 256 && tiles % 256 == 0) ? 256 : tiles;
+    const long long wgs = (persist && tiles > 256) ? 256 : tiles;
     const dim3 grid((unsigned)wgs, (unsigned)splits), block(DMA_NT);
     if (ev.start)
         hipExtLaunchKernelGGL(k, grid, block, (unsigned)DMA_LDS_BYTES, stream, ev.start, ev.stop, 0, a);

@@ -870,6 +870,16 @@ def test_bf16_wide_layers_with_many_k_tiles(dims, act, loss, B):
         assert 0 < free_n < 0.02 * B * (dims[1] + dims[2]), f"{free_n} units within rounding of the kink"
 
 
+def test_bf16_more_tiles_than_compute_units_and_not_a_multiple():
+    """5000 x 4096 outputs are 20 x 16 = 320 tiles of 256 x 256 on 256 compute units: the
+    persistent LDS-direct kernel gives 64 workgroups two tiles and the others one, the last tile
+    row is cut by the end of the batch (5000 = 19 x 256 + 136), and every workgroup that takes a
+    second tile finds LDS as its first one left it."""
+    dims, B = (264, 4096, 4096, 5), 5000
+    params, X, y = _problem(dims, hi.LOSS_SOFTMAX_CE, B, seed=1234, bias_scale=0.1)
+    check_bf16_case(dims, hi.ACT_RELU, hi.LOSS_SOFTMAX_CE, params, X, y, lr=0.1, condition_relu=False)
+
+
 @pytest.mark.parametrize("B", [5, 37, 64, 100])
 def test_bf16_batch_shorter_than_a_k_tile_in_the_batch_major_weight_gradient(B):
     """dW_2 is 2050 x 4096 (144 tiles of 256 x 256: the LDS-direct kernel with batch-major operands)
