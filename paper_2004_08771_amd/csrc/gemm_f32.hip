@@ -413,18 +413,25 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
         // Interior tile: no guards.  The backward-data product requests the 16 activation
         // values a lane needs for the derivative together; behind a bounds check per element
         // each load waited for the one before it (16 round trips to memory per block).
+        // Every address is a wavefront-uniform base (block row, block column, row inside the
+        // block: scalar arithmetic) plus one per-lane offset that is the same for all 16 values,
+        // instead of a 64-bit multiply-add per value and lane.
         const float *__restrict__ aux = static_cast<const float *>(a.aux);
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        const int wm_u = wave_u % WAVES_M, wn_u = wave_u / WAVES_M;
+        const unsigned lo_c = (unsigned)(4 * h * a.ldc + r), lo_x = (unsigned)(4 * h * a.ldaux + r);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn * WN + j * 32 + r;
+            const int nb = n0 + wn_u * WN + j * 32;  // uniform
             const float bias = bias_pre[j];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int mb = m0 + wm * WM + i * 32 + 4 * h;
+                const int mbu = m0 + wm_u * WM + i * 32;  // uniform; the lane's rows are mbu + 8 (v / 4) + 4 h + v % 4
                 float o[16];
                 if (KIND == GEMM_DA) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) o[v] = aux[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldaux + n];
+                    for (int v = 0; v < 16; ++v)
+                        o[v] = (aux + ((size_t)(mbu + 8 * (v >> 2) + (v & 3)) * a.ldaux + nb))[lo_x];
                 }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -438,7 +445,7 @@ __device__ __forceinline__ void gemm_f32_tile(const GemmArgs &a, float *smem, in
                         if (ACT == ACT_SIGMOID) x *= o[v] * (1.f - o[v]);
                         else if (ACT == ACT_RELU) x = (o[v] > 0.f) ? x : 0.f;
                     }
-                    C[(size_t)(mb + 8 * (v >> 2) + (v & 3)) * a.ldc + n] = x;
+                    (C + ((size_t)(mbu + 8 * (v >> 2) + (v & 3)) * a.ldc + nb))[lo_c] = x;
                 }
             }
         }
