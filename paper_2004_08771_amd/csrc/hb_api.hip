@@ -143,13 +143,12 @@ struct hb_model {
     float *d_w1t = nullptr;
     int32_t *d_col_cnt = nullptr, *d_col_start = nullptr, *d_chunk_start = nullptr;
     int32_t *d_cursor = nullptr;  // per-block column histograms / cursors of the CSC build
-    int32_t *d_csc_row = nullptr;
+    int2 *d_csc_ent = nullptr;           // the batch's non-zeros by column: {row, value bits}
     float *dw_partial = nullptr;         // bf16 mode: slices of a split weight gradient (largest layer that splits)
     size_t dw_partial_cap = 0;           // its capacity in floats
     void *worker_state = nullptr;        // staging buffers of the worker loop (worker.hip), kept between epochs
     void (*worker_state_free)(void *) = nullptr;
-    int4 *d_chunk_desc = nullptr;        // descriptor of each gradient chunk (capacity follows the CSC arrays)
-    float *d_csc_val = nullptr;
+    int4 *d_chunk_desc = nullptr;        // descriptor of each column of the batch (d_0 + 1 of them)
     int64_t csc_cap = 0;
     // the per-batch CSC build depends on the batch only: it runs on a stream of its own beside
     // the forward pass and is joined before the sparse weight gradient
@@ -201,11 +200,9 @@ void release_device(hb_model *m)
     if (m->csc_join) (void)hipEventDestroy(m->csc_join);
     m->csc_stream = nullptr;
     m->csc_fork = m->csc_join = nullptr;
-    if (m->d_csc_row) (void)hipFree(m->d_csc_row);
-    if (m->d_csc_val) (void)hipFree(m->d_csc_val);
+    if (m->d_csc_ent) (void)hipFree(m->d_csc_ent);
     if (m->d_chunk_desc) (void)hipFree(m->d_chunk_desc);
-    m->d_csc_row = nullptr;
-    m->d_csc_val = nullptr;
+    m->d_csc_ent = nullptr;
     m->d_chunk_desc = nullptr;
     m->csc_cap = 0;
     for (void *p : m->owned) (void)hipFree(p);
@@ -283,18 +280,14 @@ int ensure_csc_capacity(hb_model *m, int64_t nnz)
     if (m->csc_stream) HB_HIP(hipStreamSynchronize(m->csc_stream));
     int64_t cap = m->csc_cap > 0 ? m->csc_cap : 1024;
     while (cap < nnz) cap *= 2;
-    if (m->d_csc_row) (void)hipFree(m->d_csc_row);
-    if (m->d_csc_val) (void)hipFree(m->d_csc_val);
+    if (m->d_csc_ent) (void)hipFree(m->d_csc_ent);
     if (m->d_chunk_desc) (void)hipFree(m->d_chunk_desc);
-    m->d_csc_row = nullptr;
-    m->d_csc_val = nullptr;
+    m->d_csc_ent = nullptr;
     m->d_chunk_desc = nullptr;
     m->csc_cap = 0;
-    // chunks <= cap / CHUNK + d_0
-    const size_t max_chunks = (size_t)cap / sparse_chunk() + (size_t)m->dims[0] + 1;
-    if (hipMalloc(reinterpret_cast<void **>(&m->d_csc_row), sizeof(int32_t) * (size_t)cap) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&m->d_csc_val), sizeof(float) * (size_t)cap) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&m->d_chunk_desc), sizeof(int4) * max_chunks) != hipSuccess)
+    const size_t max_desc = (size_t)m->dims[0] + 1;  // one descriptor per column that occurs in the batch
+    if (hipMalloc(reinterpret_cast<void **>(&m->d_csc_ent), sizeof(int2) * (size_t)cap) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&m->d_chunk_desc), sizeof(int4) * max_desc) != hipSuccess)
         return fail(HB_ERR_ALLOC, "could not allocate the per-batch CSC workspace for %lld non-zeros",
                     (long long)nnz);
     m->csc_cap = cap;
@@ -321,7 +314,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
     auto csc_build = [&](hipStream_t s) -> int {
         HB_HIP(launch_csc_build(in.row_ptr, in.col_idx, in.vals, in.nnz, B, m->dims[0], m->d_cursor,
                                 m->d_col_cnt, m->d_col_start, m->d_chunk_start, m->d_chunk_desc,
-                                m->d_csc_row, m->d_csc_val, s,
+                                m->d_csc_ent, s,
                                 prof_begin(m, HB_K_OTHER, 2, 0, 0, 0, 0.0, 4.0 * in.nnz),
                                 prof_begin(m, HB_K_OTHER, 3, 0, 0, 0, 0.0,
                                            8.0 * (double)csc_hist_elems(B, m->dims[0])),
@@ -545,8 +538,7 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
             sd.col_start = m->d_col_start;
             sd.chunk_start = m->d_chunk_start;
             sd.chunk_desc = m->d_chunk_desc;
-            sd.csc_row = m->d_csc_row;
-            sd.csc_val = m->d_csc_val;
+            sd.csc_ent = m->d_csc_ent;
             sd.delta = delta_l;
             sd.ldd = m->ld[1];
             sd.W1t = m->d_w1t;
@@ -559,13 +551,11 @@ int run_step(hb_model *m, const Input &in, const int32_t *y, int64_t B, float lr
                 sd.grad_out = d_grad_flat + m->w_off[1];
                 HB_HIP(hipMemsetAsync(sd.grad_out, 0, sizeof(float) * (size_t)m->dims[1] * m->dims[0], sw_stream));
             }
-            // chunks <= nnz / CHUNK + (number of distinct columns) <= nnz / CHUNK + min(d_0, nnz)
-            const long long max_chunks = in.nnz / sparse_chunk() + (in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
             // algorithmic bytes: delta_1 rows gathered once per non-zero is cache traffic; HBM sees
             // delta_1 once, the CSC arrays, and a read + write of each touched weight row (bounded
             // by min(nnz, d_0) rows)
             const double touched = (double)(in.nnz < m->dims[0] ? in.nnz : m->dims[0]);
-            HB_HIP(launch_sparse_dw(sd, max_chunks, sw_stream,
+            HB_HIP(launch_sparse_dw(sd, in.nnz, sw_stream,
                                     prof_begin(m, HB_K_SPARSE_DW, 1, m->dims[1], m->dims[0], in.nnz,
                                                2.0 * in.nnz * m->dims[1],
                                                4.0 * B * m->dims[1] + 8.0 * in.nnz +
@@ -1184,7 +1174,7 @@ int hb_mlp_configure(hb_model *m, int dtype, int64_t max_B, int sparse_first_lay
         rc = dev_alloc(m, &m->d_w1t, d0 * m->dims[1]);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_cnt, csc_cnt_elems(d0));
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_col_start, d0 + 1);
-        if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 2);
+        if (rc == HB_OK) rc = dev_alloc(m, &m->d_chunk_start, d0 + 3);
         if (rc == HB_OK) rc = dev_alloc(m, &m->d_cursor, csc_hist_elems(max_B, m->dims[0]));
         // HB_CSC_INLINE=1 (tuning aid) keeps the CSC build on the handle's stream, before the weight gradient
         static const bool csc_inline = getenv("HB_CSC_INLINE") && atoi(getenv("HB_CSC_INLINE")) != 0;

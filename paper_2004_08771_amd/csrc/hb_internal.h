@@ -261,11 +261,10 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream,
                            const LaunchEvents &ev = LaunchEvents());
 
 struct SparseDwArgs {
-    const int32_t *col_start;    // d_0 + 1: segment of each column in csc_row / csc_val
-    const int32_t *chunk_start;  // d_0 + 2: first chunk of each column; [d_0] = number of chunks, [d_0 + 1] = of class 0
-    const int4 *chunk_desc;      // per chunk: {column, first entry, end entry, chunks of the column}
-    const int32_t *csc_row;
-    const float *csc_val;
+    const int32_t *col_start;    // d_0 + 1: segment of each column in csc_ent
+    const int32_t *chunk_start;  // d_0 + 3: descriptor of each column; [d_0] = number of descriptors, [d_0 + 1] = of class 0, [d_0 + 2] = of classes 0 and 1
+    const int4 *chunk_desc;      // per column of the batch, by size class: {column, first entry, end entry, class}
+    const int2 *csc_ent;         // the batch's non-zeros by column: {row, value bits}
     const float *delta;          // B x ldd
     int ldd;
     float *W1t;
@@ -275,7 +274,6 @@ struct SparseDwArgs {
     float lr;
     int vec;
 };
-int sparse_chunk();
 // Per-batch CSC (column-segmented copy of the batch's non-zeros) by a multi-block counting
 // sort; hist is scratch of csc_hist_elems(max_B, d0) int32, cnt of csc_cnt_elems(d0) int32.
 // Needs csc_supported(d0, max_B):
@@ -285,12 +283,12 @@ size_t csc_hist_elems(long long max_B, int d0);
 size_t csc_cnt_elems(int d0);
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
                             long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
-                            int32_t *col_start, int32_t *chunk_start, int4 *chunk_desc, int32_t *csc_row,
-                            float *csc_val, hipStream_t stream, const LaunchEvents &ev_hist = LaunchEvents(),
+                            int32_t *col_start, int32_t *chunk_start, int4 *chunk_desc, int2 *csc_ent,
+                            hipStream_t stream, const LaunchEvents &ev_hist = LaunchEvents(),
                             const LaunchEvents &ev_colsum = LaunchEvents(),
                             const LaunchEvents &ev_scan = LaunchEvents(),
                             const LaunchEvents &ev_place = LaunchEvents());
-hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStream_t stream,
+hipError_t launch_sparse_dw(const SparseDwArgs &a, long long nnz, hipStream_t stream,
                             const LaunchEvents &ev = LaunchEvents());
 hipError_t launch_colsum(const float *delta, int ldd, long long B, int d, int splits, float *partial,
                          hipStream_t stream, const LaunchEvents &ev = LaunchEvents());

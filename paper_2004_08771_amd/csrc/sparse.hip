@@ -7,10 +7,10 @@
 // that the weights of one input column are one contiguous row: the forward SpMM gathers
 // whole rows with 16-byte coalesced loads, and the gradient/update touches only the rows
 // of columns that occur in the batch.  The gradient is column-segmented: the batch's
-// non-zeros are bucketed by column (a per-batch CSC built on the device), long columns
-// are cut into chunks, and every chunk sums its rows of delta_1 once; a column that fits
-// one chunk is updated with a plain read-modify-write, longer ones with fp32 atomic adds
-// of their chunk sums.  Everything is HBM/L2-bandwidth work; no MFMA.
+// non-zeros are bucketed by column (a per-batch CSC built on the device) and every column
+// sums its rows of delta_1 once, then updates its weight row with a plain read-modify-write;
+// a long column is shared by the 16-lane groups of one workgroup, whose partial sums meet
+// in LDS in a fixed order.  Everything is HBM/L2-bandwidth work; no MFMA.
 #include "hb_internal.h"
 
 #include <mutex>
@@ -20,16 +20,27 @@ namespace hb {
 namespace {
 
 constexpr int SP_NT = 128;    // threads per row / per chunk: one float4 each for d_1 = 512
-constexpr int CHUNK = 128;    // non-zeros per gradient chunk
-// Chunk descriptors are laid out by size class, so that the 16-lane groups of one wavefront
-// work on chunks of similar length (next to a 128-entry chunk three one-entry chunks sat idle
-// for seven of eight gather windows): first the whole columns of at most LIGHT_MAX entries (one
-// window of 16 gathers; most columns of a skewed distribution), then everything else, cut into
-// chunks of CHUNK entries.  (Four classes -- 16, 32, 64, more -- measured the same as these two.)
-constexpr int N_CLASS = 2;
+constexpr int CHUNK = 128;    // a column with more entries is shared by several groups / workgroups
+// One descriptor per column that occurs in the batch, laid out by size class: first the
+// columns of at most LIGHT_MAX entries (most columns of a skewed distribution) by their exact
+// number of entries, then those of at most CHUNK entries by their number of 16-entry gather
+// windows, then the long ones.  A gather is one instruction for the four 16-lane groups of a
+// wavefront and costs the texture-address unit the same 16 cycles however many of its lanes
+// are active (measured: a quarter of the groups active, same time), and that unit is what
+// bounds these kernels (83 % busy): so the groups of a wavefront should want the same number of
+// gathers.  (In column order, a 128-entry column beside three one-entry columns left three
+// quarters of seven gather windows idle.)
 constexpr int LIGHT_MAX = 16;
-__host__ __device__ inline int chunk_class(int cnt) { return cnt <= LIGHT_MAX ? 0 : 1; }
-__host__ __device__ inline int chunks_of(int cnt) { return cnt <= LIGHT_MAX ? (cnt > 0 ? 1 : 0) : (cnt + CHUNK - 1) / CHUNK; }
+constexpr int N_LIGHT = LIGHT_MAX;             // classes 0 .. 15: 1 .. 16 entries
+constexpr int N_MID = CHUNK / 16 - 1;          // classes 16 .. 22: 2 .. 8 windows
+constexpr int N_CLASS = N_LIGHT + N_MID + 1;   // class 23: more than CHUNK entries
+__host__ __device__ inline int chunk_class(int cnt)
+{
+    if (cnt <= LIGHT_MAX) return cnt > 0 ? cnt - 1 : 0;
+    if (cnt <= CHUNK) return N_LIGHT + (cnt + 15) / 16 - 2;
+    return N_CLASS - 1;
+}
+__host__ __device__ inline int chunks_of(int cnt) { return cnt > 0 ? 1 : 0; }
 
 constexpr int SPMM_CAP = 512;  // entries of a row staged in LDS at a time (forward product)
 
@@ -241,7 +252,9 @@ __global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ 
         cnt[c] = run;
     }
     int tot[1 + N_CLASS] = {run};
-    tot[1 + chunk_class(run)] = chunks_of(run);
+    const int cls = chunk_class(run), ch = chunks_of(run);
+#pragma unroll
+    for (int k = 0; k < N_CLASS; ++k) tot[1 + k] = (k == cls) ? ch : 0;
     group_sum(tot, red);
     if (threadIdx.x == 0) {
 #pragma unroll
@@ -249,14 +262,14 @@ __global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ 
     }
 }
 
-// Exclusive scan of cnt[0..n) (-> col_start) and the position of every column's first chunk
-// descriptor (-> chunk_start; [n] = number of chunks, [n + 1] = chunks of class 0): the chunks of size class 0 come first, in
-// column order, then class 1, and so on.  One descriptor per chunk {column, first entry, end
-// entry, chunks of the column} lets the gradient kernel find its work with one load.
+// Exclusive scan of cnt[0..n) (-> col_start) and the position of every column's descriptor
+// (-> chunk_start; [n] = number of descriptors, [n + 1] = those of at most LIGHT_MAX entries,
+// [n + 2] = of at most CHUNK entries): the columns of size class 0 come first, in column
+// order, then class 1, and so on.  One descriptor per column that occurs in the batch {column, first entry, end
+// entry, class} lets the gradient kernel find its work with one load.
 // One workgroup per group of 256 columns: it adds up the totals of the groups before it (and the
 // class totals of ALL groups), scans its own columns with shuffles, and writes its outputs
-// coalesced.  A column with more than two chunks (the head of a skewed column distribution has
-// hundreds) goes on an LDS list and the whole workgroup writes its descriptors.
+// coalesced.
 // (A single-workgroup scan of all 21k columns took 20-60 us in three different forms: one
 // CU's shuffle latency and store issue rate bound it.)
 __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restrict__ cnt,
@@ -266,8 +279,6 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
                                                         int4 *__restrict__ chunk_desc)
 {
     __shared__ int red[4 * (1 + N_CLASS)], w_a[4], w_c[4][N_CLASS];
-    __shared__ int n_heavy;
-    __shared__ int4 heavy[COLG];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int g = blockIdx.x, n_groups = gridDim.x;
     const int c = g * COLG + t;
@@ -283,8 +294,7 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
             all[k] += x;
         }
     }
-    if (t == 0) n_heavy = 0;
-    group_sum(before, red);  // its barrier also publishes n_heavy
+    group_sum(before, red);
     __syncthreads();         // red is reused
     group_sum(all, red);
     const int cls = chunk_class(v), ch = chunks_of(v);
@@ -318,24 +328,15 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
             for (int k = 0; k < N_CLASS; ++k) total += all[k];
             col_start[n] = first_e + v;
             chunk_start[n] = total;
-            chunk_start[n + 1] = all[0];
+            int light = 0, mid = 0;
+#pragma unroll
+            for (int k = 0; k < N_LIGHT; ++k) light += all[k];
+#pragma unroll
+            for (int k = N_LIGHT; k < N_CLASS - 1; ++k) mid += all[k];
+            chunk_start[n + 1] = light;
+            chunk_start[n + 2] = light + mid;
         }
-        if (ch > 2) {
-            heavy[atomicAdd(&n_heavy, 1)] = make_int4(c, first_e, v, first_ch);
-        } else if (ch == 1) {
-            chunk_desc[first_ch] = make_int4(c, first_e, first_e + v, 1);
-        } else if (ch == 2) {
-            chunk_desc[first_ch] = make_int4(c, first_e, first_e + CHUNK, 2);
-            chunk_desc[first_ch + 1] = make_int4(c, first_e + CHUNK, first_e + v, 2);
-        }
-    }
-    __syncthreads();
-    const int nh = n_heavy;
-    for (int k = 0; k < nh; ++k) {
-        const int4 h = heavy[k];  // {column, first entry, entries, first chunk}
-        const int hch = (h.z + CHUNK - 1) / CHUNK;
-        for (int q = t; q < hch; q += COLG)
-            chunk_desc[h.w + q] = make_int4(h.x, h.y + q * CHUNK, min(h.y + h.z, h.y + (q + 1) * CHUNK), hch);
+        if (v > 0) chunk_desc[first_ch] = make_int4(c, first_e, first_e + v, cls);
     }
 }
 
@@ -345,8 +346,7 @@ __global__ __launch_bounds__(CSC_NT) void csc_place_kernel(const int32_t *__rest
                                                            int rows_per_block, int d0,
                                                            const int32_t *__restrict__ hist,
                                                            const int32_t *__restrict__ col_start,
-                                                           int32_t *__restrict__ csc_row,
-                                                           float *__restrict__ csc_val)
+                                                           int2 *__restrict__ csc_ent)
 {
     extern __shared__ int32_t s_cur[];
     const int32_t *mine = hist + (size_t)blockIdx.x * d0;
@@ -387,25 +387,27 @@ __global__ __launch_bounds__(CSC_NT) void csc_place_kernel(const int32_t *__rest
                 if (s_rp[mid] <= p) lo = mid; else hi = mid;
             }
             const int pos = base[u] + atomicAdd(&s_cur[c[u]], 1);
-            csc_row[pos] = (int32_t)(r0 + lo);
-            csc_val[pos] = val[u];
+            csc_ent[pos] = make_int2((int)(r0 + lo), __float_as_int(val[u]));
         }
     }
 }
 
-// One workgroup per chunk of one column's entries:
-//   g[:] = sum_e csc_val[e] * delta_1[csc_row[e], :]
-// then W1t[c,:] -= lr * g (plain for a single-chunk column, atomic otherwise), or in
-// gradient mode dW_1[:, c] (+)= g in the flat out x in layout.
-__global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
+// One workgroup per column that occurs in the batch:
+//   g[:] = sum_e val[e] * delta_1[row[e], :]   over the column's entries {row, val} of csc_ent
+// then W1t[c,:] -= lr * g, or in gradient mode dW_1[:, c] = g in the flat out x in layout.
+// A column of more than CHUNK entries (the last class) is cut into up to FB_PARTS parts: its
+// descriptor's workgroup takes the first, and the FB_EXTRA workgroups behind the descriptors
+// walk over the other parts of all such columns; their sums meet through fp32 atomic adds.
+constexpr int FB_PARTS = 32, FB_EXTRA = 2048;
+__device__ __forceinline__ int fb_part_len(int cnt)
 {
-    const int chunk = blockIdx.x;
-    const int total_chunks = a.chunk_start[a.d0];
-    const int4 desc = a.chunk_desc[chunk];  // the launch covers at most the array's capacity
-    if (chunk >= total_chunks) return;
-    const int c = desc.x, e_beg = desc.y, e_end = desc.z;
-    const bool single = (desc.w == 1);
+    const int per = (((cnt + FB_PARTS - 1) / FB_PARTS) + 15) & ~15;
+    return per > CHUNK ? per : CHUNK;
+}
 
+// entries [e_beg, e_end) of column c: their sum, then the update (plain if `single`)
+__device__ __forceinline__ void sparse_dw_part(const SparseDwArgs &a, int c, int e_beg, int e_end, bool single)
+{
     if (a.vec) {
         const int n4 = a.d1 >> 2;
         for (int q = threadIdx.x; q < n4; q += SP_NT) {
@@ -416,8 +418,9 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
                 float v[16];
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
-                    v[u] = a.csc_val[e + u];
-                    d[u] = reinterpret_cast<const float4 *>(a.delta + (size_t)a.csc_row[e + u] * a.ldd)[q];
+                    const int2 en = a.csc_ent[e + u];
+                    v[u] = __int_as_float(en.y);
+                    d[u] = reinterpret_cast<const float4 *>(a.delta + (size_t)en.x * a.ldd)[q];
                 }
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
@@ -430,8 +433,9 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
                     const bool ok = e + u < e_end;
-                    v[u] = ok ? a.csc_val[e + u] : 0.f;
-                    d[u] = ok ? reinterpret_cast<const float4 *>(a.delta + (size_t)a.csc_row[e + u] * a.ldd)[q]
+                    const int2 en = a.csc_ent[ok ? e + u : e];
+                    v[u] = ok ? __int_as_float(en.y) : 0.f;
+                    d[u] = ok ? reinterpret_cast<const float4 *>(a.delta + (size_t)en.x * a.ldd)[q]
                               : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
 #pragma unroll
@@ -463,7 +467,10 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
         for (int j = threadIdx.x; j < a.d1; j += SP_NT) {
             float g = 0.f;
             for (int e = e_beg; e < e_end; ++e)
-                g += a.csc_val[e] * a.delta[(size_t)a.csc_row[e] * a.ldd + j];
+            {
+                const int2 en = a.csc_ent[e];
+                g += __int_as_float(en.y) * a.delta[(size_t)en.x * a.ldd + j];
+            }
             if (a.grad_out) {
                 float *o = a.grad_out + (size_t)j * a.d0 + c;
                 if (single) *o = g; else atomicAdd(o, g);
@@ -472,6 +479,25 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a)
                 if (single) *w -= a.lr * g; else atomicAdd(w, -a.lr * g);
             }
         }
+    }
+}
+
+__global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a, int max_desc)
+{
+    const int n_desc = a.chunk_start[a.d0], n01 = a.chunk_start[a.d0 + 2];
+    if ((int)blockIdx.x < max_desc) {
+        if ((int)blockIdx.x >= n_desc) return;
+        const int4 desc = a.chunk_desc[blockIdx.x];
+        const int per = fb_part_len(desc.z - desc.y);
+        sparse_dw_part(a, desc.x, desc.y, min(desc.z, desc.y + per), desc.z - desc.y <= per);
+        return;
+    }
+    const int n_work = (n_desc - n01) * (FB_PARTS - 1);
+    for (int w = (int)blockIdx.x - max_desc; w < n_work; w += FB_EXTRA) {
+        const int4 desc = a.chunk_desc[n01 + w / (FB_PARTS - 1)];
+        const int per = fb_part_len(desc.z - desc.y);
+        const int beg = desc.y + (1 + w % (FB_PARTS - 1)) * per;
+        if (beg < desc.z) sparse_dw_part(a, desc.x, beg, min(desc.z, beg + per), false);
     }
 }
 
@@ -517,14 +543,51 @@ __device__ __forceinline__ void slice_of_block(const SliceMap &m, int b, int &sl
 // already points at the lane's float4 of the slice).  idx / val are read 16 entries at a time,
 // lane l taking entry p + l; a full window issues its 16 gathers together, the last, partial
 // window four at a time (lanes past the end hold the last valid index and a zero value).
-__device__ __forceinline__ float4 group_gather_sum(float4 acc, const int32_t *__restrict__ idx,
-                                                   const float *__restrict__ val, int beg, int end,
+// (One form for both -- 16 gathers, each group's lanes switched off past its end, an
+// instruction that no group of the wavefront needs skipped -- issues 15 % fewer gathers in the
+// forward product and is slower, 41.0 -> 42.7 us: a branch per gather.)
+// AHEAD: the next window's idx / val are requested in front of the current window's gathers.
+// For a long run of windows on one group (the critical path of a long column) that takes one
+// of two round trips out of every window; where many short runs keep the memory pipeline full
+// it only adds to the traffic in flight (forward product: 39.5 -> 42.6 us).
+// Where the entries {index, value} of a gather run come from: the caller's CSR arrays, or the
+// per-batch CSC copy (one 8-byte word per entry).
+struct CsrEntries {
+    const int32_t *__restrict__ idx;
+    const float *__restrict__ val;
+    __device__ __forceinline__ void get(int at, bool live, int &i, float &v) const
+    {
+        i = idx[at];
+        v = live ? val[at] : 0.f;
+    }
+};
+struct CscEntries {
+    const int2 *__restrict__ ent;
+    __device__ __forceinline__ void get(int at, bool live, int &i, float &v) const
+    {
+        const int2 e = ent[at];
+        i = e.x;
+        v = live ? __int_as_float(e.y) : 0.f;
+    }
+};
+
+template <bool AHEAD = false, class Entries>
+__device__ __forceinline__ float4 group_gather_sum(float4 acc, const Entries en, int beg, int end,
                                                    const float *__restrict__ src, size_t ld, int l)
 {
+    int nx_i = 0;
+    float nx_v = 0.f;
+    if (AHEAD && beg < end) en.get(min(beg + l, end - 1), beg + l < end, nx_i, nx_v);
     for (int p = beg; p < end; p += 16) {
-        const int at = min(p + l, end - 1);
-        const int my_i = idx[at];
-        const float my_v = (p + l < end) ? val[at] : 0.f;
+        int my_i;
+        float my_v;
+        if (AHEAD) {
+            my_i = nx_i;
+            my_v = nx_v;
+            if (p + 16 < end) en.get(min(p + 16 + l, end - 1), p + 16 + l < end, nx_i, nx_v);
+        } else {
+            en.get(min(p + l, end - 1), p + l < end, my_i, my_v);
+        }
         if (p + 16 <= end) {
             float4 w[16];
 #pragma unroll
@@ -564,74 +627,94 @@ __global__ __launch_bounds__(XS_NT) void spmm_fwd_sliced_kernel(SpmmArgs a, long
     const int beg = a.row_ptr[row], end = a.row_ptr[row + 1];
     const int col0 = slice * SL + 4 * l;
     float4 acc = *reinterpret_cast<const float4 *>(a.bias + col0);
-    acc = group_gather_sum(acc, a.col_idx, a.vals, beg, end, a.W1t + col0, (size_t)a.ldw, l);
+    acc = group_gather_sum(acc, CsrEntries{a.col_idx, a.vals}, beg, end, a.W1t + col0, (size_t)a.ldw, l);
     acc.x = act_apply(acc.x, a.act); acc.y = act_apply(acc.y, a.act);
     acc.z = act_apply(acc.z, a.act); acc.w = act_apply(acc.w, a.act);
     *reinterpret_cast<float4 *>(a.out + (size_t)row * a.ldo + col0) = acc;
 }
 
-// W1t[c, slice] -= lr * g (or the gradient output) for one chunk's sum g, as in sparse_dw_kernel
-__device__ __forceinline__ void apply_chunk_sum(const SparseDwArgs &a, int c, int col0, float4 g, bool single)
+// W1t[c, slice] -= lr * g (or the gradient output) for the sum g of column c
+__device__ __forceinline__ void apply_column_sum(const SparseDwArgs &a, int c, int col0, float4 g)
 {
     if (a.grad_out) {
         float *o = a.grad_out + (size_t)col0 * a.d0 + c;
-        if (single) { o[0] = g.x; o[a.d0] = g.y; o[2 * (size_t)a.d0] = g.z; o[3 * (size_t)a.d0] = g.w; }
-        else {
-            atomicAdd(o, g.x); atomicAdd(o + a.d0, g.y);
-            atomicAdd(o + 2 * (size_t)a.d0, g.z); atomicAdd(o + 3 * (size_t)a.d0, g.w);
-        }
+        o[0] = g.x; o[a.d0] = g.y; o[2 * (size_t)a.d0] = g.z; o[3 * (size_t)a.d0] = g.w;
     } else {
         float *w = a.W1t + (size_t)c * a.ldw + col0;
-        if (single) {
-            float4 x = *reinterpret_cast<float4 *>(w);
-            x.x -= a.lr * g.x; x.y -= a.lr * g.y; x.z -= a.lr * g.z; x.w -= a.lr * g.w;
-            *reinterpret_cast<float4 *>(w) = x;
-        } else {
-            atomicAdd(w, -a.lr * g.x); atomicAdd(w + 1, -a.lr * g.y);
-            atomicAdd(w + 2, -a.lr * g.z); atomicAdd(w + 3, -a.lr * g.w);
-        }
+        float4 x = *reinterpret_cast<float4 *>(w);
+        x.x -= a.lr * g.x; x.y -= a.lr * g.y; x.z -= a.lr * g.z; x.w -= a.lr * g.w;
+        *reinterpret_cast<float4 *>(w) = x;
     }
 }
 
-// g[slice] = sum_e csc_val[e] * delta_1[csc_row[e], slice] over one chunk, then the update of
-// W1t[c, slice] (or the gradient output) as in sparse_dw_kernel.
-// The chunks of class 0 (whole columns of at most 16 entries, most of them with one to three)
-// come first: a group of 16 lanes takes LP of them at once and issues every step of their
-// chains (descriptors, indices, gathers LR per column and round, weight rows) for all LP
-// together -- one such column alone is five dependent round trips with nothing to overlap
-// them but other groups.  The other chunks follow, one per group.  unit = 16 groups.
-// (Requesting the descriptor together with the chunk count, and the weight row of a single-chunk
-// column before the gathers instead of after them, made the one-chunk form slower: 70 -> 76 us.)
-constexpr int LP = 4, LR = 2;
-__global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a, SliceMap m, int units)
+// g[slice] = sum_e val[e] * delta_1[row[e], slice] over one column's entries, then the update of
+// W1t[c, slice] (or the gradient output).  unit = one workgroup = 16 groups of 16 lanes.
+// The first LONG_UNITS units walk over the columns of more than CHUNK entries (the
+// head of a skewed distribution holds half of all entries in a few hundred columns): the 16
+// groups share one column's entries in contiguous runs of whole gather windows, their sums
+// meet in LDS and are added in group order, and the first group updates the row -- no atomics,
+// and the same sum on every run for a given order of the entries (with one fp32 atomic add
+// per 128-entry chunk instead, the kernel took 65.8 us on the real-sim shape; a plain, racing
+// read-modify-write in their place, to price them: 52.7).
+// Then the columns of at most LIGHT_MAX entries (most of them one to three): a group takes
+// LP of them at once and issues every step of their chains (descriptors, indices, gathers
+// LR per column and round, weight rows) for all LP together -- one such column alone is five
+// dependent round trips with nothing to overlap them but other groups.  Then the rest, one
+// column per group.
+// (Requesting the descriptor together with the descriptor count, and the weight row of a
+// class-1 column before the gathers instead of after them, was slower: 70 -> 76 us.)
+constexpr int LP = 4, LR = 2, LONG_UNITS = 512;
+__global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a, SliceMap m, int units, int long_units)
 {
     int slice, unit;
     slice_of_block(m, blockIdx.x, slice, unit);
     if (unit >= units) return;
     const int g16 = threadIdx.x >> 4, l = threadIdx.x & 15;
-    const int n_chunks = a.chunk_start[a.d0], n_light = a.chunk_start[a.d0 + 1];
-    const int light_units = (n_light + 16 * LP - 1) / (16 * LP);
+    const int n_desc = a.chunk_start[a.d0], n_light = a.chunk_start[a.d0 + 1], n01 = a.chunk_start[a.d0 + 2];
     const int col0 = slice * SL + 4 * l;
+    if (unit < long_units) {
+        __shared__ float4 part[16][16];
+        for (int j = n01 + unit; j < n_desc; j += long_units) {
+            const int4 desc = a.chunk_desc[j];
+            const int per = (((desc.z - desc.y + 15) >> 4) + 15) & ~15;  // entries per group: whole windows
+            const int beg = min(desc.z, desc.y + g16 * per);
+            float4 g = {0.f, 0.f, 0.f, 0.f};
+            g = group_gather_sum<true>(g, CscEntries{a.csc_ent}, beg, min(desc.z, beg + per), a.delta + col0, (size_t)a.ldd, l);
+            part[g16][l] = g;
+            __syncthreads();
+            if (g16 == 0) {
+                float4 sum = part[0][l];
+#pragma unroll
+                for (int k = 1; k < 16; ++k) {
+                    const float4 p = part[k][l];
+                    sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
+                }
+                apply_column_sum(a, desc.x, col0, sum);
+            }
+            __syncthreads();  // part is reused
+        }
+        return;
+    }
+    unit -= long_units;
+    const int light_units = (n_light + 16 * LP - 1) / (16 * LP);
     if (unit < light_units) {
         const int first = (unit * 16 + g16) * LP;
         if (first >= n_light) return;
         int c[LP], n[LP], my_i[LP];
         float my_v[LP];
-        int4 desc[LP];
-#pragma unroll
-        for (int k = 0; k < LP; ++k) desc[k] = a.chunk_desc[min(first + k, n_light - 1)];
+        // lane k of the group fetches descriptor k; the others get it by shuffle
+        const int4 mine = a.chunk_desc[min(first + min(l, LP - 1), n_light - 1)];
         int n_max = 0;
 #pragma unroll
         for (int k = 0; k < LP; ++k) {
-            c[k] = desc[k].x;
-            n[k] = (first + k < n_light) ? desc[k].z - desc[k].y : 0;  // a class-0 chunk holds 1..16 entries
+            c[k] = __shfl(mine.x, k, 16);
+            const int e0 = __shfl(mine.y, k, 16), e1 = __shfl(mine.z, k, 16);
+            n[k] = (first + k < n_light) ? e1 - e0 : 0;  // 1 .. LIGHT_MAX entries
             n_max = max(n_max, n[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < LP; ++k) {  // lanes past the end hold the last entry's row and a zero value
-            const int at = desc[k].y + min(l, max(n[k], 1) - 1);
-            my_i[k] = a.csc_row[at];
-            my_v[k] = (l < n[k]) ? a.csc_val[at] : 0.f;
+            // lanes past the end hold the last entry's row and a zero value
+            const int2 en = a.csc_ent[e0 + min(l, max(n[k], 1) - 1)];
+            my_i[k] = en.x;
+            my_v[k] = (l < n[k]) ? __int_as_float(en.y) : 0.f;
         }
         float4 g[LP];
 #pragma unroll
@@ -655,7 +738,7 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
         if (a.grad_out) {
 #pragma unroll
             for (int k = 0; k < LP; ++k)
-                if (first + k < n_light) apply_chunk_sum(a, c[k], col0, g[k], true);
+                if (first + k < n_light) apply_column_sum(a, c[k], col0, g[k]);
         } else {  // the LP weight rows are requested together (distinct columns: no row twice)
             float4 x[LP];
 #pragma unroll
@@ -668,12 +751,12 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
         }
         return;
     }
-    const int chunk = n_light + (unit - light_units) * 16 + g16;
-    if (chunk >= n_chunks) return;
-    const int4 desc = a.chunk_desc[chunk];
+    const int j = n_light + (unit - light_units) * 16 + g16;
+    if (j >= n01) return;
+    const int4 desc = a.chunk_desc[j];
     float4 g = {0.f, 0.f, 0.f, 0.f};
-    g = group_gather_sum(g, a.csc_row, a.csc_val, desc.y, desc.z, a.delta + col0, (size_t)a.ldd, l);
-    apply_chunk_sum(a, desc.x, col0, g, desc.w == 1);
+    g = group_gather_sum(g, CscEntries{a.csc_ent}, desc.y, desc.z, a.delta + col0, (size_t)a.ldd, l);
+    apply_column_sum(a, desc.x, col0, g);
 }
 
 // partial[s][j] = sum over the s-th slice of rows of delta[i][j]   (bias gradient of layer 1)
@@ -755,8 +838,6 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream, c
     return launch_kernel(spmm_fwd_kernel, dim3((unsigned)B), dim3(SP_NT), stream, ev, a);
 }
 
-int sparse_chunk() { return CHUNK; }
-
 int csc_blocks(long long B)
 {
     long long nb = (B + 127) / 128;  // at least 128 rows per block
@@ -781,8 +862,8 @@ size_t csc_hist_elems(long long max_B, int d0) { return (size_t)csc_blocks(max_B
 
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,
                             long long nnz, long long B, int d0, int32_t *hist, int32_t *cnt,
-                            int32_t *col_start, int32_t *chunk_start, int4 *chunk_desc, int32_t *csc_row,
-                            float *csc_val, hipStream_t stream, const LaunchEvents &ev_hist,
+                            int32_t *col_start, int32_t *chunk_start, int4 *chunk_desc, int2 *csc_ent,
+                            hipStream_t stream, const LaunchEvents &ev_hist,
                             const LaunchEvents &ev_colsum, const LaunchEvents &ev_scan,
                             const LaunchEvents &ev_place)
 {
@@ -826,28 +907,32 @@ hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, cons
         hipExtLaunchKernelGGL(csc_place_kernel, dim3(nb), dim3(CSC_NT), (unsigned)lds, stream, ev_place.start,
                               ev_place.stop, 0, row_ptr, col_idx, vals, B, rows_per_block, d0,
                               static_cast<const int32_t *>(hist), static_cast<const int32_t *>(col_start),
-                              csc_row, csc_val);
+                              csc_ent);
     else
         hipLaunchKernelGGL(csc_place_kernel, dim3(nb), dim3(CSC_NT), lds, stream, row_ptr, col_idx, vals, B,
                            rows_per_block, d0, static_cast<const int32_t *>(hist),
-                           static_cast<const int32_t *>(col_start), csc_row, csc_val);
+                           static_cast<const int32_t *>(col_start), csc_ent);
     return hipGetLastError();
 }
 
-hipError_t launch_sparse_dw(const SparseDwArgs &a, long long max_chunks, hipStream_t stream,
-                            const LaunchEvents &ev)
+hipError_t launch_sparse_dw(const SparseDwArgs &a, long long nnz, hipStream_t stream, const LaunchEvents &ev)
 {
-    if (max_chunks <= 0) return hipSuccess;
+    const long long max_cols = nnz < a.d0 ? nnz : a.d0;  // distinct columns of the batch
+    if (max_cols <= 0) return hipSuccess;
     SliceMap m;
     if (slice_map(a.d1, a.vec, &m)) {
-        // ceil(light / (16 LP)) + ceil(others / 16) units are needed, whatever the split
-        const long long units = (max_chunks + 15) / 16 + 1;
+        // one unit per long column while there are at most LONG_UNITS of them, then
+        // ceil(light / (16 LP)) + ceil(others / 16) units
+        const long long max_long = nnz / (CHUNK + 1);
+        const int lu = (int)(max_long < 1 ? 1 : (max_long < LONG_UNITS ? max_long : LONG_UNITS));
+        const long long units = lu + (max_cols + 15) / 16 + 2;
         const long long blocks = sliced_blocks(m, units);
         if (blocks <= 0x7fffffffLL)
             return launch_kernel(sparse_dw_sliced_kernel, dim3((unsigned)blocks), dim3(XS_NT), stream, ev, a, m,
-                                 (int)units);
+                                 (int)units, lu);
     }
-    return launch_kernel(sparse_dw_kernel, dim3((unsigned)max_chunks), dim3(SP_NT), stream, ev, a);
+    return launch_kernel(sparse_dw_kernel, dim3((unsigned)(max_cols + FB_EXTRA)), dim3(SP_NT), stream, ev, a,
+                         (int)max_cols);
 }
 
 hipError_t launch_colsum(const float *delta, int ldd, long long B, int d, int splits, float *partial,
