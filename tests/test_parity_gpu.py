@@ -585,8 +585,8 @@ def check_csr_case(dims, act, loss, params, rp, ci, va, y, lr, tol=TOL_F32):
     for name, v in (("batch_grad_csr", lg), ("batch_loss_csr", ll), ("batch_step_csr", ls)):
         assert abs(v - l_ref) <= tol * abs(l_ref), f"{name} loss {v} vs {l_ref}"
     assert_close(dims, d_g.cpu().numpy(), g_ref, tol, "gradient", scale=scale, tol_scale=TOL_F32_TERMS)
-    # a column that occurs in many rows receives its update as several atomic adds, each rounded to
-    # fp32 (up to 64 chunks of 128 rows at B = 8192): a few units in the last place of W
+    # a column that occurs in many rows is summed in parts (16 groups of one workgroup, or up to 32
+    # atomic adds in the general kernel), each part rounded to fp32: a few units in the last place of W
     assert_close(dims, after, p_ref, tol, "parameters after one step", scale=scale, tol_scale=TOL_F32_TERMS,
                  scale_factor=lr, ref_rounding=2.0 ** -20)
     # weight columns that do not occur in the batch are bit-unchanged
@@ -636,6 +636,25 @@ def test_csr_rows_with_unsorted_and_duplicate_columns():
     va3 = rng.standard_normal(ci3.size).astype(np.float32) * 0.3
     y3 = (2 * rng.integers(0, 2, size=B) - 1).astype(np.int32)
     check_csr_case(dims, hi.ACT_SIGMOID, hi.LOSS_LOGISTIC, params, rp3, ci3, va3, y3, lr=0.1)
+
+
+@pytest.mark.parametrize("d1", [64, 36])
+def test_csr_more_long_columns_than_workgroups_set_aside_for_them(d1):
+    """Every one of 600 columns occurs in about a quarter of 1500 rows: more columns of over 128
+    entries than the weight-gradient kernel has workgroups for long columns (it walks over the
+    rest), in the sliced kernel (d_1 = 64) and in the general one (36)."""
+    dims = (600, d1, 2)
+    rng = np.random.default_rng(4100 + d1)
+    B = 1500
+    rows_c = [np.sort(rng.choice(600, size=int(rng.integers(130, 170)), replace=False)).astype(np.int32)
+              for _ in range(B)]
+    rp = np.concatenate([[0], np.cumsum([r.size for r in rows_c])]).astype(np.int32)
+    ci = np.concatenate(rows_c)
+    assert np.bincount(ci, minlength=600).min() > 128
+    va = (rng.standard_normal(ci.size) * 0.1).astype(np.float32)
+    y = (2 * rng.integers(0, 2, size=B) - 1).astype(np.int32)
+    params = hi.xavier_uniform_params(dims, rng, bias_scale=0.2)
+    check_csr_case(dims, hi.ACT_SIGMOID, hi.LOSS_LOGISTIC, params, rp, ci, va, y, lr=0.1)
 
 
 @pytest.mark.parametrize("seed", [11, 12])
