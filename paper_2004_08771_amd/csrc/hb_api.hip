@@ -148,7 +148,7 @@ struct hb_model {
     size_t dw_partial_cap = 0;           // its capacity in floats
     void *worker_state = nullptr;        // staging buffers of the worker loop (worker.hip), kept between epochs
     void (*worker_state_free)(void *) = nullptr;
-    int4 *d_chunk_desc = nullptr;        // descriptor of each column of the batch (d_0 + 1 of them)
+    int4 *d_chunk_desc = nullptr;        // descriptors of the batch's columns (capacity follows the CSC arrays)
     int64_t csc_cap = 0;
     // the per-batch CSC build depends on the batch only: it runs on a stream of its own beside
     // the forward pass and is joined before the sparse weight gradient
@@ -285,7 +285,7 @@ int ensure_csc_capacity(hb_model *m, int64_t nnz)
     m->d_csc_ent = nullptr;
     m->d_chunk_desc = nullptr;
     m->csc_cap = 0;
-    const size_t max_desc = (size_t)m->dims[0] + 1;  // one descriptor per column that occurs in the batch
+    const size_t max_desc = sparse_desc_capacity(m->dims[0], cap);
     if (hipMalloc(reinterpret_cast<void **>(&m->d_csc_ent), sizeof(int2) * (size_t)cap) != hipSuccess ||
         hipMalloc(reinterpret_cast<void **>(&m->d_chunk_desc), sizeof(int4) * max_desc) != hipSuccess)
         return fail(HB_ERR_ALLOC, "could not allocate the per-batch CSC workspace for %lld non-zeros",

@@ -263,7 +263,7 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream,
 struct SparseDwArgs {
     const int32_t *col_start;    // d_0 + 1: segment of each column in csc_ent
     const int32_t *chunk_start;  // d_0 + 3: descriptor of each column; [d_0] = number of descriptors, [d_0 + 1] = of class 0, [d_0 + 2] = of classes 0 and 1
-    const int4 *chunk_desc;      // per column of the batch, by size class: {column, first entry, end entry, class}
+    const int4 *chunk_desc;      // per column of the batch (per part of a very long one), by size class: {column, first entry, end entry, parts of the column}
     const int2 *csc_ent;         // the batch's non-zeros by column: {row, value bits}
     const float *delta;          // B x ldd
     int ldd;
@@ -279,6 +279,7 @@ struct SparseDwArgs {
 // Needs csc_supported(d0, max_B):
 // the column histogram of one block and its slice of row_ptr live in LDS.
 bool csc_supported(int d0, long long max_B);
+size_t sparse_desc_capacity(int d0, long long nnz_cap);  // descriptors of a batch of at most nnz_cap non-zeros
 size_t csc_hist_elems(long long max_B, int d0);
 size_t csc_cnt_elems(int d0);
 hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, const float *vals,

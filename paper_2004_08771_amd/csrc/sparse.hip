@@ -40,7 +40,11 @@ __host__ __device__ inline int chunk_class(int cnt)
     if (cnt <= CHUNK) return N_LIGHT + (cnt + 15) / 16 - 2;
     return N_CLASS - 1;
 }
-__host__ __device__ inline int chunks_of(int cnt) { return cnt > 0 ? 1 : 0; }
+// A column of more than SPLIT entries gets several descriptors, one per part of about equal
+// length (whole gather windows), so that its parts run on different compute units.
+constexpr int SPLIT = 1024;
+__host__ __device__ inline int chunks_of(int cnt) { return cnt <= 0 ? 0 : (cnt + SPLIT - 1) / SPLIT; }
+__host__ __device__ inline int part_len(int cnt, int parts) { return (((cnt + parts - 1) / parts) + 15) & ~15; }
 
 constexpr int SPMM_CAP = 512;  // entries of a row staged in LDS at a time (forward product)
 
@@ -265,11 +269,13 @@ __global__ __launch_bounds__(COLG) void csc_colsum_kernel(int32_t *__restrict__ 
 // Exclusive scan of cnt[0..n) (-> col_start) and the position of every column's descriptor
 // (-> chunk_start; [n] = number of descriptors, [n + 1] = those of at most LIGHT_MAX entries,
 // [n + 2] = of at most CHUNK entries): the columns of size class 0 come first, in column
-// order, then class 1, and so on.  One descriptor per column that occurs in the batch {column, first entry, end
-// entry, class} lets the gradient kernel find its work with one load.
+// order, then class 1, and so on.  One descriptor {column, first entry, end entry, parts of the
+// column} per column that occurs in the batch (per part of a column of more than SPLIT entries)
+// lets the gradient kernel find its work with one load.
 // One workgroup per group of 256 columns: it adds up the totals of the groups before it (and the
 // class totals of ALL groups), scans its own columns with shuffles, and writes its outputs
-// coalesced.
+// coalesced.  A column with several parts goes on an LDS list and the whole workgroup writes
+// its descriptors.
 // (A single-workgroup scan of all 21k columns took 20-60 us in three different forms: one
 // CU's shuffle latency and store issue rate bound it.)
 __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restrict__ cnt,
@@ -279,6 +285,8 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
                                                         int4 *__restrict__ chunk_desc)
 {
     __shared__ int red[4 * (1 + N_CLASS)], w_a[4], w_c[4][N_CLASS];
+    __shared__ int n_heavy;
+    __shared__ int4 heavy[COLG];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int g = blockIdx.x, n_groups = gridDim.x;
     const int c = g * COLG + t;
@@ -294,7 +302,8 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
             all[k] += x;
         }
     }
-    group_sum(before, red);
+    if (t == 0) n_heavy = 0;
+    group_sum(before, red);  // its barrier also publishes n_heavy
     __syncthreads();         // red is reused
     group_sum(all, red);
     const int cls = chunk_class(v), ch = chunks_of(v);
@@ -336,7 +345,16 @@ __global__ __launch_bounds__(COLG) void col_scan_kernel(const int32_t *__restric
             chunk_start[n + 1] = light;
             chunk_start[n + 2] = light + mid;
         }
-        if (v > 0) chunk_desc[first_ch] = make_int4(c, first_e, first_e + v, cls);
+        if (ch == 1) chunk_desc[first_ch] = make_int4(c, first_e, first_e + v, 1);
+        else if (ch > 1) heavy[atomicAdd(&n_heavy, 1)] = make_int4(c, first_e, v, first_ch);
+    }
+    __syncthreads();
+    const int nh = n_heavy;  // the whole workgroup writes the descriptors of a column's parts
+    for (int k = 0; k < nh; ++k) {
+        const int4 h = heavy[k];  // {column, first entry, entries, first descriptor}
+        const int parts = chunks_of(h.z), len = part_len(h.z, parts);
+        for (int q = t; q < parts; q += COLG)
+            chunk_desc[h.w + q] = make_int4(h.x, min(h.y + h.z, h.y + q * len), min(h.y + h.z, h.y + (q + 1) * len), parts);
     }
 }
 
@@ -395,9 +413,9 @@ __global__ __launch_bounds__(CSC_NT) void csc_place_kernel(const int32_t *__rest
 // One workgroup per column that occurs in the batch:
 //   g[:] = sum_e val[e] * delta_1[row[e], :]   over the column's entries {row, val} of csc_ent
 // then W1t[c,:] -= lr * g, or in gradient mode dW_1[:, c] = g in the flat out x in layout.
-// A column of more than CHUNK entries (the last class) is cut into up to FB_PARTS parts: its
-// descriptor's workgroup takes the first, and the FB_EXTRA workgroups behind the descriptors
-// walk over the other parts of all such columns; their sums meet through fp32 atomic adds.
+// A descriptor of more than CHUNK entries (the last class) is cut into up to FB_PARTS parts: its
+// workgroup takes the first, and the FB_EXTRA workgroups behind the descriptors walk over the
+// other parts of all such descriptors; the sums of a column's parts meet through fp32 atomic adds.
 constexpr int FB_PARTS = 32, FB_EXTRA = 2048;
 __device__ __forceinline__ int fb_part_len(int cnt)
 {
@@ -489,7 +507,7 @@ __global__ __launch_bounds__(SP_NT) void sparse_dw_kernel(SparseDwArgs a, int ma
         if ((int)blockIdx.x >= n_desc) return;
         const int4 desc = a.chunk_desc[blockIdx.x];
         const int per = fb_part_len(desc.z - desc.y);
-        sparse_dw_part(a, desc.x, desc.y, min(desc.z, desc.y + per), desc.z - desc.y <= per);
+        sparse_dw_part(a, desc.x, desc.y, min(desc.z, desc.y + per), desc.w == 1 && desc.z - desc.y <= per);
         return;
     }
     const int n_work = (n_desc - n01) * (FB_PARTS - 1);
@@ -647,15 +665,32 @@ __device__ __forceinline__ void apply_column_sum(const SparseDwArgs &a, int c, i
     }
 }
 
+// the same for one of several parts of a column, whose sums meet through fp32 atomic adds
+__device__ __forceinline__ void apply_part_sum(const SparseDwArgs &a, int c, int col0, float4 g)
+{
+    if (a.grad_out) {
+        float *o = a.grad_out + (size_t)col0 * a.d0 + c;
+        atomicAdd(o, g.x); atomicAdd(o + a.d0, g.y);
+        atomicAdd(o + 2 * (size_t)a.d0, g.z); atomicAdd(o + 3 * (size_t)a.d0, g.w);
+    } else {
+        float *w = a.W1t + (size_t)c * a.ldw + col0;
+        atomicAdd(w, -a.lr * g.x); atomicAdd(w + 1, -a.lr * g.y);
+        atomicAdd(w + 2, -a.lr * g.z); atomicAdd(w + 3, -a.lr * g.w);
+    }
+}
+
 // g[slice] = sum_e val[e] * delta_1[row[e], slice] over one column's entries, then the update of
 // W1t[c, slice] (or the gradient output).  unit = one workgroup = 16 groups of 16 lanes.
 // The first LONG_UNITS units walk over the columns of more than CHUNK entries (the
 // head of a skewed distribution holds half of all entries in a few hundred columns): the 16
 // groups share one column's entries in contiguous runs of whole gather windows, their sums
-// meet in LDS and are added in group order, and the first group updates the row -- no atomics,
-// and the same sum on every run for a given order of the entries (with one fp32 atomic add
-// per 128-entry chunk instead, the kernel took 65.8 us on the real-sim shape; a plain, racing
-// read-modify-write in their place, to price them: 52.7).
+// meet in LDS and are added in group order, and the first group updates the row (with one fp32
+// atomic add per 128-entry chunk instead, the kernel took 65.8 us on the real-sim shape; a
+// plain, racing read-modify-write in their place, to price them: 52.7).  Such a workgroup is
+// bound by what ONE compute unit gathers -- the hottest column of that batch, 8,100 entries,
+// took 43 us, as long as the rest of the kernel -- so a column of more than SPLIT entries
+// comes as several descriptors whose workgroups add their sums with fp32 atomic adds (a few
+// dozen columns, about a hundred parts).
 // Then the columns of at most LIGHT_MAX entries (most of them one to three): a group takes
 // LP of them at once and issues every step of their chains (descriptors, indices, gathers
 // LR per column and round, weight rows) for all LP together -- one such column alone is five
@@ -689,7 +724,8 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
                     const float4 p = part[k][l];
                     sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
                 }
-                apply_column_sum(a, desc.x, col0, sum);
+                if (desc.w == 1) apply_column_sum(a, desc.x, col0, sum);
+                else apply_part_sum(a, desc.x, col0, sum);
             }
             __syncthreads();  // part is reused
         }
@@ -838,6 +874,8 @@ hipError_t launch_spmm_fwd(const SpmmArgs &a, long long B, hipStream_t stream, c
     return launch_kernel(spmm_fwd_kernel, dim3((unsigned)B), dim3(SP_NT), stream, ev, a);
 }
 
+size_t sparse_desc_capacity(int d0, long long nnz_cap) { return (size_t)d0 + 1 + (size_t)(nnz_cap / SPLIT); }
+
 int csc_blocks(long long B)
 {
     long long nb = (B + 127) / 128;  // at least 128 rows per block
@@ -917,13 +955,14 @@ hipError_t launch_csc_build(const int32_t *row_ptr, const int32_t *col_idx, cons
 
 hipError_t launch_sparse_dw(const SparseDwArgs &a, long long nnz, hipStream_t stream, const LaunchEvents &ev)
 {
-    const long long max_cols = nnz < a.d0 ? nnz : a.d0;  // distinct columns of the batch
-    if (max_cols <= 0) return hipSuccess;
+    // descriptors: one per distinct column of the batch + the extra parts of the very long ones
+    const long long max_cols = (nnz < a.d0 ? nnz : a.d0) + nnz / SPLIT;
+    if (nnz <= 0) return hipSuccess;
     SliceMap m;
     if (slice_map(a.d1, a.vec, &m)) {
-        // one unit per long column while there are at most LONG_UNITS of them, then
+        // one unit per long descriptor while there are at most LONG_UNITS of them, then
         // ceil(light / (16 LP)) + ceil(others / 16) units
-        const long long max_long = nnz / (CHUNK + 1);
+        const long long max_long = nnz / (CHUNK + 1) + nnz / SPLIT;
         const int lu = (int)(max_long < 1 ? 1 : (max_long < LONG_UNITS ? max_long : LONG_UNITS));
         const long long units = lu + (max_cols + 15) / 16 + 2;
         const long long blocks = sliced_blocks(m, units);
