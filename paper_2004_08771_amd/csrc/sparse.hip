@@ -681,7 +681,7 @@ __device__ __forceinline__ void apply_part_sum(const SparseDwArgs &a, int c, int
 
 // g[slice] = sum_e val[e] * delta_1[row[e], slice] over one column's entries, then the update of
 // W1t[c, slice] (or the gradient output).  unit = one workgroup = 16 groups of 16 lanes.
-// The first LONG_UNITS units walk over the columns of more than CHUNK entries (the
+// First come the descriptors of more than CHUNK entries, a unit each (the
 // head of a skewed distribution holds half of all entries in a few hundred columns): the 16
 // groups share one column's entries in contiguous runs of whole gather windows, their sums
 // meet in LDS and are added in group order, and the first group updates the row (with one fp32
@@ -691,15 +691,16 @@ __device__ __forceinline__ void apply_part_sum(const SparseDwArgs &a, int c, int
 // took 43 us, as long as the rest of the kernel -- so a column of more than SPLIT entries
 // comes as several descriptors whose workgroups add their sums with fp32 atomic adds (a few
 // dozen columns, about a hundred parts).
-// Then the columns of at most LIGHT_MAX entries (most of them one to three): a group takes
+// Last the columns of at most LIGHT_MAX entries (most of them one to three): a group takes
 // LP of them at once and issues every step of their chains (descriptors, indices, gathers
 // LR per column and round, weight rows) for all LP together -- one such column alone is five
-// dependent round trips with nothing to overlap them but other groups.  Then the rest, one
-// column per group.
+// dependent round trips with nothing to overlap them but other groups.  Between the two, the
+// columns of 2 .. 8 gather windows, one per group.  Within each class range the units run from
+// the largest columns down, so that the launch ends on its shortest work.
 // (Requesting the descriptor together with the descriptor count, and the weight row of a
 // class-1 column before the gathers instead of after them, was slower: 70 -> 76 us.)
-constexpr int LP = 4, LR = 2, LONG_UNITS = 512;
-__global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a, SliceMap m, int units, int long_units)
+constexpr int LP = 4, LR = 2, DW_UNITS = 1024;
+__global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a, SliceMap m, int units)
 {
     int slice, unit;
     slice_of_block(m, blockIdx.x, slice, unit);
@@ -707,10 +708,15 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
     const int g16 = threadIdx.x >> 4, l = threadIdx.x & 15;
     const int n_desc = a.chunk_start[a.d0], n_light = a.chunk_start[a.d0 + 1], n01 = a.chunk_start[a.d0 + 2];
     const int col0 = slice * SL + 4 * l;
-    if (unit < long_units) {
-        __shared__ float4 part[16][16];
-        for (int j = n01 + unit; j < n_desc; j += long_units) {
-            const int4 desc = a.chunk_desc[j];
+    const int long_units = n_desc - n01, mid_units = (n01 - n_light + 15) / 16;
+    const int light_units = (n_light + 16 * LP - 1) / (16 * LP);
+    const int need = long_units + mid_units + light_units;
+    __shared__ float4 part[16][16];
+    // the launch has a fixed number of units (how many the batch needs is only known here):
+    // a unit takes every `units`-th piece of work, long descriptors first
+    for (int vu = unit; vu < need; vu += units) {
+        if (vu < long_units) {
+            const int4 desc = a.chunk_desc[n01 + vu];
             const int per = (((desc.z - desc.y + 15) >> 4) + 15) & ~15;  // entries per group: whole windows
             const int beg = min(desc.z, desc.y + g16 * per);
             float4 g = {0.f, 0.f, 0.f, 0.f};
@@ -728,14 +734,20 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
                 else apply_part_sum(a, desc.x, col0, sum);
             }
             __syncthreads();  // part is reused
+            continue;
         }
-        return;
-    }
-    unit -= long_units;
-    const int light_units = (n_light + 16 * LP - 1) / (16 * LP);
-    if (unit < light_units) {
-        const int first = (unit * 16 + g16) * LP;
-        if (first >= n_light) return;
+        // the columns of 2 .. 8 windows next, longest first, so that the kernel ends on short work
+        if (vu < long_units + mid_units) {
+            const int j = n_light + (mid_units - 1 - (vu - long_units)) * 16 + g16;
+            if (j >= n01) continue;
+            const int4 desc = a.chunk_desc[j];
+            float4 g = {0.f, 0.f, 0.f, 0.f};
+            g = group_gather_sum(g, CscEntries{a.csc_ent}, desc.y, desc.z, a.delta + col0, (size_t)a.ldd, l);
+            apply_column_sum(a, desc.x, col0, g);
+            continue;
+        }
+        const int first = ((need - 1 - vu) * 16 + g16) * LP;  // also from the largest down
+        if (first >= n_light) continue;
         int c[LP], n[LP], my_i[LP];
         float my_v[LP];
         // lane k of the group fetches descriptor k; the others get it by shuffle
@@ -785,14 +797,7 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
                 if (first + k < n_light) *reinterpret_cast<float4 *>(a.W1t + (size_t)c[k] * a.ldw + col0) = x[k];
             }
         }
-        return;
     }
-    const int j = n_light + (unit - light_units) * 16 + g16;
-    if (j >= n01) return;
-    const int4 desc = a.chunk_desc[j];
-    float4 g = {0.f, 0.f, 0.f, 0.f};
-    g = group_gather_sum(g, CscEntries{a.csc_ent}, desc.y, desc.z, a.delta + col0, (size_t)a.ldd, l);
-    apply_column_sum(a, desc.x, col0, g);
 }
 
 // partial[s][j] = sum over the s-th slice of rows of delta[i][j]   (bias gradient of layer 1)
@@ -960,15 +965,19 @@ hipError_t launch_sparse_dw(const SparseDwArgs &a, long long nnz, hipStream_t st
     if (nnz <= 0) return hipSuccess;
     SliceMap m;
     if (slice_map(a.d1, a.vec, &m)) {
-        // one unit per long descriptor while there are at most LONG_UNITS of them, then
-        // ceil(light / (16 LP)) + ceil(others / 16) units
+        // what the batch can need at most -- a unit per long descriptor, ceil(light / (16 LP)) +
+        // ceil(others / 16) for the rest -- but no more than DW_UNITS: the kernel walks over
+        // its work with that stride, and workgroups that find none cost a dispatch each (7,600
+        // of them behind the real-sim batch's 7,100: 1.8 us)
         const long long max_long = nnz / (CHUNK + 1) + nnz / SPLIT;
-        const int lu = (int)(max_long < 1 ? 1 : (max_long < LONG_UNITS ? max_long : LONG_UNITS));
-        const long long units = lu + (max_cols + 15) / 16 + 2;
+        long long units = max_long + (max_cols + 15) / 16 + 2;
+        const char *cap_env = getenv("HB_DW_UNITS");  // tuning and test aid; read per call
+        const long long cap = cap_env && atoi(cap_env) > 0 ? atoi(cap_env) : DW_UNITS;
+        if (units > cap) units = cap;
         const long long blocks = sliced_blocks(m, units);
         if (blocks <= 0x7fffffffLL)
             return launch_kernel(sparse_dw_sliced_kernel, dim3((unsigned)blocks), dim3(XS_NT), stream, ev, a, m,
-                                 (int)units, lu);
+                                 (int)units);
     }
     return launch_kernel(sparse_dw_kernel, dim3((unsigned)(max_cols + FB_EXTRA)), dim3(SP_NT), stream, ev, a,
                          (int)max_cols);

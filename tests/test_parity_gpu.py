@@ -657,6 +657,18 @@ def test_csr_more_long_columns_than_workgroups_set_aside_for_them(d1):
     check_csr_case(dims, hi.ACT_SIGMOID, hi.LOSS_LOGISTIC, params, rp, ci, va, y, lr=0.1)
 
 
+def test_csr_weight_gradient_with_fewer_workgroups_than_pieces_of_work(monkeypatch):
+    """The sliced weight-gradient kernel is launched with a bounded number of units and walks over
+    its work with that stride; three units per slice make every unit take many pieces of each kind
+    (long columns with their barriers first, then the others)."""
+    monkeypatch.setenv("HB_DW_UNITS", "3")
+    dims = (3000, 64, 2)
+    params, rp, ci, va, y = _csr_problem(dims, 1200, seed=515, mean_nnz=40)
+    counts = np.bincount(ci, minlength=dims[0])
+    assert (counts > 1024).sum() >= 1 and (counts > 128).sum() >= 8 and ((counts > 16) & (counts <= 128)).sum() >= 100
+    check_csr_case(dims, hi.ACT_SIGMOID, hi.LOSS_LOGISTIC, params, rp, ci, va, y, lr=0.1)
+
+
 @pytest.mark.parametrize("seed", [11, 12])
 def test_random_csr_shapes_match_oracle(seed):
     """Seeded sweep over CSR batches: input widths from 10 to 30,000 columns, 1 to 50 stored entries
