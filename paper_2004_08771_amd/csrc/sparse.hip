@@ -768,7 +768,8 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
 #pragma unroll
         for (int k = 0; k < LP; ++k) g[k] = make_float4(0.f, 0.f, 0.f, 0.f);
         const float *src = a.delta + col0;
-        for (int u0 = 0; u0 < n_max; u0 += LR) {
+        int u0 = 0;
+        for (; u0 + LR <= n_max; u0 += LR) {
             float4 w[LP][LR];
 #pragma unroll
             for (int k = 0; k < LP; ++k)
@@ -782,6 +783,17 @@ __global__ __launch_bounds__(XS_NT) void sparse_dw_sliced_kernel(SparseDwArgs a,
                     const float v = __shfl(my_v[k], u0 + u, 16);
                     g[k].x += v * w[k][u].x; g[k].y += v * w[k][u].y; g[k].z += v * w[k][u].z; g[k].w += v * w[k][u].w;
                 }
+        }
+        if (u0 < n_max) {  // an odd number of entries (the four columns mostly have the same): one gather each
+            float4 w[LP];
+#pragma unroll
+            for (int k = 0; k < LP; ++k)
+                w[k] = *reinterpret_cast<const float4 *>(src + (size_t)__shfl(my_i[k], u0, 16) * a.ldd);
+#pragma unroll
+            for (int k = 0; k < LP; ++k) {
+                const float v = __shfl(my_v[k], u0, 16);
+                g[k].x += v * w[k].x; g[k].y += v * w[k].y; g[k].z += v * w[k].z; g[k].w += v * w[k].w;
+            }
         }
         if (a.grad_out) {
 #pragma unroll
